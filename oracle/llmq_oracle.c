@@ -1,0 +1,244 @@
+/*
+ * CPU oracle for the FP8 linear-layer path of LLMQ's 8-bit training pipeline.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * GPU library is checked against.  It shares no code with the GPU library and
+ * must never be called from the product path; only the test-suite, the smoke
+ * check and the benchmark's cpu_baseline leg load it.
+ *
+ * What it follows (paper sections):
+ *   - Section 3, "Overview": just-in-time tensor-level absmax scaling -- find
+ *     the largest absolute value of the tensor, rescale so that it lands on
+ *     the largest representable FP8 value (no clipping), convert BF16 -> FP8;
+ *     the main transformer matmuls (forward and backward) run in FP8, their
+ *     results stay in BF16.
+ *   - Section 2: the two FP8 types E4M3 and E5M2 (OCP 8-bit floating point
+ *     formats, the specification the paper cites for FP8).
+ *   - Section 3, paragraph on kernel fusion: FP8 GEMM is TN-only, so the
+ *     transposed copies are produced by a fused transpose+quantize step.
+ *
+ * Readings where the paper is silent (listed in the design notes as well):
+ *   scale  s = fl32(FMAX / amax), one binary32 division; amax == 0 -> s = 1;
+ *          a quotient that overflows binary32 is clamped to FLT_MAX;
+ *   value  p = fl32(fl32(x) * s), one binary32 multiplication, not fused;
+ *   cast   round-to-nearest-even onto the FP8 grid, saturating to +-FMAX
+ *          (never produces an Inf or NaN code from a finite p); NaN -> S.1111111;
+ *   amax   of a tensor holding a NaN is the canonical quiet NaN (0x7FC00000),
+ *          otherwise max |x| (which is +Inf if an Inf is present);
+ *   GEMM   fp64 accumulation of exact products of the decoded FP8 values,
+ *          divided by (double)sA * (double)sB.
+ *
+ * Parity status: every function below is pinned by tests/test_oracle_*.py
+ * (closed forms of the formats, an independent library cast, brute force on
+ * small integer inputs, algebraic invariants).
+ */
+#include <float.h>
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+#define ORACLE_E4M3 0
+#define ORACLE_E5M2 1
+
+/* ---- format constants (OCP FP8) ----------------------------------------- */
+
+static int fmt_mbits(int fmt) { return fmt == ORACLE_E4M3 ? 3 : 2; }
+static int fmt_bias(int fmt) { return fmt == ORACLE_E4M3 ? 7 : 15; }
+
+/* Largest finite magnitude: E4M3 S.1111.110 = 1.75 * 2^8, E5M2 S.11110.11 = 1.75 * 2^15. */
+double oracle_fp8_max(int fmt) { return fmt == ORACLE_E4M3 ? 448.0 : 57344.0; }
+
+/* ---- BF16 ------------------------------------------------------------------ */
+
+/* A BF16 number is the upper half of the binary32 with the same value. */
+float oracle_bf16_to_f32(uint16_t b) {
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return f;
+}
+
+/* binary64 -> BF16 with round-to-nearest-even (used by tests to form expected
+ * outputs; overflow goes to Inf as IEEE rounding prescribes). */
+uint16_t oracle_f64_to_bf16(double v) {
+    if (isnan(v)) return 0x7FC0;
+    uint16_t sign = signbit(v) ? 0x8000 : 0;
+    double a = fabs(v);
+    if (a == 0.0) return sign;
+    if (isinf(a)) return sign | 0x7F80;
+    int ex;
+    frexp(a, &ex);               /* a = m * 2^ex, m in [0.5, 1) */
+    int e = ex - 1;              /* a in [2^e, 2^(e+1)) */
+    if (e < -126) e = -126;      /* subnormal range shares the quantum of e = -126 */
+    double u = ldexp(1.0, e - 7);
+    double t = a / u;            /* exact: division by a power of two */
+    double f = floor(t), d = t - f;
+    if (d > 0.5 || (d == 0.5 && fmod(f, 2.0) == 1.0)) f += 1.0;
+    if (f >= 256.0) { f = 128.0; e += 1; }
+    if (e > 127) return sign | 0x7F80;
+    uint32_t n = (uint32_t)f;
+    if (n < 128) return sign | (uint16_t)n;              /* subnormal, exponent field 0 */
+    return sign | (uint16_t)(((e + 127) << 7) | (n - 128));
+}
+
+/* ---- FP8 decode: the closed form of the format ------------------------------ */
+
+double oracle_fp8_decode(uint8_t code, int fmt) {
+    const int m = fmt_mbits(fmt), bias = fmt_bias(fmt);
+    const int sign = code >> 7;
+    const int E = (code & 0x7F) >> m;
+    const int M = code & ((1 << m) - 1);
+    double v;
+    if (fmt == ORACLE_E4M3) {
+        if (E == 15 && M == 7) return NAN;               /* only NaN, no infinities */
+    } else {
+        if (E == 31) {
+            if (M == 0) return sign ? -INFINITY : INFINITY;
+            return NAN;
+        }
+    }
+    if (E == 0)
+        v = ldexp((double)M / (double)(1 << m), 1 - bias);          /* subnormal */
+    else
+        v = ldexp(1.0 + (double)M / (double)(1 << m), E - bias);    /* normal */
+    return sign ? -v : v;
+}
+
+/* ---- FP8 encode: saturating round-to-nearest-even ---------------------------- */
+
+uint8_t oracle_fp8_encode(float p, int fmt) {
+    const int m = fmt_mbits(fmt), bias = fmt_bias(fmt);
+    const int emin = 1 - bias;
+    const uint8_t sign = signbit(p) ? 0x80 : 0x00;
+    if (isnan(p)) return sign | 0x7F;
+    const double a = fabs((double)p);
+    const double fmax = oracle_fp8_max(fmt);
+    if (a > fmax) return sign | (fmt == ORACLE_E4M3 ? 0x7E : 0x7B);   /* saturate, +-Inf too */
+    if (a == 0.0) return sign;
+    int ex;
+    frexp(a, &ex);
+    int e = ex - 1;                       /* a in [2^e, 2^(e+1)) */
+    if (e < emin) e = emin;               /* below the smallest normal the quantum is fixed */
+    const double u = ldexp(1.0, e - m);   /* spacing of the grid in this binade */
+    const double t = a / u;               /* exact */
+    double f = floor(t);
+    const double d = t - f;
+    if (d > 0.5 || (d == 0.5 && fmod(f, 2.0) == 1.0)) f += 1.0;   /* ties to even */
+    int n = (int)f;                       /* 0 .. 2^(m+1) */
+    if (n == (2 << m)) { n = 1 << m; e += 1; }                    /* carried into next binade */
+    if (n < (1 << m)) return sign | (uint8_t)n;                   /* zero or subnormal */
+    return sign | (uint8_t)(((e + bias) << m) | (n - (1 << m)));
+}
+
+/* Element-wise application of the encoder to an array (no other arithmetic). */
+void oracle_fp8_encode_array(const float* p, size_t n, int fmt, uint8_t* out) {
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; ++i) out[i] = oracle_fp8_encode(p[i], fmt);
+}
+
+/* ---- absmax and scale --------------------------------------------------------- */
+
+float oracle_amax_bf16(const uint16_t* x, size_t n) {
+    float a = 0.0f;
+    int saw_nan = 0;
+#pragma omp parallel for reduction(max : a) reduction(| : saw_nan) schedule(static)
+    for (size_t i = 0; i < n; ++i) {
+        float v = fabsf(oracle_bf16_to_f32(x[i]));
+        if (isnan(v)) saw_nan = 1;
+        else if (v > a) a = v;
+    }
+    if (saw_nan) {
+        uint32_t q = 0x7FC00000u;
+        memcpy(&a, &q, sizeof a);
+    }
+    return a;
+}
+
+float oracle_scale(float amax, int fmt) {
+    if (amax == 0.0f) return 1.0f;
+    volatile float num = (float)oracle_fp8_max(fmt);
+    volatile float den = amax;
+    volatile float s = num / den;          /* one binary32 division */
+    if (isinf(s)) s = FLT_MAX;
+    return s;
+}
+
+/* ---- quantize (+ transposed copy) --------------------------------------------- */
+
+/* q[i*cols + j] = cast(fl32(x[i,j] * scale)); qt[j*rows + i] = q[i*cols + j]; qt may be NULL. */
+void oracle_quantize(const uint16_t* x, int64_t rows, int64_t cols, float scale, int fmt,
+                     uint8_t* q, uint8_t* qt) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        for (int64_t j = 0; j < cols; ++j) {
+            volatile float p = oracle_bf16_to_f32(x[i * cols + j]) * scale;   /* rounded to binary32 */
+            uint8_t c = oracle_fp8_encode(p, fmt);
+            q[i * cols + j] = c;
+            if (qt) qt[j * rows + i] = c;
+        }
+    }
+}
+
+/* ---- the contraction shared by forward, dgrad and wgrad ----------------------- */
+
+/*
+ * y[r,c] = ( sum_t dec(A[r,t]) * dec(B[c,t]) ) / (sA*sB),   S[r,c] = ( sum_t |dec(A)*dec(B)| ) / (sA*sB)
+ * A is [R,T], B is [C,T], both row-major with the contraction index contiguous.
+ *   forward: A = Xq  [M,K],  B = Wq  [N,K]   ->  Y  [M,N]
+ *   dgrad  : A = dYq [M,N],  B = Wq^T [K,N]  ->  dX [M,K]
+ *   wgrad  : A = dYq^T [N,M], B = Xq^T [K,M] ->  dW [N,K]
+ * S is the quantity the GEMM tolerance is stated in.  Either output may be NULL.
+ */
+static void dot_tn(const uint8_t* a, const double* da, const uint8_t* b, const double* db,
+                   int64_t T, double den, double* y, double* S) {
+    double acc = 0.0, mag = 0.0;
+    for (int64_t t = 0; t < T; ++t) {
+        double prod = da[a[t]] * db[b[t]];   /* exact in binary64 */
+        acc += prod;
+        mag += fabs(prod);
+    }
+    if (y) *y = acc / den;
+    if (S) *S = mag / den;
+}
+
+static void decode_table(int fmt, double* tab) {
+    for (int c = 0; c < 256; ++c) tab[c] = oracle_fp8_decode((uint8_t)c, fmt);
+}
+
+void oracle_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB,
+                    int64_t R, int64_t C, int64_t T, float sA, float sB,
+                    double* y, double* S) {
+    double da[256], db[256];
+    decode_table(fmtA, da);
+    decode_table(fmtB, db);
+    const double den = (double)sA * (double)sB;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < R; ++r)
+        for (int64_t c = 0; c < C; ++c)
+            dot_tn(A + r * T, da, B + c * T, db, T, den,
+                   y ? y + r * C + c : NULL, S ? S + r * C + c : NULL);
+}
+
+/* Same contraction for a list of (row, col) output positions only. */
+void oracle_gemm_tn_sampled(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB,
+                            int64_t R, int64_t C, int64_t T, float sA, float sB,
+                            const int64_t* rr, const int64_t* cc, int64_t n,
+                            double* y, double* S) {
+    (void)R; (void)C;
+    double da[256], db[256];
+    decode_table(fmtA, da);
+    decode_table(fmtB, db);
+    const double den = (double)sA * (double)sB;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i)
+        dot_tn(A + rr[i] * T, da, B + cc[i] * T, db, T, den, y ? y + i : NULL, S ? S + i : NULL);
+}
+
+/* Threads the OpenMP loops above will use (reported by the benchmark). */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_num_threads(void) { return 1; }
+#endif
