@@ -1,0 +1,206 @@
+"""Benchmark of the FP8 linear path on one MI355X.
+
+A step is one pass of the whole path over one block's linears (QKV, attention-out, gate/up, down):
+per linear  absmax+scale of X and W, quantize+transpose both, forward GEMM (with fused output absmax),
+absmax+scale of dY, quantize+transpose, dgrad GEMM, wgrad GEMM.  Inputs are resident in HBM.
+
+Prints ONE JSON line: whole-step TFLOP/s (6*M*K*N summed over the linears / step time), the roofline
+of the dominant kernel (the FP8 MFMA GEMM, timed live with events on the launch stream) and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP8_TFLOPS = 5000.0      # MI355X dense FP8 MFMA, published
+PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E, published
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=20)
+    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--config", type=int, default=2, help="BASELINE config index (2 = 3B-class block ... 5 = 32B-class)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--prequantized-w", action="store_true",
+                   help="weights quantized once outside the timed region (reused across micro-steps)")
+    return p.parse_args()
+
+
+class LinearState:
+    def __init__(self, cfg, li, dev):
+        import torch
+        from paper_2512_15306_amd import llmq, synth
+        lin = cfg.linears[li]
+        self.name, self.M, self.K, self.N = lin.name, cfg.M, lin.K, lin.N
+        M, K, N = self.M, self.K, self.N
+        self.X = synth.make_x(cfg, li, device=dev)
+        self.W = synth.make_w(cfg, li, device=dev)
+        self.dY = synth.make_dy(cfg, li, device=dev)
+        self.ws = torch.empty(llmq.llmq_fp8_linear_workspace_bytes(M, N, K), dtype=torch.uint8, device=dev)
+        self.offs = llmq.llmq_fp8_linear_workspace_offsets(M, N, K)
+        self.Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        self.dX = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+        self.dW = torch.empty((N, K), dtype=torch.bfloat16, device=dev)
+        self.f = torch.zeros(8, dtype=torch.float32, device=dev)   # amax/scale of X, W, dY; amax of Y, dX
+        f = self.f
+        self.ax, self.sx, self.aw, self.sw, self.ad, self.sd, self.ay, self.adx = (f[i:i + 1] for i in range(8))
+
+    def view(self, which):
+        M, K, N = self.M, self.K, self.N
+        shape = {0: (M, K), 1: (K, M), 2: (N, K), 3: (K, N), 4: (M, N), 5: (N, M)}[which]
+        o = self.offs[which]
+        return self.ws[o:o + shape[0] * shape[1]].view(shape)
+
+
+def run_step(states, prequantized_w):
+    from paper_2512_15306_amd import llmq
+    for s in states:
+        M, K, N = s.M, s.K, s.N
+        llmq.llmq_amax(s.X, llmq.E4M3, s.ax, s.sx)
+        if not prequantized_w:
+            llmq.llmq_amax(s.W, llmq.E4M3, s.aw, s.sw)
+        llmq.llmq_fp8_linear_fwd(s.X, s.W, M, N, K, s.sx, s.sw, s.Y, s.ay, s.ws,
+                                 llmq.REUSE_W if prequantized_w else 0)
+        llmq.llmq_amax(s.dY, llmq.E5M2, s.ad, s.sd)
+        llmq.llmq_fp8_linear_dgrad(s.dY, None, M, N, K, s.sd, s.sw, llmq.E5M2, s.dX, s.adx, s.ws, llmq.REUSE_W)
+        llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, s.sd, s.sx, llmq.E5M2, s.dW, False, s.ws,
+                                   llmq.REUSE_X | llmq.REUSE_DY)
+
+
+def run_gemms_only(states):
+    from paper_2512_15306_amd import llmq
+    for s in states:
+        llmq.llmq_fp8_gemm_tn(s.view(0), 0, s.view(2), 0, s.sx, s.sw, s.Y, False, s.ay)
+        llmq.llmq_fp8_gemm_tn(s.view(4), 1, s.view(3), 0, s.sd, s.sw, s.dX, False, s.adx)
+        llmq.llmq_fp8_gemm_tn(s.view(5), 1, s.view(1), 0, s.sd, s.sx, s.dW, False, None)
+
+
+def run_quant_only(states):
+    from paper_2512_15306_amd import llmq
+    for s in states:
+        llmq.llmq_amax(s.X, 0, s.ax, s.sx)
+        llmq.llmq_quantize_fp8(s.X, s.sx, 0, s.view(0), s.view(1))
+        llmq.llmq_amax(s.W, 0, s.aw, s.sw)
+        llmq.llmq_quantize_fp8(s.W, s.sw, 0, s.view(2), s.view(3))
+        llmq.llmq_amax(s.dY, 1, s.ad, s.sd)
+        llmq.llmq_quantize_fp8(s.dY, s.sd, 1, s.view(4), s.view(5))
+
+
+def timed(fn, reps):
+    """Average milliseconds per call of fn over reps calls, by events on the current stream."""
+    import torch
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def cpu_baseline(cfg):
+    """The oracle as it stands on a bounded sample: the 'o' projection (second linear) restricted to
+    the first rows of the token dimension, whole path (3 absmax, 3 quantize+transpose, 3 fp64 GEMMs)."""
+    import oracle
+    from paper_2512_15306_amd import synth
+    li = 1 if len(cfg.linears) > 1 else 0
+    lin = cfg.linears[li]
+    Ms = min(cfg.M, max(64, int(2048 * (3072 * 3072) / (lin.K * lin.N))))
+    x = synth.bf16_bits(synth.make_x(cfg, li, M=Ms))
+    w = synth.bf16_bits(synth.make_w(cfg, li))
+    dy = synth.bf16_bits(synth.make_dy(cfg, li, M=Ms))
+    oracle.amax_bf16(x[:8])            # load the library outside the timed region
+    t0 = time.perf_counter()
+    sx = oracle.scale(oracle.amax_bf16(x), 0)
+    sw = oracle.scale(oracle.amax_bf16(w), 0)
+    sd = oracle.scale(oracle.amax_bf16(dy), 1)
+    xq, xqt = oracle.quantize(x, sx, 0)
+    wq, wqt = oracle.quantize(w, sw, 0)
+    dq, dqt = oracle.quantize(dy, sd, 1)
+    oracle.gemm_tn(xq, 0, wq, 0, sx, sw)
+    oracle.gemm_tn(dq, 1, wqt, 0, sd, sw)
+    oracle.gemm_tn(dqt, 1, xqt, 0, sd, sx)
+    dt = time.perf_counter() - t0
+    flops = 6.0 * Ms * lin.K * lin.N
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "seconds": round(dt, 2),
+            "sample": "config %d '%s' linear (K=%d, N=%d) on the first %d of %d tokens: absmax, "
+                      "quantize+transpose and fp64 fwd/dgrad/wgrad" % (cfg.index, lin.name, lin.K, lin.N, Ms, cfg.M)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not "
+              "supported, use --gpus 1" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2512_15306_amd import llmq, synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    llmq.lib()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    states = [LinearState(cfg, li, dev) for li in range(len(cfg.linears))]
+    if args.prequantized_w:
+        for s in states:
+            llmq.llmq_amax(s.W, llmq.E4M3, s.aw, s.sw)
+            llmq.llmq_quantize_fp8(s.W, s.sw, llmq.E4M3, s.view(2), s.view(3))
+    for _ in range(args.warmup):
+        run_step(states, args.prequantized_w)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ms_step = timed(lambda: run_step(states, args.prequantized_w), args.steps)
+    wall = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_step = max(ms_step, 0.0)
+    flops = float(synth.linear_flops(cfg))
+    value = flops / (ms_step * 1e-3) / 1e12
+
+    # dominant kernel: the FP8 GEMM (three launches per linear), timed alone on the same operands
+    reps = max(3, min(args.steps, 20))
+    ms_gemm = timed(lambda: run_gemms_only(states), reps)
+    n_gemm = 3 * len(states)
+    gemm_tflops = flops / (ms_gemm * 1e-3) / 1e12
+    ms_quant = timed(lambda: run_quant_only(states), reps)
+    qbytes = 6.0 * synth.quantize_elements(cfg)         # absmax reads 2 B, quantize reads 2 B and writes 1 + 1 B
+    out = {
+        "metric": "FP8 linear fwd+bwd TFLOP/s and % dense-FP8 MFMA peak; quantize GB/s",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "wall_ms_per_step": round(wall, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "fp8", "data": "synthetic",
+        "config": {"workload": "config %d: %s, M=%d tokens, linears %s; absmax + quantize(+transpose) of X, W, dY "
+                               "(e4m3, e4m3, e5m2) and fwd+dgrad+wgrad per linear%s" % (
+                                   cfg.index, cfg.name, cfg.M,
+                                   ", ".join("%s %dx%d" % (l.name, l.K, l.N) for l in cfg.linears),
+                                   "; W pre-quantized" if args.prequantized_w else "")},
+        "pct_fp8_peak": round(100.0 * value / PEAK_FP8_TFLOPS, 2),
+        "gemm_only_tflops": round(gemm_tflops, 2),
+        "gemm_only_pct_fp8_peak": round(100.0 * gemm_tflops / PEAK_FP8_TFLOPS, 2),
+        "quantize_gbps": round(qbytes / (ms_quant * 1e-3) / 1e9, 1),
+        "quantize_pct_hbm_peak": round(100.0 * qbytes / (ms_quant * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2),
+        "roofline": {"kernel": "gemm_tn_256_kernel", "bound": "mfma", "achieved": round(gemm_tflops, 2),
+                     "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_FP8_TFLOPS, 4),
+                     "traffic": None, "launches_per_step": n_gemm,
+                     "avg_launch_ms": round(ms_gemm / n_gemm, 5),
+                     "flops_per_launch": flops / n_gemm},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

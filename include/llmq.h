@@ -1,0 +1,146 @@
+/*
+ * llmq.h -- C ABI of the MI355X (gfx950) FP8 linear-layer path of LLMQ's 8-bit training pipeline.
+ *
+ * What the path computes (paper, Section 3 "Overview" and the kernel-fusion paragraph of Section 3):
+ *   1. just-in-time tensor-level absmax scaling: find the largest |x| of a BF16 tensor and choose the
+ *      scale that maps it onto the largest finite FP8 value, so that nothing is clipped;
+ *   2. convert BF16 -> FP8 (E4M3 or E5M2, Section 2) with that scale, fused with the transposed copy,
+ *      because the FP8 GEMM takes both operands with the contraction index contiguous ("TN");
+ *   3. the transformer-block matmuls in FP8 with BF16 results: forward Y = X W^T, and in the backward
+ *      pass dX = dY W and dW = dY^T X.
+ *
+ * Conventions for every entry point
+ *   - Tensors are row-major with the last index contiguous.  X is [M,K], W is [N,K], Y and dY are
+ *     [M,N], dX is [M,K], dW is [N,K].  BF16 tensors are arrays of 16-bit patterns, FP8 tensors are
+ *     arrays of 8-bit OCP codes.
+ *   - Every pointer is DEVICE memory owned by the caller, except `stream`, which is a hipStream_t
+ *     passed as void* (NULL = the default stream).  The library allocates nothing, frees nothing and
+ *     keeps no pointer after a call returns (Section 3 "Overview": all allocation happens at start-up).
+ *   - Calls only enqueue work on `stream` and return; nothing synchronises with the host.  Scales and
+ *     absmax values are read from and written to device memory.
+ *   - BF16 and FP8 tensor pointers must be 16-byte aligned, float pointers 4-byte aligned.
+ *   - Return value: LLMQ_OK or a negative llmq_status.  Argument errors are found on the host before
+ *     anything is launched and leave all outputs untouched.  LLMQ_ERR_DEVICE reports a launch failure.
+ *   - Results are bitwise deterministic: same inputs, same bytes (Section 3 "Reproducibility").  The
+ *     only atomics used are integer max, whose result does not depend on order.
+ *   - Dimensions may be any positive value.  Shapes whose dimensions are multiples of 256 (GEMM) or of
+ *     16 rows x 8 columns (quantize) take the tuned kernels; everything else takes slower generic ones.
+ */
+#ifndef LLMQ_H
+#define LLMQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LLMQ_OK = 0,
+    LLMQ_ERR_NULL = -1,       /* a required pointer is NULL */
+    LLMQ_ERR_SHAPE = -2,      /* a dimension is < 1 or too large */
+    LLMQ_ERR_ALIGN = -3,      /* a pointer is not aligned as required */
+    LLMQ_ERR_FORMAT = -4,     /* not an llmq_fp8_format */
+    LLMQ_ERR_WORKSPACE = -5,  /* workspace missing or smaller than llmq_fp8_linear_workspace_bytes() */
+    LLMQ_ERR_DEVICE = -6,     /* the HIP runtime reported an error at launch */
+    LLMQ_ERR_FLAGS = -7       /* unknown bits in `flags` */
+} llmq_status;
+
+/* OCP 8-bit floating point formats (Section 2): E4M3 has bias 7 and max 448 (no Inf, NaN = S.1111.111),
+ * E5M2 has bias 15 and max 57344 (IEEE-like Inf/NaN). */
+typedef enum { LLMQ_E4M3 = 0, LLMQ_E5M2 = 1 } llmq_fp8_format;
+
+const char* llmq_status_string(int status);
+int llmq_version(void);
+
+/*
+ * Absmax and scale of a BF16 tensor (Section 3 "Overview": "determine the largest absolute value in
+ * each tensor, and then rescale so that this is mapped to the largest representable value").
+ *   x_bf16   [n] BF16, device, 16-byte aligned; n >= 1.
+ *   fmt      target FP8 format, selects FMAX (448 or 57344) for the scale.
+ *   d_amax   [1] float, device, written: max_i |x_i| exactly; the canonical quiet NaN 0x7FC00000 if the
+ *            tensor holds a NaN; +Inf if it holds an Inf and no NaN.
+ *   d_scale  [1] float, device, written if not NULL: FMAX / amax as one IEEE binary32 division;
+ *            1.0f when amax == 0; clamped to FLT_MAX when the quotient overflows.
+ * Two launches: a one-thread reset and a reduction whose last block writes the scale.
+ */
+int llmq_amax(const void* x_bf16, size_t n, int fmt, float* d_amax, float* d_scale, void* stream);
+
+/*
+ * Fused scale + FP8 cast + transposed copy (Section 3: "a fused transpose+quantize kernel").
+ *   q[i,j]   = cast( fl32( fl32(x[i,j]) * d_scale[0] ) ),  q_t[j,i] = q[i,j]
+ * cast = round-to-nearest-even onto the FP8 grid, saturating at +-FMAX (a finite product never yields
+ * an Inf or NaN code).  The result for NaN inputs is unspecified.
+ *   x_bf16   [rows, cols] BF16;  d_scale [1] float (device);  q [rows, cols] FP8;
+ *   q_t      [cols, rows] FP8, or NULL when no transposed copy is wanted.
+ */
+int llmq_quantize_fp8(const void* x_bf16, int64_t rows, int64_t cols, const float* d_scale, int fmt,
+                      uint8_t* q, uint8_t* q_t, void* stream);
+
+/*
+ * The FP8 contraction that forward, dgrad and wgrad share (Section 3: FP8 GEMM is TN-only):
+ *   c[r,cc] = bf16( ( sum_t A[r,t] * B[cc,t] ) / (sA * sB) )        accumulate == 0
+ *   c[r,cc] = bf16( c[r,cc] + (sum ...) / (sA * sB) )                accumulate != 0 (BF16 gradient
+ *                                                                    accumulation, Section 3 "Overview")
+ *   A [R,T] FP8 in format fmtA, B [C,T] FP8 in format fmtB (any mix of E4M3 / E5M2), products exact,
+ *   accumulation in binary32 on the matrix cores, de-scaling in binary32, one rounding to BF16 (RNE).
+ *   d_scaleA, d_scaleB  [1] float each (device): the scales the operands were quantized with.
+ *   c_bf16   [R,C] BF16, written (read first when accumulate != 0).
+ *   d_amax_c [1] float (device) or NULL: if given, receives max |c| of the BF16 result, bit-identical to
+ *            llmq_amax of c (the next layer's quantization then needs no separate reduction; Section 3,
+ *            kernel-fusion paragraph).
+ * Error of each element is bounded by 2^-7 * sum_t |A[r,t] B[cc,t]| / (sA sB).
+ */
+int llmq_fp8_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB,
+                     int64_t R, int64_t C, int64_t T,
+                     const float* d_scaleA, const float* d_scaleB,
+                     void* c_bf16, int accumulate, float* d_amax_c, void* stream);
+
+/*
+ * Workspace of the three linear-layer calls below, for one (M, N, K).  It holds the FP8 copies
+ *   Xq [M,K], Xq_t [K,M], Wq [N,K], Wq_t [K,N], dYq [M,N], dYq_t [N,M]
+ * in this order, each starting at a multiple of 256 bytes; llmq_fp8_linear_workspace_offsets() returns
+ * the six byte offsets.  The caller owns the workspace and may read the copies between calls.
+ */
+size_t llmq_fp8_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t offsets[6]);
+
+/* `flags` of the linear calls: the named operand's FP8 copies are already in the workspace (written by
+ * an earlier call with the same M, N, K and the same scale) and are not produced again.  Weights are
+ * quantized once per optimizer step and reused across micro-steps and in the backward pass (Section 3,
+ * weight caching), and the backward pass reuses the forward's copies of X. */
+#define LLMQ_REUSE_X  1
+#define LLMQ_REUSE_W  2
+#define LLMQ_REUSE_DY 4
+
+/*
+ * Forward: Y[M,N] = X[M,K] W[N,K]^T in FP8 (E4M3 x E4M3), BF16 out.
+ * Quantizes X and W (both layouts each, unless LLMQ_REUSE_X / LLMQ_REUSE_W) with the given scales, then
+ * runs the contraction on Xq and Wq.  d_amax_y may be NULL.
+ */
+int llmq_fp8_linear_fwd(const void* X, const void* W, int64_t M, int64_t N, int64_t K,
+                        const float* d_scale_x, const float* d_scale_w,
+                        void* Y, float* d_amax_y, void* ws, size_t ws_bytes, int flags, void* stream);
+
+/*
+ * Input gradient: dX[M,K] = dY[M,N] W[N,K].  dY is quantized to fmt_dy (E5M2 or E4M3; the paper tried
+ * both, Section 5 Scenario 1) unless LLMQ_REUSE_DY; W unless LLMQ_REUSE_W.  Contraction over N on dYq and
+ * Wq_t.  W and dY pointers are not read for operands whose REUSE flag is set (and may then be NULL).
+ */
+int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, int64_t K,
+                          const float* d_scale_dy, const float* d_scale_w, int fmt_dy,
+                          void* dX, float* d_amax_dx, void* ws, size_t ws_bytes, int flags, void* stream);
+
+/*
+ * Weight gradient: dW[N,K] = dY[M,N]^T X[M,K] (accumulate != 0: dW += ..., in BF16).  Contraction over M on
+ * dYq_t and Xq_t.
+ */
+int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, int64_t K,
+                          const float* d_scale_dy, const float* d_scale_x, int fmt_dy,
+                          void* dW, int accumulate, void* ws, size_t ws_bytes, int flags, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LLMQ_H */

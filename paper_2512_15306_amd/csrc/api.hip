@@ -1,0 +1,185 @@
+// C ABI of the FP8 linear path: argument checks and launch sequencing only; all arithmetic is in
+// the kernels (amax.hip, quantize.hip, gemm.hip).  Declarations and contracts: include/llmq.h.
+#include <hip/hip_runtime.h>
+
+#include "../../include/llmq.h"
+#include "llmq_kernels.h"
+
+namespace {
+
+constexpr int64_t kMaxDim = (int64_t)1 << 31;        // per dimension
+constexpr int64_t kMaxElems = (int64_t)1 << 40;      // per tensor
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline bool fmt_ok(int f) { return f == LLMQ_E4M3 || f == LLMQ_E5M2; }
+inline bool dim_ok(int64_t d) { return d >= 1 && d < kMaxDim; }
+inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+int num_cus() {
+    static int cached = 0;                              // benign race: every thread computes the same value
+    if (cached == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cached = n;
+    }
+    return cached;
+}
+
+struct WsLayout {
+    size_t xq, xqt, wq, wqt, dyq, dyqt, total;
+};
+
+WsLayout ws_layout(int64_t M, int64_t N, int64_t K) {
+    WsLayout l;
+    size_t off = 0;
+    l.xq = off;   off += round256((size_t)M * K);
+    l.xqt = off;  off += round256((size_t)M * K);
+    l.wq = off;   off += round256((size_t)N * K);
+    l.wqt = off;  off += round256((size_t)N * K);
+    l.dyq = off;  off += round256((size_t)M * N);
+    l.dyqt = off; off += round256((size_t)M * N);
+    l.total = off;
+    return l;
+}
+
+int check_linear(int64_t M, int64_t N, int64_t K, const void* ws, size_t ws_bytes, int flags) {
+    if (!dim_ok(M) || !dim_ok(N) || !dim_ok(K)) return LLMQ_ERR_SHAPE;
+    if (M * K >= kMaxElems || N * K >= kMaxElems || M * N >= kMaxElems) return LLMQ_ERR_SHAPE;
+    if (flags & ~(LLMQ_REUSE_X | LLMQ_REUSE_W | LLMQ_REUSE_DY)) return LLMQ_ERR_FLAGS;
+    if (!ws) return LLMQ_ERR_NULL;
+    if (!aligned(ws, 256)) return LLMQ_ERR_ALIGN;
+    if (ws_bytes < ws_layout(M, N, K).total) return LLMQ_ERR_WORKSPACE;
+    return LLMQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* llmq_status_string(int status) {
+    switch (status) {
+        case LLMQ_OK: return "ok";
+        case LLMQ_ERR_NULL: return "a required pointer is NULL";
+        case LLMQ_ERR_SHAPE: return "a dimension is out of range";
+        case LLMQ_ERR_ALIGN: return "a pointer is not aligned as required";
+        case LLMQ_ERR_FORMAT: return "unknown FP8 format";
+        case LLMQ_ERR_WORKSPACE: return "workspace too small";
+        case LLMQ_ERR_DEVICE: return "HIP launch failed";
+        case LLMQ_ERR_FLAGS: return "unknown flag bits";
+        default: return "unknown status";
+    }
+}
+
+int llmq_version(void) { return 100; }
+
+int llmq_amax(const void* x_bf16, size_t n, int fmt, float* d_amax, float* d_scale, void* stream) {
+    if (!x_bf16 || !d_amax) return LLMQ_ERR_NULL;
+    if (n < 1 || n >= (size_t)kMaxElems) return LLMQ_ERR_SHAPE;
+    if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
+    if (!aligned(x_bf16, 16) || !aligned(d_amax, 4) || !aligned(d_scale, 4)) return LLMQ_ERR_ALIGN;
+    return llmq::launch_amax(x_bf16, n, fmt, d_amax, d_scale, static_cast<hipStream_t>(stream), num_cus());
+}
+
+int llmq_quantize_fp8(const void* x_bf16, int64_t rows, int64_t cols, const float* d_scale, int fmt,
+                      uint8_t* q, uint8_t* q_t, void* stream) {
+    if (!x_bf16 || !d_scale || !q) return LLMQ_ERR_NULL;
+    if (!dim_ok(rows) || !dim_ok(cols) || rows * cols >= kMaxElems) return LLMQ_ERR_SHAPE;
+    if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
+    if (!aligned(x_bf16, 16) || !aligned(q, 16) || !aligned(q_t, 16) || !aligned(d_scale, 4)) return LLMQ_ERR_ALIGN;
+    return llmq::launch_quantize(x_bf16, rows, cols, d_scale, fmt, q, q_t, static_cast<hipStream_t>(stream));
+}
+
+int llmq_fp8_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64_t R, int64_t C, int64_t T,
+                     const float* d_scaleA, const float* d_scaleB, void* c_bf16, int accumulate,
+                     float* d_amax_c, void* stream) {
+    if (!A || !B || !d_scaleA || !d_scaleB || !c_bf16) return LLMQ_ERR_NULL;
+    if (!dim_ok(R) || !dim_ok(C) || !dim_ok(T)) return LLMQ_ERR_SHAPE;
+    if (R * T >= kMaxElems || C * T >= kMaxElems || R * C >= kMaxElems) return LLMQ_ERR_SHAPE;
+    if (!fmt_ok(fmtA) || !fmt_ok(fmtB)) return LLMQ_ERR_FORMAT;
+    if (!aligned(A, 16) || !aligned(B, 16) || !aligned(c_bf16, 16) || !aligned(d_scaleA, 4) ||
+        !aligned(d_scaleB, 4) || !aligned(d_amax_c, 4))
+        return LLMQ_ERR_ALIGN;
+    return llmq::launch_gemm_tn(A, fmtA, B, fmtB, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, d_amax_c,
+                                static_cast<hipStream_t>(stream), num_cus());
+}
+
+size_t llmq_fp8_linear_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    if (!dim_ok(M) || !dim_ok(N) || !dim_ok(K)) return 0;
+    return ws_layout(M, N, K).total;
+}
+
+int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t offsets[6]) {
+    if (!offsets) return LLMQ_ERR_NULL;
+    if (!dim_ok(M) || !dim_ok(N) || !dim_ok(K)) return LLMQ_ERR_SHAPE;
+    const WsLayout l = ws_layout(M, N, K);
+    offsets[0] = l.xq; offsets[1] = l.xqt; offsets[2] = l.wq; offsets[3] = l.wqt; offsets[4] = l.dyq; offsets[5] = l.dyqt;
+    return LLMQ_OK;
+}
+
+int llmq_fp8_linear_fwd(const void* X, const void* W, int64_t M, int64_t N, int64_t K,
+                        const float* d_scale_x, const float* d_scale_w, void* Y, float* d_amax_y,
+                        void* ws, size_t ws_bytes, int flags, void* stream) {
+    int st = check_linear(M, N, K, ws, ws_bytes, flags);
+    if (st != LLMQ_OK) return st;
+    if (flags & LLMQ_REUSE_DY) return LLMQ_ERR_FLAGS;
+    const bool qx = !(flags & LLMQ_REUSE_X), qw = !(flags & LLMQ_REUSE_W);
+    if ((qx && !X) || (qw && !W) || !d_scale_x || !d_scale_w || !Y) return LLMQ_ERR_NULL;
+    if ((qx && !aligned(X, 16)) || (qw && !aligned(W, 16)) || !aligned(Y, 16) || !aligned(d_scale_x, 4) ||
+        !aligned(d_scale_w, 4) || !aligned(d_amax_y, 4))
+        return LLMQ_ERR_ALIGN;
+    const WsLayout l = ws_layout(M, N, K);
+    uint8_t* base = static_cast<uint8_t*>(ws);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (qx && (st = llmq::launch_quantize(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, base + l.xqt, s))) return st;
+    if (qw && (st = llmq::launch_quantize(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, base + l.wqt, s))) return st;
+    return llmq::launch_gemm_tn(base + l.xq, LLMQ_E4M3, base + l.wq, LLMQ_E4M3, M, N, K, d_scale_x, d_scale_w,
+                                Y, 0, d_amax_y, s, num_cus());
+}
+
+int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, int64_t K,
+                          const float* d_scale_dy, const float* d_scale_w, int fmt_dy, void* dX,
+                          float* d_amax_dx, void* ws, size_t ws_bytes, int flags, void* stream) {
+    int st = check_linear(M, N, K, ws, ws_bytes, flags);
+    if (st != LLMQ_OK) return st;
+    if (flags & LLMQ_REUSE_X) return LLMQ_ERR_FLAGS;
+    if (!fmt_ok(fmt_dy)) return LLMQ_ERR_FORMAT;
+    const bool qd = !(flags & LLMQ_REUSE_DY), qw = !(flags & LLMQ_REUSE_W);
+    if ((qd && !dY) || (qw && !W) || !d_scale_dy || !d_scale_w || !dX) return LLMQ_ERR_NULL;
+    if ((qd && !aligned(dY, 16)) || (qw && !aligned(W, 16)) || !aligned(dX, 16) || !aligned(d_scale_dy, 4) ||
+        !aligned(d_scale_w, 4) || !aligned(d_amax_dx, 4))
+        return LLMQ_ERR_ALIGN;
+    const WsLayout l = ws_layout(M, N, K);
+    uint8_t* base = static_cast<uint8_t*>(ws);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (qd && (st = llmq::launch_quantize(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, base + l.dyqt, s))) return st;
+    if (qw && (st = llmq::launch_quantize(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, base + l.wqt, s))) return st;
+    // dX[m,k] = sum_n dYq[m,n] * Wq_t[k,n]
+    return llmq::launch_gemm_tn(base + l.dyq, fmt_dy, base + l.wqt, LLMQ_E4M3, M, K, N, d_scale_dy, d_scale_w,
+                                dX, 0, d_amax_dx, s, num_cus());
+}
+
+int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, int64_t K,
+                          const float* d_scale_dy, const float* d_scale_x, int fmt_dy, void* dW,
+                          int accumulate, void* ws, size_t ws_bytes, int flags, void* stream) {
+    int st = check_linear(M, N, K, ws, ws_bytes, flags);
+    if (st != LLMQ_OK) return st;
+    if (flags & LLMQ_REUSE_W) return LLMQ_ERR_FLAGS;
+    if (!fmt_ok(fmt_dy)) return LLMQ_ERR_FORMAT;
+    const bool qd = !(flags & LLMQ_REUSE_DY), qx = !(flags & LLMQ_REUSE_X);
+    if ((qd && !dY) || (qx && !X) || !d_scale_dy || !d_scale_x || !dW) return LLMQ_ERR_NULL;
+    if ((qd && !aligned(dY, 16)) || (qx && !aligned(X, 16)) || !aligned(dW, 16) || !aligned(d_scale_dy, 4) ||
+        !aligned(d_scale_x, 4))
+        return LLMQ_ERR_ALIGN;
+    const WsLayout l = ws_layout(M, N, K);
+    uint8_t* base = static_cast<uint8_t*>(ws);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (qd && (st = llmq::launch_quantize(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, base + l.dyqt, s))) return st;
+    if (qx && (st = llmq::launch_quantize(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, base + l.xqt, s))) return st;
+    // dW[n,k] = sum_m dYq_t[n,m] * Xq_t[k,m]
+    return llmq::launch_gemm_tn(base + l.dyqt, fmt_dy, base + l.xqt, LLMQ_E4M3, N, K, M, d_scale_dy, d_scale_x,
+                                dW, accumulate, nullptr, s, num_cus());
+}
+
+}  // extern "C"

@@ -1,0 +1,18 @@
+// Host-side launchers of the gfx950 kernels (internal to the library; the public ABI is llmq.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace llmq {
+
+// Each returns 0 or LLMQ_ERR_DEVICE (-6).  Arguments are validated by the callers in api.hip.
+int launch_amax(const void* x, size_t n, int fmt, float* d_amax, float* d_scale, hipStream_t stream,
+                int num_cus);
+int launch_quantize(const void* x, int64_t rows, int64_t cols, const float* d_scale, int fmt,
+                    uint8_t* q, uint8_t* q_t, hipStream_t stream);
+int launch_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64_t R, int64_t C,
+                   int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16,
+                   int accumulate, float* d_amax_c, hipStream_t stream, int num_cus);
+
+}  // namespace llmq

@@ -1,0 +1,155 @@
+// Fused scale + FP8 cast + transposed copy (paper Section 3: "a fused transpose+quantize kernel";
+// the FP8 GEMM wants both operands contraction-contiguous, so every quantized tensor is also
+// needed transposed in the backward pass).
+//
+// HBM-bound: per element 2 bytes read, 1 byte written row-major and 1 byte written transposed.
+// Tuned kernel: one lane owns a 16-row x 8-column patch.  It reads the patch with sixteen 16-byte
+// loads (eight lanes side by side cover a full 128-byte line of a row), converts with one binary32
+// multiply and the hardware RNE cast (clamped first, which makes it saturating), writes its 8 bytes
+// of each row, transposes the 16x8 byte patch in registers with byte permutes and writes eight
+// 16-byte vectors of the transposed tensor (eight lanes stacked in rows cover a full 128-byte line
+// there).  No LDS, no barrier.
+#include "llmq_device.h"
+#include "llmq_kernels.h"
+
+namespace llmq {
+
+constexpr int kQThreads = 256;
+constexpr int kPatchRows = 16;
+constexpr int kPatchCols = 8;
+constexpr int kLanesR = 8;                               // lanes of a wave stacked along rows
+constexpr int kLanesC = kWave / kLanesR;                 // lanes of a wave side by side
+constexpr int kWaveRows = kPatchRows * kLanesR;          // 128
+constexpr int kWaveCols = kPatchCols * kLanesC;          // 64
+constexpr int kBlockCols = kWaveCols * (kQThreads / kWave);   // 256: the four waves sit side by side
+
+template <int FMT>
+__device__ inline unsigned cvt_pair(float a, float b, unsigned old, bool high) {
+    constexpr float fmax = FMT == 0 ? 448.0f : 57344.0f;
+    a = __builtin_amdgcn_fmed3f(a, -fmax, fmax);         // saturate; the cast below rounds to nearest even
+    b = __builtin_amdgcn_fmed3f(b, -fmax, fmax);
+    if constexpr (FMT == 0) {
+        return high ? (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, true)
+                    : (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, false);
+    } else {
+        return high ? (unsigned)__builtin_amdgcn_cvt_pk_bf8_f32(a, b, (int)old, true)
+                    : (unsigned)__builtin_amdgcn_cvt_pk_bf8_f32(a, b, (int)old, false);
+    }
+}
+
+// Four BF16 pairs (one 16-byte load) -> eight FP8 codes in two dwords.
+template <int FMT>
+__device__ inline void quantize8(const v4u& r, float s, unsigned& lo, unsigned& hi) {
+    float f[8];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        f[2 * j] = __uint_as_float(r[j] << 16) * s;            // even element: low half of the dword
+        f[2 * j + 1] = __uint_as_float(r[j] & 0xFFFF0000u) * s;
+    }
+    lo = cvt_pair<FMT>(f[0], f[1], 0u, false);
+    lo = cvt_pair<FMT>(f[2], f[3], lo, true);
+    hi = cvt_pair<FMT>(f[4], f[5], 0u, false);
+    hi = cvt_pair<FMT>(f[6], f[7], hi, true);
+}
+
+// w[r] holds bytes (r,0..3) of a 4x4 byte block; returns o[c] = bytes (0..3,c).
+__device__ inline void transpose4x4_bytes(const unsigned w[4], unsigned o[4]) {
+    // v_perm_b32 selects from the 8 bytes {first operand: 4..7, second operand: 0..3}
+    unsigned t01l = __builtin_amdgcn_perm(w[1], w[0], 0x05010400u);   // w0.0 w1.0 w0.1 w1.1
+    unsigned t01h = __builtin_amdgcn_perm(w[1], w[0], 0x07030602u);   // w0.2 w1.2 w0.3 w1.3
+    unsigned t23l = __builtin_amdgcn_perm(w[3], w[2], 0x05010400u);
+    unsigned t23h = __builtin_amdgcn_perm(w[3], w[2], 0x07030602u);
+    o[0] = __builtin_amdgcn_perm(t23l, t01l, 0x05040100u);
+    o[1] = __builtin_amdgcn_perm(t23l, t01l, 0x07060302u);
+    o[2] = __builtin_amdgcn_perm(t23h, t01h, 0x05040100u);
+    o[3] = __builtin_amdgcn_perm(t23h, t01h, 0x07060302u);
+}
+
+template <int FMT, bool TRANSPOSE>
+__global__ __launch_bounds__(kQThreads) void quantize_patch_kernel(
+    const uint16_t* __restrict__ x, int64_t rows, int64_t cols, const float* __restrict__ d_scale,
+    uint8_t* __restrict__ q, uint8_t* __restrict__ qt) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int64_t r0 = (int64_t)blockIdx.y * kWaveRows + (lane % kLanesR) * kPatchRows;
+    const int64_t c0 = (int64_t)blockIdx.x * kBlockCols + wave * kWaveCols + (lane / kLanesR) * kPatchCols;
+    if (r0 >= rows || c0 >= cols) return;       // rows % 16 == 0 and cols % 8 == 0: a patch is all in or all out
+    const float s = *d_scale;
+    v4u in[kPatchRows];
+    const uint16_t* src = x + r0 * cols + c0;
+#pragma unroll
+    for (int i = 0; i < kPatchRows; ++i)
+        in[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(src + (int64_t)i * cols));
+    unsigned lo[kPatchRows], hi[kPatchRows];
+#pragma unroll
+    for (int i = 0; i < kPatchRows; ++i) quantize8<FMT>(in[i], s, lo[i], hi[i]);
+    uint8_t* dst = q + r0 * cols + c0;
+#pragma unroll
+    for (int i = 0; i < kPatchRows; ++i) {
+        v2u v = {lo[i], hi[i]};
+        __builtin_nontemporal_store(v, reinterpret_cast<v2u*>(dst + (int64_t)i * cols));
+    }
+    if constexpr (TRANSPOSE) {
+        // column j of the patch -> 16 consecutive bytes of row (c0 + j) of the transposed tensor
+        unsigned col[kPatchCols][4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            unsigned o[4];
+            transpose4x4_bytes(&lo[4 * t], o);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) col[c][t] = o[c];
+            transpose4x4_bytes(&hi[4 * t], o);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) col[4 + c][t] = o[c];
+        }
+        uint8_t* dt = qt + c0 * rows + r0;
+#pragma unroll
+        for (int j = 0; j < kPatchCols; ++j) {
+            v4u v = {col[j][0], col[j][1], col[j][2], col[j][3]};
+            __builtin_nontemporal_store(v, reinterpret_cast<v4u*>(dt + (int64_t)j * rows));
+        }
+    }
+}
+
+// Any shape: one element per lane.  Lanes run along columns for the read and the row-major write.
+template <int FMT>
+__global__ __launch_bounds__(256) void quantize_generic_kernel(
+    const uint16_t* __restrict__ x, int64_t rows, int64_t cols, const float* __restrict__ d_scale,
+    uint8_t* __restrict__ q, uint8_t* __restrict__ qt) {
+    const int64_t n = rows * cols;
+    const float s = *d_scale;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        float p = __uint_as_float((unsigned)x[i] << 16) * s;
+        unsigned code = cvt_pair<FMT>(p, p, 0u, false) & 0xFFu;
+        q[i] = (uint8_t)code;
+        if (qt) {
+            int64_t r = i / cols, c = i - r * cols;
+            qt[c * rows + r] = (uint8_t)code;
+        }
+    }
+}
+
+int launch_quantize(const void* x, int64_t rows, int64_t cols, const float* d_scale, int fmt,
+                    uint8_t* q, uint8_t* q_t, hipStream_t stream) {
+    const uint16_t* xb = reinterpret_cast<const uint16_t*>(x);
+    if (rows % kPatchRows == 0 && cols % kPatchCols == 0) {
+        dim3 grid((unsigned)((cols + kBlockCols - 1) / kBlockCols), (unsigned)((rows + kWaveRows - 1) / kWaveRows));
+        dim3 block(kQThreads);
+        if (fmt == 0) {
+            if (q_t) hipLaunchKernelGGL((quantize_patch_kernel<0, true>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t);
+            else hipLaunchKernelGGL((quantize_patch_kernel<0, false>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t);
+        } else {
+            if (q_t) hipLaunchKernelGGL((quantize_patch_kernel<1, true>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t);
+            else hipLaunchKernelGGL((quantize_patch_kernel<1, false>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t);
+        }
+    } else {
+        int64_t n = rows * cols;
+        int64_t blocks = (n + 255) / 256;
+        if (blocks > 65536) blocks = 65536;
+        if (fmt == 0) hipLaunchKernelGGL((quantize_generic_kernel<0>), dim3((unsigned)blocks), dim3(256), 0, stream, xb, rows, cols, d_scale, q, q_t);
+        else hipLaunchKernelGGL((quantize_generic_kernel<1>), dim3((unsigned)blocks), dim3(256), 0, stream, xb, rows, cols, d_scale, q, q_t);
+    }
+    return hipGetLastError() == hipSuccess ? 0 : -6;
+}
+
+}  // namespace llmq

@@ -1,0 +1,162 @@
+"""Python binding of libllmq.so: same names as the C ABI (include/llmq.h), argument marshalling only.
+
+PyTorch supplies device memory and the current HIP stream; every step of the path runs in the
+library's kernels.  There is no fallback: a missing library or a missing GPU raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch  # imported first on purpose: the library then binds to the HIP runtime PyTorch loaded
+
+E4M3 = 0
+E5M2 = 1
+REUSE_X = 1
+REUSE_W = 2
+REUSE_DY = 4
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libllmq.so")
+_lib = None
+
+EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax", "llmq_quantize_fp8", "llmq_fp8_gemm_tn",
+           "llmq_fp8_linear_workspace_bytes", "llmq_fp8_linear_workspace_offsets",
+           "llmq_fp8_linear_fwd", "llmq_fp8_linear_dgrad", "llmq_fp8_linear_wgrad"]
+
+
+class LlmqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %d (%s)" % (where, status, status_string(status)))
+
+
+def lib() -> ctypes.CDLL:
+    """Load libllmq.so (built in-tree by paper_2512_15306_amd/build.py); raise if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libllmq.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                           "(expected at %s)" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp, i64, sz, i32 = c.c_void_p, c.c_int64, c.c_size_t, c.c_int
+    L.llmq_status_string.restype = c.c_char_p
+    L.llmq_status_string.argtypes = [i32]
+    L.llmq_version.restype = i32
+    L.llmq_version.argtypes = []
+    L.llmq_amax.restype = i32
+    L.llmq_amax.argtypes = [vp, sz, i32, vp, vp, vp]
+    L.llmq_quantize_fp8.restype = i32
+    L.llmq_quantize_fp8.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp]
+    L.llmq_fp8_gemm_tn.restype = i32
+    L.llmq_fp8_gemm_tn.argtypes = [vp, i32, vp, i32, i64, i64, i64, vp, vp, vp, i32, vp, vp]
+    L.llmq_fp8_linear_workspace_bytes.restype = sz
+    L.llmq_fp8_linear_workspace_bytes.argtypes = [i64, i64, i64]
+    L.llmq_fp8_linear_workspace_offsets.restype = i32
+    L.llmq_fp8_linear_workspace_offsets.argtypes = [i64, i64, i64, c.POINTER(sz)]
+    L.llmq_fp8_linear_fwd.restype = i32
+    L.llmq_fp8_linear_fwd.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, sz, i32, vp]
+    L.llmq_fp8_linear_dgrad.restype = i32
+    L.llmq_fp8_linear_dgrad.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, vp, vp, vp, sz, i32, vp]
+    L.llmq_fp8_linear_wgrad.restype = i32
+    L.llmq_fp8_linear_wgrad.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, vp, i32, vp, sz, i32, vp]
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().llmq_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib().llmq_version())
+
+
+def _dev(t: Optional[torch.Tensor], dtype=None, name="tensor") -> Optional[int]:
+    """Device pointer of a contiguous CUDA/HIP tensor (None passes through as NULL)."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise LlmqError(status, where)
+
+
+def llmq_amax(x: torch.Tensor, fmt: int, d_amax: torch.Tensor, d_scale: Optional[torch.Tensor]) -> None:
+    _check(lib().llmq_amax(_dev(x, torch.bfloat16, "x"), x.numel(), fmt, _dev(d_amax, torch.float32, "d_amax"),
+                           _dev(d_scale, torch.float32, "d_scale"), _stream()), "llmq_amax")
+
+
+def llmq_quantize_fp8(x: torch.Tensor, d_scale: torch.Tensor, fmt: int, q: torch.Tensor,
+                      q_t: Optional[torch.Tensor]) -> None:
+    rows, cols = x.shape
+    if q.numel() != rows * cols or (q_t is not None and q_t.numel() != rows * cols):
+        raise ValueError("output size does not match the input")
+    _check(lib().llmq_quantize_fp8(_dev(x, torch.bfloat16, "x"), rows, cols, _dev(d_scale, torch.float32, "d_scale"),
+                                   fmt, _dev(q, torch.uint8, "q"), _dev(q_t, torch.uint8, "q_t"), _stream()),
+           "llmq_quantize_fp8")
+
+
+def llmq_fp8_gemm_tn(A: torch.Tensor, fmtA: int, B: torch.Tensor, fmtB: int, d_scaleA: torch.Tensor,
+                     d_scaleB: torch.Tensor, c: torch.Tensor, accumulate: bool = False,
+                     d_amax_c: Optional[torch.Tensor] = None) -> None:
+    R, T = A.shape
+    C, T2 = B.shape
+    if T != T2 or tuple(c.shape) != (R, C):
+        raise ValueError("shape mismatch: A %s, B %s, c %s" % (tuple(A.shape), tuple(B.shape), tuple(c.shape)))
+    _check(lib().llmq_fp8_gemm_tn(_dev(A, torch.uint8, "A"), fmtA, _dev(B, torch.uint8, "B"), fmtB, R, C, T,
+                                  _dev(d_scaleA, torch.float32), _dev(d_scaleB, torch.float32),
+                                  _dev(c, torch.bfloat16, "c"), int(bool(accumulate)),
+                                  _dev(d_amax_c, torch.float32), _stream()), "llmq_fp8_gemm_tn")
+
+
+def llmq_fp8_linear_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(lib().llmq_fp8_linear_workspace_bytes(M, N, K))
+
+
+def llmq_fp8_linear_workspace_offsets(M: int, N: int, K: int) -> Tuple[int, ...]:
+    arr = (ctypes.c_size_t * 6)()
+    _check(lib().llmq_fp8_linear_workspace_offsets(M, N, K, arr), "llmq_fp8_linear_workspace_offsets")
+    return tuple(int(v) for v in arr)
+
+
+def llmq_fp8_linear_fwd(X, W, M: int, N: int, K: int, d_scale_x, d_scale_w, Y, d_amax_y, ws: torch.Tensor,
+                        flags: int = 0) -> None:
+    _check(lib().llmq_fp8_linear_fwd(_dev(X, torch.bfloat16, "X"), _dev(W, torch.bfloat16, "W"), M, N, K,
+                                     _dev(d_scale_x, torch.float32), _dev(d_scale_w, torch.float32),
+                                     _dev(Y, torch.bfloat16, "Y"), _dev(d_amax_y, torch.float32),
+                                     _dev(ws, torch.uint8, "ws"), ws.numel(), flags, _stream()),
+           "llmq_fp8_linear_fwd")
+
+
+def llmq_fp8_linear_dgrad(dY, W, M: int, N: int, K: int, d_scale_dy, d_scale_w, fmt_dy: int, dX, d_amax_dx,
+                          ws: torch.Tensor, flags: int = 0) -> None:
+    _check(lib().llmq_fp8_linear_dgrad(_dev(dY, torch.bfloat16, "dY"), _dev(W, torch.bfloat16, "W"), M, N, K,
+                                       _dev(d_scale_dy, torch.float32), _dev(d_scale_w, torch.float32), fmt_dy,
+                                       _dev(dX, torch.bfloat16, "dX"), _dev(d_amax_dx, torch.float32),
+                                       _dev(ws, torch.uint8, "ws"), ws.numel(), flags, _stream()),
+           "llmq_fp8_linear_dgrad")
+
+
+def llmq_fp8_linear_wgrad(dY, X, M: int, N: int, K: int, d_scale_dy, d_scale_x, fmt_dy: int, dW,
+                          accumulate: bool, ws: torch.Tensor, flags: int = 0) -> None:
+    _check(lib().llmq_fp8_linear_wgrad(_dev(dY, torch.bfloat16, "dY"), _dev(X, torch.bfloat16, "X"), M, N, K,
+                                       _dev(d_scale_dy, torch.float32), _dev(d_scale_x, torch.float32), fmt_dy,
+                                       _dev(dW, torch.bfloat16, "dW"), int(bool(accumulate)),
+                                       _dev(ws, torch.uint8, "ws"), ws.numel(), flags, _stream()),
+           "llmq_fp8_linear_wgrad")

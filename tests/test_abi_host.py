@@ -1,0 +1,82 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol that
+include/llmq.h declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_15306_amd import llmq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "llmq.h")).read()
+    declared = set(re.findall(r"\b(llmq_[a-z0-9_]+)\s*\(", header))
+    declared -= {"llmq_status", "llmq_fp8_format"}
+    assert declared == set(llmq.EXPORTS)
+    L = llmq.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert llmq.version() >= 100
+    assert llmq.status_string(0) == "ok"
+    for st in range(-7, 0):
+        assert llmq.status_string(st) not in ("ok", "unknown status")
+
+
+def test_workspace_layout():
+    M, N, K = 256, 1024, 512
+    offs = llmq.llmq_fp8_linear_workspace_offsets(M, N, K)
+    sizes = [M * K, M * K, N * K, N * K, M * N, M * N]
+    assert offs[0] == 0
+    for i in range(5):
+        assert offs[i + 1] >= offs[i] + sizes[i] and offs[i + 1] % 256 == 0
+    assert llmq.llmq_fp8_linear_workspace_bytes(M, N, K) >= offs[5] + sizes[5]
+    # ragged sizes are padded to 256-byte boundaries
+    offs = llmq.llmq_fp8_linear_workspace_offsets(3, 5, 7)
+    assert all(o % 256 == 0 for o in offs) and len(set(offs)) == 6
+    assert llmq.llmq_fp8_linear_workspace_bytes(0, 1, 1) == 0
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    L = llmq.lib()
+    ok_ptr = 0x10000          # never dereferenced: every call below fails validation on the host
+    odd_ptr = 0x10008
+    n = ctypes.c_size_t
+    assert L.llmq_amax(None, 8, 0, ok_ptr, ok_ptr, None) == -1
+    assert L.llmq_amax(ok_ptr, 8, 0, None, ok_ptr, None) == -1
+    assert L.llmq_amax(ok_ptr, 0, 0, ok_ptr, ok_ptr, None) == -2
+    assert L.llmq_amax(ok_ptr, 8, 2, ok_ptr, ok_ptr, None) == -4
+    assert L.llmq_amax(odd_ptr, 8, 0, ok_ptr, ok_ptr, None) == -3
+    assert L.llmq_amax(ok_ptr, 8, 0, ok_ptr + 2, ok_ptr, None) == -3
+    assert L.llmq_quantize_fp8(ok_ptr, 4, 4, None, 0, ok_ptr, ok_ptr, None) == -1
+    assert L.llmq_quantize_fp8(ok_ptr, 0, 4, ok_ptr, 0, ok_ptr, ok_ptr, None) == -2
+    assert L.llmq_quantize_fp8(ok_ptr, 4, -1, ok_ptr, 0, ok_ptr, ok_ptr, None) == -2
+    assert L.llmq_quantize_fp8(ok_ptr, 4, 4, ok_ptr, 7, ok_ptr, ok_ptr, None) == -4
+    assert L.llmq_quantize_fp8(ok_ptr, 4, 4, ok_ptr, 0, odd_ptr, ok_ptr, None) == -3
+    assert L.llmq_fp8_gemm_tn(ok_ptr, 0, None, 0, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, 0, None, None) == -1
+    assert L.llmq_fp8_gemm_tn(ok_ptr, 0, ok_ptr, 0, 16, 0, 16, ok_ptr, ok_ptr, ok_ptr, 0, None, None) == -2
+    assert L.llmq_fp8_gemm_tn(ok_ptr, 3, ok_ptr, 0, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, 0, None, None) == -4
+    assert L.llmq_fp8_gemm_tn(ok_ptr, 0, ok_ptr, 0, 16, 16, 16, ok_ptr, ok_ptr, odd_ptr, 0, None, None) == -3
+    ws = 0x100000
+    need = llmq.llmq_fp8_linear_workspace_bytes(16, 16, 16)
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, None, n(need), 0, None) == -1
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need - 1), 0, None) == -5
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws + 16, n(need), 0, None) == -3
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 8, None) == -7
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 4, None) == -7
+    assert L.llmq_fp8_linear_fwd(None, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 0, None) == -1
+    assert L.llmq_fp8_linear_dgrad(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, 5, ok_ptr, None, ws, n(need), 0, None) == -4
+    assert L.llmq_fp8_linear_dgrad(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, 1, ok_ptr, None, ws, n(need), 1, None) == -7
+    assert L.llmq_fp8_linear_dgrad(ok_ptr, ok_ptr, 16, 0, 16, ok_ptr, ok_ptr, 1, ok_ptr, None, ws, n(need), 0, None) == -2
+    assert L.llmq_fp8_linear_wgrad(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, 1, None, 0, ws, n(need), 0, None) == -1
+    assert L.llmq_fp8_linear_wgrad(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, 1, ok_ptr, 0, ws, n(need), 2, None) == -7
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(8, dtype=torch.bfloat16)
+    a = torch.zeros(1)
+    with pytest.raises(ValueError):
+        llmq.llmq_amax(x, 0, a, a)

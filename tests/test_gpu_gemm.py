@@ -1,0 +1,240 @@
+"""GPU parity: the FP8 contraction and the three linear-layer calls against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2512_15306_amd import llmq, synth
+from gpu_common import (DEV, GEMM_TOL, f32_bits, np_f32_bits, gpu_amax, gpu_quantize, oracle_quantized,
+                        bf16_to_f64, assert_gemm_close)
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand_codes(shape, fmt, seed):
+    """Random finite FP8 codes with moderate magnitudes (exponent field in the middle of the range)."""
+    rng = np.random.default_rng(seed)
+    if fmt == 0:
+        e = rng.integers(3, 11, size=shape)
+        m = rng.integers(0, 8, size=shape)
+        c = (e << 3) | m
+    else:
+        e = rng.integers(10, 20, size=shape)
+        m = rng.integers(0, 4, size=shape)
+        c = (e << 2) | m
+    c |= rng.integers(0, 2, size=shape) << 7
+    return c.astype(np.uint8)
+
+
+def _scales(sa, sb):
+    return (torch.tensor([sa], dtype=torch.float32, device=DEV), torch.tensor([sb], dtype=torch.float32, device=DEV))
+
+
+def _run_gemm(A, fa, B, fb, sa, sb, accumulate=False, c_init=None, want_amax=False):
+    Ad, Bd = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    dsa, dsb = _scales(sa, sb)
+    c = torch.full((A.shape[0], B.shape[0]), float("nan"), dtype=torch.bfloat16, device=DEV) if c_init is None else c_init.clone()
+    am = torch.full((1,), -1.0, dtype=torch.float32, device=DEV) if want_amax else None
+    llmq.llmq_fp8_gemm_tn(Ad, fa, Bd, fb, dsa, dsb, c, accumulate, am)
+    return c, am
+
+
+# generic path: odd shapes, ragged K; tuned path: multiples of 256 x 256 x 128 (odd and even K steps)
+GEMM_SHAPES = [(1, 1, 1), (5, 3, 7), (16, 16, 128), (33, 17, 130), (100, 136, 72), (48, 40, 1000),
+               (256, 256, 128), (256, 256, 256), (256, 512, 384), (512, 256, 640), (768, 1024, 512)]
+
+
+@pytest.mark.parametrize("R,C,T", GEMM_SHAPES)
+@pytest.mark.parametrize("fa,fb", [(0, 0), (1, 0), (0, 1), (1, 1)])
+def test_gemm_tn_within_tolerance(R, C, T, fa, fb):
+    print("gemm R=%d C=%d T=%d fa=%d fb=%d" % (R, C, T, fa, fb), flush=True)
+    A = _rand_codes((R, T), fa, 11 * R + T + fa)
+    B = _rand_codes((C, T), fb, 13 * C + T + fb + 1)
+    sa, sb = 3.7, 0.61
+    c, am = _run_gemm(A, fa, B, fb, sa, sb, want_amax=True)
+    y, S = oracle.gemm_tn(A, fa, B, fb, sa, sb)
+    assert_gemm_close(c, y, S, "gemm")
+    # fused output absmax == absmax of the BF16 result the kernel wrote, bit for bit
+    a2, _ = gpu_amax(c.reshape(-1), 0, want_scale=False)
+    assert f32_bits(am) == f32_bits(a2)
+    assert am.item() == c.float().abs().max().item()
+    # determinism
+    c2, _ = _run_gemm(A, fa, B, fb, sa, sb)
+    assert torch.equal(c2.view(torch.int16), c.view(torch.int16))
+
+
+@pytest.mark.parametrize("R,C,T", [(33, 17, 130), (256, 512, 384)])
+def test_gemm_accumulate_in_bf16(R, C, T):
+    A = _rand_codes((R, T), 1, 5)
+    B = _rand_codes((C, T), 0, 6)
+    sa, sb = 2.0, 0.5
+    g = torch.Generator().manual_seed(3)
+    c0 = (torch.randn((R, C), generator=g) * 50).to(torch.bfloat16).to(DEV)
+    c, _ = _run_gemm(A, 1, B, 0, sa, sb, accumulate=True, c_init=c0)
+    y, S = oracle.gemm_tn(A, 1, B, 0, sa, sb)
+    want = bf16_to_f64(c0) + y
+    got = bf16_to_f64(c)
+    # one extra BF16 rounding of the sum on top of the GEMM tolerance
+    assert np.all(np.abs(got - want) <= GEMM_TOL * S + 2.0 ** -8 * np.abs(want))
+
+
+@pytest.mark.parametrize("M,K,N", [(5, 7, 3), (40, 32, 24), (256, 128, 256)])
+def test_integer_inputs_give_exact_products(M, K, N):
+    """Lossless inputs (small integers, absmax 7): every GEMM result is an exact small integer."""
+    rng = np.random.default_rng(M + K + N)
+
+    def ints(shape):
+        v = rng.integers(-2, 3, size=shape).astype(np.float32)
+        v[tuple(rng.integers(0, s) for s in shape)] = 7.0
+        return torch.from_numpy(v).to(torch.bfloat16)
+
+    X, W, dY = ints((M, K)), ints((N, K)), ints((M, N))
+    Xd, Wd, dYd = X.to(DEV), W.to(DEV), dY.to(DEV)
+    ws = torch.empty(llmq.llmq_fp8_linear_workspace_bytes(M, N, K), dtype=torch.uint8, device=DEV)
+    _, sx = gpu_amax(Xd, 0)
+    _, sw = gpu_amax(Wd, 0)
+    _, sd = gpu_amax(dYd, 1)
+    assert (sx.item(), sw.item(), sd.item()) == (64.0, 64.0, 8192.0)
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    dX = torch.empty((M, K), dtype=torch.bfloat16, device=DEV)
+    dW = torch.empty((N, K), dtype=torch.bfloat16, device=DEV)
+    llmq.llmq_fp8_linear_fwd(Xd, Wd, M, N, K, sx, sw, Y, None, ws)
+    llmq.llmq_fp8_linear_dgrad(dYd, Wd, M, N, K, sd, sw, 1, dX, None, ws, llmq.REUSE_W)
+    llmq.llmq_fp8_linear_wgrad(dYd, Xd, M, N, K, sd, sx, 1, dW, False, ws, llmq.REUSE_X | llmq.REUSE_DY)
+    Xi, Wi, Di = X.double().numpy(), W.double().numpy(), dY.double().numpy()
+    assert np.array_equal(bf16_to_f64(Y), Xi @ Wi.T)
+    assert np.array_equal(bf16_to_f64(dX), Di @ Wi)
+    assert np.array_equal(bf16_to_f64(dW), Di.T @ Xi)
+
+
+def _linear_case(cfg, li, M=None, fmt_dy=1, K=None, N=None):
+    x = synth.make_x(cfg, li, device="cpu", M=M)
+    w = synth.make_w(cfg, li, device="cpu")
+    dy = synth.make_dy(cfg, li, device="cpu", M=M)
+    if K is not None:
+        x, w = x[:, :K].contiguous(), w[:, :K].contiguous()
+    if N is not None:
+        w, dy = w[:N].contiguous(), dy[:, :N].contiguous()
+    return x, w, dy
+
+
+@pytest.mark.parametrize("shape", synth.small_cases())
+@pytest.mark.parametrize("fmt_dy", [1, 0])
+def test_linear_fwd_dgrad_wgrad_full_compare(shape, fmt_dy):
+    """Whole outputs of the three calls against the oracle on config-1 style inputs, every workspace
+    copy bit-exact, every reuse flag exercised."""
+    M, K, N = shape
+    print("linear M=%d K=%d N=%d fmt_dy=%d" % (M, K, N, fmt_dy), flush=True)
+    cfg = synth.CONFIGS[1]
+    x, w, dy = _linear_case(cfg, 0, M=M, K=K if K <= 512 else None, N=N if N <= 1024 else None)
+    if x.shape[1] != K or w.shape[0] != N:      # shapes beyond config 1's tensor: draw fresh ones
+        g = torch.Generator().manual_seed(M * 7 + K * 3 + N)
+        x = torch.randn((M, K), generator=g).to(torch.bfloat16)
+        w = (torch.randn((N, K), generator=g) * 0.02).to(torch.bfloat16)
+        dy = (torch.randn((M, N), generator=g) * 1e-3).to(torch.bfloat16)
+    ax, sx, xq, xqt = oracle_quantized(x, 0)
+    aw, sw, wq, wqt = oracle_quantized(w, 0)
+    ad, sd, dq, dqt = oracle_quantized(dy, fmt_dy)
+    xd, wd, dyd = x.to(DEV), w.to(DEV), dy.to(DEV)
+    _, gsx = gpu_amax(xd, 0)
+    _, gsw = gpu_amax(wd, 0)
+    _, gsd = gpu_amax(dyd, fmt_dy)
+    assert [f32_bits(t) for t in (gsx, gsw, gsd)] == [np_f32_bits(v) for v in (sx, sw, sd)]
+    nbytes = llmq.llmq_fp8_linear_workspace_bytes(M, N, K)
+    offs = llmq.llmq_fp8_linear_workspace_offsets(M, N, K)
+    ws = torch.full((nbytes,), 0x55, dtype=torch.uint8, device=DEV)
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    dX = torch.empty((M, K), dtype=torch.bfloat16, device=DEV)
+    dW = torch.empty((N, K), dtype=torch.bfloat16, device=DEV)
+    amax_y = torch.zeros(1, dtype=torch.float32, device=DEV)
+    amax_dx = torch.zeros(1, dtype=torch.float32, device=DEV)
+    llmq.llmq_fp8_linear_fwd(xd, wd, M, N, K, gsx, gsw, Y, amax_y, ws)
+    llmq.llmq_fp8_linear_dgrad(dyd, None, M, N, K, gsd, gsw, fmt_dy, dX, amax_dx, ws, llmq.REUSE_W)
+    llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, gsd, gsx, fmt_dy, dW, False, ws, llmq.REUSE_X | llmq.REUSE_DY)
+    wsh = ws.cpu().numpy()
+    for off, want in zip(offs, (xq, xqt, wq, wqt, dq, dqt)):
+        assert np.array_equal(wsh[off:off + want.size].reshape(want.shape), want)
+    y, S = oracle.gemm_tn(xq, 0, wq, 0, sx, sw)
+    assert_gemm_close(Y, y, S, "fwd")
+    y, S = oracle.gemm_tn(dq, fmt_dy, wqt, 0, sd, sw)
+    assert_gemm_close(dX, y, S, "dgrad")
+    y, S = oracle.gemm_tn(dqt, fmt_dy, xqt, 0, sd, sx)
+    assert_gemm_close(dW, y, S, "wgrad")
+    assert amax_y.item() == Y.float().abs().max().item()
+    assert amax_dx.item() == dX.float().abs().max().item()
+    # without reuse flags the backward calls quantize for themselves and give the same bytes
+    ws2 = torch.full((nbytes,), 0x33, dtype=torch.uint8, device=DEV)
+    dX2, dW2 = torch.empty_like(dX), torch.empty_like(dW)
+    llmq.llmq_fp8_linear_dgrad(dyd, wd, M, N, K, gsd, gsw, fmt_dy, dX2, None, ws2, 0)
+    llmq.llmq_fp8_linear_wgrad(dyd, xd, M, N, K, gsd, gsx, fmt_dy, dW2, False, ws2, 0)
+    assert torch.equal(dX2.view(torch.int16), dX.view(torch.int16))
+    assert torch.equal(dW2.view(torch.int16), dW.view(torch.int16))
+    # gradient accumulation: dW += on top of the previous result
+    llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, gsd, gsx, fmt_dy, dW2, True, ws2, llmq.REUSE_X | llmq.REUSE_DY)
+    want2 = 2.0 * y
+    assert np.all(np.abs(bf16_to_f64(dW2) - want2) <= 2 * GEMM_TOL * S + 2.0 ** -8 * np.abs(want2))
+
+
+def _sample_positions(R, C, n, seed, tile=256):
+    rng = np.random.default_rng(seed)
+    rr = rng.integers(0, R, n)
+    cc = rng.integers(0, C, n)
+    # plus full tile-boundary rows and columns (first/last row of interior tiles), subsampled
+    rows = [0, R - 1] + ([tile - 1, tile] if R > tile else [])
+    cols = [0, C - 1] + ([tile - 1, tile] if C > tile else [])
+    er, ec = [], []
+    for r in rows:
+        cs = np.unique(np.concatenate([np.arange(0, C, max(1, C // 257)), [C - 1]]))
+        er.append(np.full(cs.shape, r)); ec.append(cs)
+    for c in cols:
+        rs = np.unique(np.concatenate([np.arange(0, R, max(1, R // 257)), [R - 1]]))
+        er.append(rs); ec.append(np.full(rs.shape, c))
+    return np.concatenate([rr] + er), np.concatenate([cc] + ec)
+
+
+@pytest.mark.parametrize("cfg_i,li", [(2, 1), (2, 0), (3, 0), (3, 3), (5, 1)])
+def test_full_size_linears_on_sampled_outputs(cfg_i, li):
+    """BASELINE shapes in the launch configuration bench.py times; the oracle computes >= 4096 random
+    outputs plus tile-boundary rows and columns of each of the three GEMMs with full-length dot
+    products; quantized operands are compared in full."""
+    cfg = synth.CONFIGS[cfg_i]
+    lin = cfg.linears[li]
+    M, K, N = cfg.M, lin.K, lin.N
+    print("full-size config %d %s M=%d K=%d N=%d" % (cfg_i, lin.name, M, K, N), flush=True)
+    xd = synth.make_x(cfg, li, device=DEV)
+    wd = synth.make_w(cfg, li, device=DEV)
+    dyd = synth.make_dy(cfg, li, device=DEV)
+    _, sx = gpu_amax(xd, 0)
+    _, sw = gpu_amax(wd, 0)
+    _, sd = gpu_amax(dyd, 1)
+    ws = torch.empty(llmq.llmq_fp8_linear_workspace_bytes(M, N, K), dtype=torch.uint8, device=DEV)
+    offs = llmq.llmq_fp8_linear_workspace_offsets(M, N, K)
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    dX = torch.empty((M, K), dtype=torch.bfloat16, device=DEV)
+    dW = torch.empty((N, K), dtype=torch.bfloat16, device=DEV)
+    amax_y = torch.zeros(1, dtype=torch.float32, device=DEV)
+    llmq.llmq_fp8_linear_fwd(xd, wd, M, N, K, sx, sw, Y, amax_y, ws)
+    llmq.llmq_fp8_linear_dgrad(dyd, None, M, N, K, sd, sw, 1, dX, None, ws, llmq.REUSE_W)
+    llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, sd, sx, 1, dW, False, ws, llmq.REUSE_X | llmq.REUSE_DY)
+    torch.cuda.synchronize()
+    print("  gpu done; oracle quantize", flush=True)
+    ox = oracle_quantized(xd, 0)
+    ow = oracle_quantized(wd, 0)
+    od = oracle_quantized(dyd, 1)
+    assert [f32_bits(t) for t in (sx, sw, sd)] == [np_f32_bits(o[1]) for o in (ox, ow, od)]
+    wsh = ws.cpu().numpy()
+    for off, want in zip(offs, (ox[2], ox[3], ow[2], ow[3], od[2], od[3])):
+        assert np.array_equal(wsh[off:off + want.size].reshape(want.shape), want)
+    del wsh
+    assert amax_y.item() == Y.float().abs().max().item()
+    for name, out, (A, fa, sa), (B, fb, sb) in [
+            ("fwd", Y, (ox[2], 0, ox[1]), (ow[2], 0, ow[1])),
+            ("dgrad", dX, (od[2], 1, od[1]), (ow[3], 0, ow[1])),
+            ("wgrad", dW, (od[3], 1, od[1]), (ox[3], 0, ox[1]))]:
+        print("  oracle samples %s" % name, flush=True)
+        rr, cc = _sample_positions(out.shape[0], out.shape[1], 4096, 17 + li)
+        y, S = oracle.gemm_tn_sampled(A, fa, B, fb, sa, sb, rr, cc)
+        got = out[torch.from_numpy(rr).to(DEV), torch.from_numpy(cc).to(DEV)].cpu().to(torch.float64).numpy()
+        err = np.abs(got - y)
+        assert np.all(err <= GEMM_TOL * S), (name, err.max(), (GEMM_TOL * S)[err.argmax()])
+        assert np.isfinite(got).all() and np.abs(got).max() > 0
