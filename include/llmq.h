@@ -22,7 +22,7 @@
  *   - Return value: LLMQ_OK or a negative llmq_status.  Argument errors are found on the host before
  *     anything is launched and leave all outputs untouched.  LLMQ_ERR_DEVICE reports a launch failure.
  *   - Results are bitwise deterministic: same inputs, same bytes (Section 3 "Reproducibility").  The
- *     only atomics used are integer max, whose result does not depend on order.
+ *     only atomics used are integer max and min, whose results do not depend on order.
  *   - Dimensions may be any positive value.  Shapes whose dimensions are multiples of 256 (GEMM) or of
  *     16 rows x 8 columns (quantize) take the tuned kernels; everything else takes slower generic ones.
  */
@@ -61,9 +61,10 @@ int llmq_version(void);
  *   fmt      target FP8 format, selects FMAX (448 or 57344) for the scale.
  *   d_amax   [1] float, device, written: max_i |x_i| exactly; the canonical quiet NaN 0x7FC00000 if the
  *            tensor holds a NaN; +Inf if it holds an Inf and no NaN.
- *   d_scale  [1] float, device, written if not NULL: FMAX / amax as one IEEE binary32 division;
- *            1.0f when amax == 0; clamped to FLT_MAX when the quotient overflows.
- * Two launches: a one-thread reset and a reduction whose last block writes the scale.
+ *   d_scale  [1] float, device, written if not NULL: min(FMAX / amax, FLT_MAX) with one IEEE binary32
+ *            division, so FLT_MAX for an all-zero tensor (every code is then +-0) and for an absmax so
+ *            small that the quotient overflows; 0 when amax is +Inf; unspecified when amax is NaN.
+ * Two launches: a one-thread reset and the reduction (integer atomic max / min, order-independent).
  */
 int llmq_amax(const void* x_bf16, size_t n, int fmt, float* d_amax, float* d_scale, void* stream);
 

@@ -18,8 +18,9 @@
  *     transposed copies are produced by a fused transpose+quantize step.
  *
  * Readings where the paper is silent (listed in the design notes as well):
- *   scale  s = fl32(FMAX / amax), one binary32 division; amax == 0 -> s = 1;
- *          a quotient that overflows binary32 is clamped to FLT_MAX;
+ *   scale  s = min(fl32(FMAX / amax), FLT_MAX): one IEEE binary32 division, whose
+ *          overflow (tiny amax, and amax == 0 where the quotient is +Inf) is
+ *          clamped to the largest finite binary32;
  *   value  p = fl32(fl32(x) * s), one binary32 multiplication, not fused;
  *   cast   round-to-nearest-even onto the FP8 grid, saturating to +-FMAX
  *          (never produces an Inf or NaN code from a finite p); NaN -> S.1111111;
@@ -156,7 +157,6 @@ float oracle_amax_bf16(const uint16_t* x, size_t n) {
 }
 
 float oracle_scale(float amax, int fmt) {
-    if (amax == 0.0f) return 1.0f;
     volatile float num = (float)oracle_fp8_max(fmt);
     volatile float den = amax;
     volatile float s = num / den;          /* one binary32 division */

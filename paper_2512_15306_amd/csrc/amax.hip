@@ -2,9 +2,12 @@
 //
 // HBM-bound: 2 bytes read per element, nothing else.  Each lane streams 16-byte vectors, keeps a
 // packed 16-bit integer maximum of the magnitude bits (exact: |x| orders like bits & 0x7FFF), the
-// wavefront combines with DPP, the block with a small LDS tree, and blocks meet in one integer
-// atomic max, whose result is order-independent and therefore deterministic.  The last block to
-// finish turns the absmax into the scale, so no third launch is needed.
+// wavefront combines with DPP, the block with a small LDS tree.  Blocks meet in integer atomics:
+// max on the absmax bits and min on the scale bits (the scale FMAX/amax falls as amax grows, and
+// non-negative floats order like their bit patterns), both order-independent and therefore
+// deterministic.  Read-modify-write atomics of many blocks on one address serialise at roughly
+// 12 ns each on this chip, so a block first reads the running maximum and only issues its atomics
+// when it would raise it; on real tensors that is a handful of blocks.
 #include "llmq_device.h"
 #include "llmq_kernels.h"
 
@@ -13,10 +16,10 @@ namespace llmq {
 constexpr int kAmaxThreads = 256;
 constexpr int kAmaxUnroll = 8;          // 16-byte loads in flight per lane
 
-__global__ void amax_reset_kernel(unsigned* amax_bits, unsigned* ticket) {
+__global__ void amax_reset_kernel(unsigned* amax_bits, unsigned* scale_bits) {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
         *amax_bits = 0u;
-        if (ticket) *ticket = 0u;
+        if (scale_bits) *scale_bits = 0x7F7FFFFFu;       // FLT_MAX: the scale of an all-zero tensor
     }
 }
 
@@ -28,17 +31,16 @@ __device__ inline unsigned pk_max_mag(unsigned acc, unsigned w) {
 
 __global__ __launch_bounds__(kAmaxThreads) void amax_kernel(
     const v4u* __restrict__ x, size_t n_vec, const uint16_t* __restrict__ tail, int n_tail,
-    unsigned* __restrict__ amax_bits, unsigned* __restrict__ ticket_then_scale, float fmax) {
+    unsigned* __restrict__ amax_bits, unsigned* __restrict__ scale_bits, float fmax) {
     __shared__ unsigned s_part[kAmaxThreads / kWave];
     unsigned m0 = 0, m1 = 0, m2 = 0, m3 = 0;      // packed pairs of 15-bit magnitudes
     const size_t chunk = (size_t)kAmaxThreads * kAmaxUnroll;
-    for (size_t base = (size_t)blockIdx.x * chunk; base < n_vec; base += (size_t)gridDim.x * chunk) {
+    const size_t n_full = n_vec / chunk;
+    for (size_t c = blockIdx.x; c < n_full; c += gridDim.x) {
+        const v4u* p = x + c * chunk + threadIdx.x;
         v4u r[kAmaxUnroll];
 #pragma unroll
-        for (int j = 0; j < kAmaxUnroll; ++j) {
-            size_t i = base + (size_t)j * kAmaxThreads + threadIdx.x;
-            r[j] = i < n_vec ? __builtin_nontemporal_load(x + i) : v4u{0u, 0u, 0u, 0u};
-        }
+        for (int j = 0; j < kAmaxUnroll; ++j) r[j] = __builtin_nontemporal_load(p + j * kAmaxThreads);
 #pragma unroll
         for (int j = 0; j < kAmaxUnroll; ++j) {
             m0 = pk_max_mag(m0, r[j][0]);
@@ -47,36 +49,35 @@ __global__ __launch_bounds__(kAmaxThreads) void amax_kernel(
             m3 = pk_max_mag(m3, r[j][3]);
         }
     }
+    if (blockIdx.x == gridDim.x - 1) {            // the partial chunk and the n % 8 trailing elements
+        for (size_t i = n_full * chunk + threadIdx.x; i < n_vec; i += kAmaxThreads) {
+            v4u r = x[i];
+            m0 = pk_max_mag(m0, r[0]);
+            m1 = pk_max_mag(m1, r[1]);
+            m2 = pk_max_mag(m2, r[2]);
+            m3 = pk_max_mag(m3, r[3]);
+        }
+        if ((int)threadIdx.x < n_tail) m0 = pk_max_mag(m0, (unsigned)tail[threadIdx.x]);
+    }
     m0 = pk_max_mag(pk_max_mag(m0, m1), pk_max_mag(m2, m3));
     unsigned m = (m0 & 0xFFFFu) > (m0 >> 16) ? (m0 & 0xFFFFu) : (m0 >> 16);
-    if (blockIdx.x == 0 && (int)threadIdx.x < n_tail) {          // the n % 8 trailing elements
-        unsigned t = tail[threadIdx.x] & 0x7FFFu;
-        m = m > t ? m : t;
-    }
     m = wave_max_u32(m);
     if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x / kWave] = m;
     __syncthreads();
     if (threadIdx.x == 0) {
 #pragma unroll
         for (int w = 1; w < kAmaxThreads / kWave; ++w) m = m > s_part[w] ? m : s_part[w];
-        atomicMax(amax_bits, amax_bits_from_bf16_mag(m));
-        bool last = false;
-        if (ticket_then_scale) {
-            __threadfence();
-            last = atomicAdd(ticket_then_scale, 1u) == gridDim.x - 1;
-        }
-        if (last) {
-            __threadfence();
-            unsigned bits = atomicMax(amax_bits, 0u);            // coherent read of the final value
-            float a = __uint_as_float(bits);
-            float s;
-            if (a == 0.0f) {
-                s = 1.0f;
-            } else {
-                s = fmax / a;                                     // one correctly rounded division
+        const unsigned bits = amax_bits_from_bf16_mag(m);
+        // A stale value is never above the true running maximum, so skipping on it is safe: whoever
+        // wrote that value also issues (or has issued) the matching scale.
+        const unsigned cur = __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (bits > cur) {
+            atomicMax(amax_bits, bits);
+            if (scale_bits) {
+                float s = fmax / __uint_as_float(bits);           // one correctly rounded division
                 if (__builtin_isinf(s)) s = 3.402823466e+38f;
+                atomicMin(scale_bits, __float_as_uint(s));        // a NaN scale (NaN absmax) never wins
             }
-            *reinterpret_cast<float*>(ticket_then_scale) = s;
         }
     }
 }
@@ -86,8 +87,8 @@ int launch_amax(const void* x, size_t n, int fmt, float* d_amax, float* d_scale,
     const size_t n_vec = n / 8;
     const int n_tail = (int)(n % 8);
     const size_t chunk = (size_t)kAmaxThreads * kAmaxUnroll;
-    size_t blocks = (n_vec + chunk - 1) / chunk;
-    const size_t max_blocks = (size_t)num_cus * 8;
+    size_t blocks = n_vec / chunk;
+    const size_t max_blocks = (size_t)num_cus * 4;
     if (blocks > max_blocks) blocks = max_blocks;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL(amax_reset_kernel, dim3(1), dim3(64), 0, stream,
