@@ -76,7 +76,34 @@ __device__ inline void mma_4x4(v16f (&acc)[4][4], const v8i (&a)[4], const v8i (
             acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[i][j], FB, FA, 0, 0, 0, 0);
 }
 
-template <int FA, int FB>
+// Tuning knobs of the tuned kernel.
+struct GemmTuning {
+    // K steps ahead of the direct-to-LDS loads at which each wave touches one dword per 128-byte
+    // line of its share of the slabs, to pull them into L2 early (0 = no touching).
+    static constexpr int kTouchAhead = 2;
+    // Development aid: a tuning struct with kProfile = true also provides
+    //   static __device__ void record(int block, int slot, long long value)
+    // and gets cycle stamps of the phases of wave 0 of every workgroup.
+    static constexpr bool kProfile = false;
+    // LDS swizzle of the operand slabs: the 16-byte chunk index of a row is XOR-ed with
+    // (row >> kSwizzleShift) & 7.
+    static constexpr int kSwizzleShift = 1;
+};
+
+template <int N>
+__device__ inline void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Workgroup barrier that orders LDS traffic only: the caller has already waited for the
+// direct-to-LDS loads it needs with wait_vmcnt<>, other global loads may stay in flight.
+__device__ inline void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+template <int FA, int FB, class V = GemmTuning>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_256_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ C,
     int Cn, int T, const float* __restrict__ d_sA, const float* __restrict__ d_sB,
@@ -95,27 +122,41 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_256_kernel(
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int wr = wave >> 1, wc = wave & 1;
+    auto stamp = [&](int slot) {
+        if constexpr (V::kProfile) {
+            if (threadIdx.x == 0) {
+                V::record(blockIdx.x, slot, (long long)__builtin_readcyclecounter());
+                V::record(blockIdx.x, slot + 8, (long long)__builtin_amdgcn_s_memrealtime());
+            }
+        }
+    };
+    stamp(0);
 
     // ---- global -> LDS: one instruction moves 8 rows x 128 B; wave w moves rows [64w, 64w+64) of A and B
     const __amdgpu_buffer_rsrc_t rsA = make_rsrc(A + (size_t)tr * BM * T, (unsigned)((size_t)BM * T));
     const __amdgpu_buffer_rsrc_t rsB = make_rsrc(B + (size_t)tc * BN * T, (unsigned)((size_t)BN * T));
+    // Instruction j of a wave covers rows 64*wave + 8*j + (lane >> 3); the swizzle of those rows only
+    // depends on the parity of j.
+    constexpr int kSw = V::kSwizzleShift;
     const int ld_row = lane >> 3;                                   // row inside the group of 8
-    const int ld_voff = ld_row * T + (((lane & 7) ^ ld_row) << 4);
+    const int ld_voff0 = ld_row * T + (((lane & 7) ^ ((ld_row >> kSw) & 7)) << 4);
+    const int ld_voff1 = ld_row * T + (((lane & 7) ^ (((8 + ld_row) >> kSw) & 7)) << 4);
     const int ld_soff = wave * 64 * T;
     auto issue_loads = [&](uint8_t* slabA, uint8_t* slabB, int k0) {
         uint8_t* sa = slabA + wave * 64 * BK;
         uint8_t* sb = slabB + wave * 64 * BK;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_void*)(sa + j * 8 * BK), 16, ld_voff, ld_soff + k0 + j * 8 * T, 0, 0);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_void*)(sb + j * 8 * BK), 16, ld_voff, ld_soff + k0 + j * 8 * T, 0, 0);
+            const int voff = (j & 1) ? ld_voff1 : ld_voff0;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_void*)(sa + j * 8 * BK), 16, voff, ld_soff + k0 + j * 8 * T, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_void*)(sb + j * 8 * BK), 16, voff, ld_soff + k0 + j * 8 * T, 0, 0);
         }
     };
 
     // ---- LDS -> registers: lane reads 32 contiguous bytes (two swizzled 16-byte chunks) of its row
     const int fr_row = lane & 31;
     const int fr_half = lane >> 5;                                  // which 32 bytes of the 64-byte K half
-    const int swz = fr_row & 7;                                     // (row & 7) for every row this lane reads
+    const int swz = (fr_row >> kSw) & 7;                            // same for every row this lane reads
     // byte offsets inside a slab for K-half 0 and 1, first and second chunk
     const int offA = (wr * 128 + fr_row) * BK, offB = (wc * 128 + fr_row) * BK;
     const int ch00 = ((fr_half * 2) ^ swz) << 4, ch01 = ((fr_half * 2 + 1) ^ swz) << 4;
@@ -142,6 +183,14 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_256_kernel(
     v8i a0[4], b0[4], a1[4], b1[4];        // fragment sets of the two 64-byte halves of a K step
     const int nk = T / BK;
 
+    // L2 touch loads: lane l of wave w reads the first dword of row 64w + l of a slab still V::kTouchAhead
+    // steps ahead of the direct-to-LDS loads.  All CUs of an XCD walk K in lock-step, so without this
+    // every slab is first requested only ~1.5 steps before it is needed, less than an L2 miss takes.
+    constexpr int kTouch = V::kTouchAhead;
+    const int touch_voff = lane * T;
+    int touchA[2] = {0, 0}, touchB[2] = {0, 0};   // results are only kept so that the loads stay tracked
+    int touch_sink = 0;
+
     // One K step on the stage (curA, curB) while the other stage (nxtA, nxtB) is being filled:
     //   first half : read the second-half fragments            | 16 MFMAs on the first-half fragments
     //   barrier    : the next slab has landed, everybody is done reading the current one
@@ -150,7 +199,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_256_kernel(
     // Loads that would start beyond the last slab are pointed outside the buffer range instead:
     // the hardware then fetches nothing, and the stage they would fill is never read.
     constexpr int kOutOfRange = 0x7FFFFF00;
-    auto k_step = [&](uint8_t* curA, uint8_t* curB, uint8_t* nxtA, uint8_t* nxtB, int kt) {
+    auto k_step = [&](uint8_t* curA, uint8_t* curB, uint8_t* nxtA, uint8_t* nxtB, int kt, int parity) {
         read_frags(curA, offA, 1, a1);
         read_frags(curB, offB, 1, b1);
         mma_4x4<FA, FB>(acc, a0, b0);
@@ -161,8 +210,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_256_kernel(
             __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 0);
         }
         __builtin_amdgcn_sched_group_barrier(kSchedMfma, 8, 0);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
+        // the 16 direct-to-LDS loads of the previous step must have landed; its two touch loads, issued
+        // after them, may still be in flight
+        if constexpr (kTouch > 0) wait_vmcnt<2>(); else wait_vmcnt<0>();
+        lds_barrier();
         __builtin_amdgcn_sched_barrier(0);
         issue_loads(curA, curB, kt + 2 < nk ? (kt + 2) * BK : kOutOfRange);
         read_frags(nxtA, offA, 0, a0);          // past the last slab this reads stale bytes that are never used
@@ -180,48 +231,101 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_256_kernel(
             __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, 1, 1);
         }
         __builtin_amdgcn_sched_barrier(0);
+        if constexpr (kTouch > 0) {
+            const int kp = kt + 2 + kTouch;
+            const int off = kp < nk ? ld_soff + kp * BK : kOutOfRange;
+            touch_sink ^= touchA[parity] ^ touchB[parity];          // issued two steps ago: long landed
+            touchA[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voff, off, 0);
+            touchB[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voff, off, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
     issue_loads(ldsA0, ldsB0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    wait_vmcnt<0>();
+    lds_barrier();
     issue_loads(ldsA1, ldsB1, nk > 1 ? BK : kOutOfRange);
+    if constexpr (kTouch > 0) {                   // keep "two touch loads are the newest" true from the start
+        touchA[1] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voff, 2 < nk ? ld_soff + 2 * BK : kOutOfRange, 0);
+        touchB[1] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voff, 2 < nk ? ld_soff + 2 * BK : kOutOfRange, 0);
+    }
     read_frags(ldsA0, offA, 0, a0);
     read_frags(ldsB0, offB, 0, b0);
+    stamp(1);
     int kt = 0;
     for (; kt + 1 < nk; kt += 2) {
-        k_step(ldsA0, ldsB0, ldsA1, ldsB1, kt);
-        k_step(ldsA1, ldsB1, ldsA0, ldsB0, kt + 1);
+        k_step(ldsA0, ldsB0, ldsA1, ldsB1, kt, 0);
+        k_step(ldsA1, ldsB1, ldsA0, ldsB0, kt + 1, 1);
     }
-    if (kt < nk) k_step(ldsA0, ldsB0, ldsA1, ldsB1, kt);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may still be landing in LDS when the wave ends
+    if (kt < nk) k_step(ldsA0, ldsB0, ldsA1, ldsB1, kt, 0);
+    wait_vmcnt<0>();                               // nothing may still be landing in LDS when the wave ends
+    if constexpr (kTouch > 0) {
+        touch_sink ^= touchA[0] ^ touchB[0] ^ touchA[1] ^ touchB[1];
+        asm volatile("" ::"v"(touch_sink));
+    }
+    stamp(2);
 
-    // ---- epilogue: lane holds, per block, 4 groups of 4 consecutive columns of row (lane % 32)
+    // ---- epilogue.  Per 32x32 block a lane holds 4 groups of 4 consecutive columns of row (lane % 32).
+    // Storing those 8-byte pieces directly scatters every store over 32 rows; instead each wave
+    // stages its 128x128 BF16 quadrant (32 KB) in one of the four slabs, which nobody reads any more,
+    // and writes it out as full 256-byte row segments, 16 bytes per lane.  Rows are 256 B in LDS with
+    // the 16-byte slot index XOR-ed with (row & 15), so both the 8-byte writes and the 16-byte reads
+    // spread over all banks.  The region is private to the wave and LDS executes a wave's accesses
+    // in order, so no barrier is needed.
     const float inv_a = 1.0f / *d_sA, inv_b = 1.0f / *d_sB;
     unsigned mag = 0;
-    const int row_base = tr * BM + wr * 128 + fr_row;
-    const int col_base = tc * BN + wc * 128 + fr_half * 4;
+    if (!accumulate) {
+        uint8_t* stage = wave == 0 ? ldsA0 : wave == 1 ? ldsB0 : wave == 2 ? ldsA1 : ldsB1;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        uint16_t* crow = C + (size_t)(row_base + i * 32) * Cn + col_base;
+        for (int i = 0; i < 4; ++i) {
+            const int row = i * 32 + fr_row;
+            uint8_t* srow = stage + row * 256;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < 4; ++j) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                uint16_t* dst = crow + j * 32 + g * 8;
-                v4f y;
+                for (int g = 0; g < 4; ++g) {
+                    const int col = j * 32 + g * 8 + fr_half * 4;            // multiple of 4
+                    v4f y;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) y[e] = acc[i][j][4 * g + e] * inv_a * inv_b;
-                if (accumulate) {
+                    for (int e = 0; e < 4; ++e) y[e] = acc[i][j][4 * g + e] * inv_a * inv_b;
+                    bf16x4 o = __builtin_convertvector(y, bf16x4);
+                    mag = bf16_mag_max4(mag, o);
+                    *reinterpret_cast<bf16x4*>(srow + ((((col >> 3) ^ (row & 15)) << 4) | ((col & 7) << 1))) = o;
+                }
+            }
+        }
+        const int slot = lane & 15, sub = lane >> 4;                          // 16 lanes per row, 4 rows per pass
+        uint16_t* cbase = C + (size_t)(tr * BM + wr * 128) * Cn + tc * BN + wc * 128 + slot * 8;
+#pragma unroll 8
+        for (int it = 0; it < 32; ++it) {
+            const int row = it * 4 + sub;
+            v4u v = *reinterpret_cast<const v4u*>(stage + row * 256 + ((slot ^ (row & 15)) << 4));
+            *reinterpret_cast<v4u*>(cbase + (size_t)row * Cn) = v;
+        }
+    } else {
+        // BF16 accumulation needs the old value before the single rounding: straight from the registers.
+        const int row_base = tr * BM + wr * 128 + fr_row;
+        const int col_base = tc * BN + wc * 128 + fr_half * 4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint16_t* crow = C + (size_t)(row_base + i * 32) * Cn + col_base;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    uint16_t* dst = crow + j * 32 + g * 8;
+                    v4f y;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) y[e] = acc[i][j][4 * g + e] * inv_a * inv_b;
                     v2u old = *reinterpret_cast<const v2u*>(dst);
                     y[0] += __uint_as_float(old[0] << 16);
                     y[1] += __uint_as_float(old[0] & 0xFFFF0000u);
                     y[2] += __uint_as_float(old[1] << 16);
                     y[3] += __uint_as_float(old[1] & 0xFFFF0000u);
+                    bf16x4 o = __builtin_convertvector(y, bf16x4);
+                    mag = bf16_mag_max4(mag, o);
+                    *reinterpret_cast<bf16x4*>(dst) = o;
                 }
-                bf16x4 o = __builtin_convertvector(y, bf16x4);
-                mag = bf16_mag_max4(mag, o);
-                *reinterpret_cast<bf16x4*>(dst) = o;
             }
         }
     }
@@ -232,8 +336,14 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_256_kernel(
         if (threadIdx.x == 0) {
 #pragma unroll
             for (int w = 1; w < kGemmThreads / kWave; ++w) mag = mag > s_amax[w] ? mag : s_amax[w];
-            atomicMax(amax_bits, amax_bits_from_bf16_mag(mag));
+            // same-address atomics of many workgroups serialise; a stale read never exceeds the true maximum
+            const unsigned bits = amax_bits_from_bf16_mag(mag);
+            if (bits > __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(amax_bits, bits);
         }
+    }
+    if constexpr (V::kProfile) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        stamp(3);
     }
 }
 
