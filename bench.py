@@ -51,6 +51,7 @@ class LinearState:
         self.Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
         self.dX = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
         self.dW = torch.empty((N, K), dtype=torch.bfloat16, device=dev)
+        self.aws = torch.empty(llmq.llmq_amax_workspace_bytes(), dtype=torch.uint8, device=dev)
         self.f = torch.zeros(8, dtype=torch.float32, device=dev)   # amax/scale of X, W, dY; amax of Y, dX
         f = self.f
         self.ax, self.sx, self.aw, self.sw, self.ad, self.sd, self.ay, self.adx = (f[i:i + 1] for i in range(8))
@@ -66,12 +67,12 @@ def run_step(states, prequantized_w):
     from paper_2512_15306_amd import llmq
     for s in states:
         M, K, N = s.M, s.K, s.N
-        llmq.llmq_amax(s.X, llmq.E4M3, s.ax, s.sx)
+        llmq.llmq_amax(s.X, llmq.E4M3, s.ax, s.sx, s.aws)
         if not prequantized_w:
-            llmq.llmq_amax(s.W, llmq.E4M3, s.aw, s.sw)
+            llmq.llmq_amax(s.W, llmq.E4M3, s.aw, s.sw, s.aws)
         llmq.llmq_fp8_linear_fwd(s.X, s.W, M, N, K, s.sx, s.sw, s.Y, s.ay, s.ws,
                                  llmq.REUSE_W if prequantized_w else 0)
-        llmq.llmq_amax(s.dY, llmq.E5M2, s.ad, s.sd)
+        llmq.llmq_amax(s.dY, llmq.E5M2, s.ad, s.sd, s.aws)
         llmq.llmq_fp8_linear_dgrad(s.dY, None, M, N, K, s.sd, s.sw, llmq.E5M2, s.dX, s.adx, s.ws, llmq.REUSE_W)
         llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, s.sd, s.sx, llmq.E5M2, s.dW, False, s.ws,
                                    llmq.REUSE_X | llmq.REUSE_DY)
@@ -88,11 +89,11 @@ def run_gemms_only(states):
 def run_quant_only(states):
     from paper_2512_15306_amd import llmq
     for s in states:
-        llmq.llmq_amax(s.X, 0, s.ax, s.sx)
+        llmq.llmq_amax(s.X, 0, s.ax, s.sx, s.aws)
         llmq.llmq_quantize_fp8(s.X, s.sx, 0, s.view(0), s.view(1))
-        llmq.llmq_amax(s.W, 0, s.aw, s.sw)
+        llmq.llmq_amax(s.W, 0, s.aw, s.sw, s.aws)
         llmq.llmq_quantize_fp8(s.W, s.sw, 0, s.view(2), s.view(3))
-        llmq.llmq_amax(s.dY, 1, s.ad, s.sd)
+        llmq.llmq_amax(s.dY, 1, s.ad, s.sd, s.aws)
         llmq.llmq_quantize_fp8(s.dY, s.sd, 1, s.view(4), s.view(5))
 
 
@@ -157,7 +158,7 @@ def main():
     states = [LinearState(cfg, li, dev) for li in range(len(cfg.linears))]
     if args.prequantized_w:
         for s in states:
-            llmq.llmq_amax(s.W, llmq.E4M3, s.aw, s.sw)
+            llmq.llmq_amax(s.W, llmq.E4M3, s.aw, s.sw, s.aws)
             llmq.llmq_quantize_fp8(s.W, s.sw, llmq.E4M3, s.view(2), s.view(3))
     for _ in range(args.warmup):
         run_step(states, args.prequantized_w)

@@ -22,7 +22,7 @@
  *   - Return value: LLMQ_OK or a negative llmq_status.  Argument errors are found on the host before
  *     anything is launched and leave all outputs untouched.  LLMQ_ERR_DEVICE reports a launch failure.
  *   - Results are bitwise deterministic: same inputs, same bytes (Section 3 "Reproducibility").  The
- *     only atomics used are integer max and min, whose results do not depend on order.
+ *     only atomic used is an integer max (fused output absmax), whose result does not depend on order.
  *   - Dimensions may be any positive value.  Shapes whose dimensions are multiples of 256 (GEMM) or of
  *     16 rows x 8 columns (quantize) take the tuned kernels; everything else takes slower generic ones.
  */
@@ -63,10 +63,16 @@ int llmq_version(void);
  *            tensor holds a NaN; +Inf if it holds an Inf and no NaN.
  *   d_scale  [1] float, device, written if not NULL: min(FMAX / amax, FLT_MAX) with one IEEE binary32
  *            division, so FLT_MAX for an all-zero tensor (every code is then +-0) and for an absmax so
- *            small that the quotient overflows; 0 when amax is +Inf; unspecified when amax is NaN.
- * Two launches: a one-thread reset and the reduction (integer atomic max / min, order-independent).
+ *            small that the quotient overflows; 0 when amax is +Inf; NaN when amax is NaN.
+ *   ws       device scratch of at least llmq_amax_workspace_bytes() bytes, 4-byte aligned; contents on
+ *            entry do not matter, it holds per-block partial results between the two launches (a
+ *            streaming reduction, then a one-block kernel that reduces the partial results and writes
+ *            both outputs; no atomics: Section 3 "Reproducibility").  Calls that may overlap on the
+ *            device (different streams) need different workspaces.
  */
-int llmq_amax(const void* x_bf16, size_t n, int fmt, float* d_amax, float* d_scale, void* stream);
+size_t llmq_amax_workspace_bytes(void);
+int llmq_amax(const void* x_bf16, size_t n, int fmt, float* d_amax, float* d_scale,
+              void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Fused scale + FP8 cast + transposed copy (Section 3: "a fused transpose+quantize kernel").

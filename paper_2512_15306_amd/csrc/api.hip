@@ -74,12 +74,16 @@ const char* llmq_status_string(int status) {
 
 int llmq_version(void) { return 100; }
 
-int llmq_amax(const void* x_bf16, size_t n, int fmt, float* d_amax, float* d_scale, void* stream) {
-    if (!x_bf16 || !d_amax) return LLMQ_ERR_NULL;
+size_t llmq_amax_workspace_bytes(void) { return (size_t)llmq::kAmaxMaxPartials * sizeof(unsigned); }
+
+int llmq_amax(const void* x_bf16, size_t n, int fmt, float* d_amax, float* d_scale, void* ws, size_t ws_bytes,
+              void* stream) {
+    if (!x_bf16 || !d_amax || !ws) return LLMQ_ERR_NULL;
     if (n < 1 || n >= (size_t)kMaxElems) return LLMQ_ERR_SHAPE;
     if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
-    if (!aligned(x_bf16, 16) || !aligned(d_amax, 4) || !aligned(d_scale, 4)) return LLMQ_ERR_ALIGN;
-    return llmq::launch_amax(x_bf16, n, fmt, d_amax, d_scale, static_cast<hipStream_t>(stream), num_cus());
+    if (!aligned(x_bf16, 16) || !aligned(d_amax, 4) || !aligned(d_scale, 4) || !aligned(ws, 4)) return LLMQ_ERR_ALIGN;
+    if (ws_bytes < llmq_amax_workspace_bytes()) return LLMQ_ERR_WORKSPACE;
+    return llmq::launch_amax(x_bf16, n, fmt, d_amax, d_scale, ws, static_cast<hipStream_t>(stream), num_cus());
 }
 
 int llmq_quantize_fp8(const void* x_bf16, int64_t rows, int64_t cols, const float* d_scale, int fmt,
@@ -88,7 +92,7 @@ int llmq_quantize_fp8(const void* x_bf16, int64_t rows, int64_t cols, const floa
     if (!dim_ok(rows) || !dim_ok(cols) || rows * cols >= kMaxElems) return LLMQ_ERR_SHAPE;
     if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
     if (!aligned(x_bf16, 16) || !aligned(q, 16) || !aligned(q_t, 16) || !aligned(d_scale, 4)) return LLMQ_ERR_ALIGN;
-    return llmq::launch_quantize(x_bf16, rows, cols, d_scale, fmt, q, q_t, static_cast<hipStream_t>(stream));
+    return llmq::launch_quantize(x_bf16, rows, cols, d_scale, fmt, q, q_t, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int llmq_fp8_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64_t R, int64_t C, int64_t T,
@@ -101,7 +105,7 @@ int llmq_fp8_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int
     if (!aligned(A, 16) || !aligned(B, 16) || !aligned(c_bf16, 16) || !aligned(d_scaleA, 4) ||
         !aligned(d_scaleB, 4) || !aligned(d_amax_c, 4))
         return LLMQ_ERR_ALIGN;
-    return llmq::launch_gemm_tn(A, fmtA, B, fmtB, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, d_amax_c,
+    return llmq::launch_gemm_tn(A, fmtA, B, fmtB, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, d_amax_c, false,
                                 static_cast<hipStream_t>(stream), num_cus());
 }
 
@@ -132,10 +136,13 @@ int llmq_fp8_linear_fwd(const void* X, const void* W, int64_t M, int64_t N, int6
     const WsLayout l = ws_layout(M, N, K);
     uint8_t* base = static_cast<uint8_t*>(ws);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (qx && (st = llmq::launch_quantize(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, base + l.xqt, s))) return st;
-    if (qw && (st = llmq::launch_quantize(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, base + l.wqt, s))) return st;
+    // the first quantize kernel of the call also clears the absmax accumulator of the GEMM
+    unsigned* zero = reinterpret_cast<unsigned*>(d_amax_y);
+    const bool zeroed = zero && (qx || qw);
+    if (qx && (st = llmq::launch_quantize(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, base + l.xqt, zero, s))) return st;
+    if (qw && (st = llmq::launch_quantize(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, base + l.wqt, qx ? nullptr : zero, s))) return st;
     return llmq::launch_gemm_tn(base + l.xq, LLMQ_E4M3, base + l.wq, LLMQ_E4M3, M, N, K, d_scale_x, d_scale_w,
-                                Y, 0, d_amax_y, s, num_cus());
+                                Y, 0, d_amax_y, zeroed, s, num_cus());
 }
 
 int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, int64_t K,
@@ -153,11 +160,13 @@ int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, i
     const WsLayout l = ws_layout(M, N, K);
     uint8_t* base = static_cast<uint8_t*>(ws);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (qd && (st = llmq::launch_quantize(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, base + l.dyqt, s))) return st;
-    if (qw && (st = llmq::launch_quantize(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, base + l.wqt, s))) return st;
+    unsigned* zero = reinterpret_cast<unsigned*>(d_amax_dx);
+    const bool zeroed = zero && (qd || qw);
+    if (qd && (st = llmq::launch_quantize(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, base + l.dyqt, zero, s))) return st;
+    if (qw && (st = llmq::launch_quantize(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, base + l.wqt, qd ? nullptr : zero, s))) return st;
     // dX[m,k] = sum_n dYq[m,n] * Wq_t[k,n]
     return llmq::launch_gemm_tn(base + l.dyq, fmt_dy, base + l.wqt, LLMQ_E4M3, M, K, N, d_scale_dy, d_scale_w,
-                                dX, 0, d_amax_dx, s, num_cus());
+                                dX, 0, d_amax_dx, zeroed, s, num_cus());
 }
 
 int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, int64_t K,
@@ -175,11 +184,11 @@ int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, i
     const WsLayout l = ws_layout(M, N, K);
     uint8_t* base = static_cast<uint8_t*>(ws);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (qd && (st = llmq::launch_quantize(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, base + l.dyqt, s))) return st;
-    if (qx && (st = llmq::launch_quantize(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, base + l.xqt, s))) return st;
+    if (qd && (st = llmq::launch_quantize(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, base + l.dyqt, nullptr, s))) return st;
+    if (qx && (st = llmq::launch_quantize(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, base + l.xqt, nullptr, s))) return st;
     // dW[n,k] = sum_m dYq_t[n,m] * Xq_t[k,m]
     return llmq::launch_gemm_tn(base + l.dyqt, fmt_dy, base + l.xqt, LLMQ_E4M3, N, K, M, d_scale_dy, d_scale_x,
-                                dW, accumulate, nullptr, s, num_cus());
+                                dW, accumulate, nullptr, false, s, num_cus());
 }
 
 }  // extern "C"

@@ -4,23 +4,31 @@
 //
 //   C[r,c] = bf16( (sum_t A[r,t] * B[c,t]) / (sA * sB) ),   A [R,T] fp8, B [Cn,T] fp8.
 //
-// Tuned kernel (R, Cn multiples of 256; T a multiple of 128)
-//   - one workgroup of 4 wavefronts per 256x256 output tile, each wavefront owns 128x128 of it
-//     as 4x4 blocks of v_mfma_f32_32x32x64_f8f6f4 (fp32 accumulators, 256 registers per lane);
-//   - K advances 128 bytes per step; the A and B slabs (256 rows x 128 B each) go from global memory
-//     straight into LDS with buffer_load ... lds (16 bytes per lane, no VGPR staging), double
-//     buffered: 2 x 64 KB of the 160 KB LDS;
-//   - LDS rows are 128 B; the 16-byte chunk index is XOR-ed with (row & 7), applied on the global
-//     side of the load, so that the ds_read_b128 fragment reads of 8 consecutive rows hit all banks;
+// Tuned kernel (template on the wave tile NI x NJ in units of 32: workgroup tile BM x BN with
+// BM = 64 NI, BN = 64 NJ, both in {128, 192, 256}; R % BM == 0, Cn % BN == 0, T % 128 == 0)
+//   - one workgroup of 4 wavefronts (2 x 2) per output tile, one workgroup per CU; a wavefront owns
+//     NI x NJ blocks of v_mfma_f32_32x32x64_f8f6f4 with fp32 accumulators (256 registers per lane
+//     at 4 x 4);
+//   - K advances 128 bytes per step; the A and B slabs (BM / BN rows x 128 B) go from global memory
+//     straight into LDS with buffer_load ... lds (16 bytes per lane, no VGPR staging), double buffered;
+//   - LDS rows are 128 B; the 16-byte chunk index is XOR-ed with (row >> 1) & 7, applied on the
+//     global side of the load, so that ds_read_b128 fragment reads of 16 consecutive rows spread
+//     over all 64 banks;
 //   - the order of the contraction index inside one MFMA does not matter as long as A and B use
 //     the same order, so every lane simply reads 32 contiguous bytes of its row;
+//   - every step is software pipelined in two halves: the MFMAs of one 64-byte half run while the
+//     fragments of the next half are read and the slab after next is requested; one barrier per step;
 //   - the MFMA takes the B rows as its first operand, which leaves every lane with 4 consecutive
-//     output columns of one row: the epilogue de-scales in fp32, rounds to BF16 with the hardware
-//     conversion and stores 8 bytes per lane; the output absmax is taken on the rounded BF16 bits;
+//     output columns of one row; the epilogue de-scales in fp32, rounds to BF16 with the hardware
+//     conversion, takes the output absmax on the rounded bits, stages the wave's quadrant in LDS
+//     and stores full row segments, 16 bytes per lane;
 //   - workgroup ids are dealt round-robin to the 8 XCDs by the hardware, so ids are remapped to give
-//     each XCD (own L2) a contiguous range of tiles, walked in bands 8 tile-rows high.
+//     each XCD (own L2) a contiguous range of tiles, walked in bands 8 tile-rows high;
+//   - the host picks NI x NJ per problem so that the tiles fill the 256 CUs in whole rounds.
 // Generic kernel: any shape, one wavefront per 16x16 outputs, guarded loads; slow, for tests and
 // odd sizes.
+#include <stdlib.h>
+
 #include "llmq_device.h"
 #include "llmq_kernels.h"
 
@@ -29,9 +37,8 @@ namespace llmq {
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int BM = 256, BN = 256, BK = 128;
+constexpr int BK = 128;
 constexpr int kGemmThreads = 256;
-constexpr int kSlabBytes = BM * BK;                 // 32 KB per operand per stage
 constexpr int kXcds = 8;
 constexpr int kBandRows = 8;
 
@@ -67,20 +74,12 @@ __device__ inline bool tile_of_block(int pid, int tiles_r, int tiles_c, int& tr,
 // MFMA scheduling masks of __builtin_amdgcn_sched_group_barrier
 constexpr int kSchedMfma = 0x008, kSchedVmemRead = 0x020, kSchedDsRead = 0x100;
 
-template <int FA, int FB>
-__device__ inline void mma_4x4(v16f (&acc)[4][4], const v8i (&a)[4], const v8i (&b)[4]) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[i][j], FB, FA, 0, 0, 0, 0);
-}
-
 // Tuning knobs of the tuned kernel.
 struct GemmTuning {
     // K steps ahead of the direct-to-LDS loads at which each wave touches one dword per 128-byte
-    // line of its share of the slabs, to pull them into L2 early (0 = no touching).
-    static constexpr int kTouchAhead = 2;
+    // line of its share of the slabs, to pull them into L2 early (0 = no touching).  Measured
+    // round-robin against 0 on MI355X: no gain on the block shapes, a loss on large squares.
+    static constexpr int kTouchAhead = 0;
     // Development aid: a tuning struct with kProfile = true also provides
     //   static __device__ void record(int block, int slot, long long value)
     // and gets cycle stamps of the phases of wave 0 of every workgroup.
@@ -103,18 +102,45 @@ __device__ inline void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <int FA, int FB, class V = GemmTuning>
-__global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_256_kernel(
+template <int FA, int FB, int NI, int NJ>
+__device__ inline void mma_block(v16f (&acc)[NI][NJ], const v8i (&a)[NI], const v8i (&b)[NJ]) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[i][j], FB, FA, 0, 0, 0, 0);
+}
+
+// Interleave NM MFMAs with ND LDS reads (all within the first half of the MFMAs, so that they have
+// landed when the MFMAs end) and NV global loads (spread over all MFMAs).
+template <int NM, int ND, int NV, int SYNC, int M = 0>
+__device__ inline void interleave() {
+    if constexpr (M < NM) {
+        constexpr int kHalf = (NM + 1) / 2;
+        constexpr int kDsPer = (ND + kHalf - 1) / kHalf;
+        constexpr int kVmPer = (NV + NM - 1) / NM;
+        constexpr int kDsLeft = ND - M * kDsPer, kVmLeft = NV - M * kVmPer;
+        __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, SYNC);
+        if constexpr (kDsLeft > 0) __builtin_amdgcn_sched_group_barrier(kSchedDsRead, kDsLeft < kDsPer ? kDsLeft : kDsPer, SYNC);
+        if constexpr (kVmLeft > 0) __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, kVmLeft < kVmPer ? kVmLeft : kVmPer, SYNC);
+        interleave<NM, ND, NV, SYNC, M + 1>();
+    }
+}
+
+template <int FA, int FB, int NI, int NJ, class V = GemmTuning>
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ C,
     int Cn, int T, const float* __restrict__ d_sA, const float* __restrict__ d_sB,
     int accumulate, unsigned* __restrict__ amax_bits, int tiles_r, int tiles_c) {
+    constexpr int BM = 64 * NI, BN = 64 * NJ;
+    constexpr int kSlabA = BM * BK, kSlabB = BN * BK;
     // One array per stage and operand: distinct LDS objects let the compiler see that the
     // direct-to-LDS loads of one stage do not alias the fragment reads of the other, so it does
     // not make the reads wait for the loads in flight.
-    __shared__ __attribute__((aligned(1024))) uint8_t ldsA0[kSlabBytes];
-    __shared__ __attribute__((aligned(1024))) uint8_t ldsB0[kSlabBytes];
-    __shared__ __attribute__((aligned(1024))) uint8_t ldsA1[kSlabBytes];
-    __shared__ __attribute__((aligned(1024))) uint8_t ldsB1[kSlabBytes];
+    __shared__ __attribute__((aligned(1024))) uint8_t ldsA0[kSlabA];
+    __shared__ __attribute__((aligned(1024))) uint8_t ldsB0[kSlabB];
+    __shared__ __attribute__((aligned(1024))) uint8_t ldsA1[kSlabA];
+    __shared__ __attribute__((aligned(1024))) uint8_t ldsB1[kSlabB];
     __shared__ unsigned s_amax[kGemmThreads / kWave];
     int tr, tc;
     if (!tile_of_block(blockIdx.x, tiles_r, tiles_c, tr, tc)) return;   // uniform over the workgroup
@@ -132,39 +158,42 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_256_kernel(
     };
     stamp(0);
 
-    // ---- global -> LDS: one instruction moves 8 rows x 128 B; wave w moves rows [64w, 64w+64) of A and B
+    // ---- global -> LDS: one instruction moves 8 rows x 128 B.  Wave w moves rows [16 NI w, 16 NI (w+1))
+    // of the A slab with 2 NI instructions and rows [16 NJ w, ...) of the B slab with 2 NJ.
+    // Instruction j covers rows 8 j + (lane >> 3) of the wave's share; the swizzle of those rows only
+    // depends on the parity of j (the share starts at a multiple of 16 rows).
     const __amdgpu_buffer_rsrc_t rsA = make_rsrc(A + (size_t)tr * BM * T, (unsigned)((size_t)BM * T));
     const __amdgpu_buffer_rsrc_t rsB = make_rsrc(B + (size_t)tc * BN * T, (unsigned)((size_t)BN * T));
-    // Instruction j of a wave covers rows 64*wave + 8*j + (lane >> 3); the swizzle of those rows only
-    // depends on the parity of j.
     constexpr int kSw = V::kSwizzleShift;
     const int ld_row = lane >> 3;                                   // row inside the group of 8
     const int ld_voff0 = ld_row * T + (((lane & 7) ^ ((ld_row >> kSw) & 7)) << 4);
     const int ld_voff1 = ld_row * T + (((lane & 7) ^ (((8 + ld_row) >> kSw) & 7)) << 4);
-    const int ld_soff = wave * 64 * T;
+    const int ld_soffA = wave * 16 * NI * T, ld_soffB = wave * 16 * NJ * T;
     auto issue_loads = [&](uint8_t* slabA, uint8_t* slabB, int k0) {
-        uint8_t* sa = slabA + wave * 64 * BK;
-        uint8_t* sb = slabB + wave * 64 * BK;
+        uint8_t* sa = slabA + wave * 16 * NI * BK;
+        uint8_t* sb = slabB + wave * 16 * NJ * BK;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < 2 * (NI > NJ ? NI : NJ); ++j) {
             const int voff = (j & 1) ? ld_voff1 : ld_voff0;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_void*)(sa + j * 8 * BK), 16, voff, ld_soff + k0 + j * 8 * T, 0, 0);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_void*)(sb + j * 8 * BK), 16, voff, ld_soff + k0 + j * 8 * T, 0, 0);
+            if (j < 2 * NI)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_void*)(sa + j * 8 * BK), 16, voff, ld_soffA + k0 + j * 8 * T, 0, 0);
+            if (j < 2 * NJ)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_void*)(sb + j * 8 * BK), 16, voff, ld_soffB + k0 + j * 8 * T, 0, 0);
         }
     };
+    constexpr int kLoadsPerStep = 2 * (NI + NJ);
 
     // ---- LDS -> registers: lane reads 32 contiguous bytes (two swizzled 16-byte chunks) of its row
     const int fr_row = lane & 31;
     const int fr_half = lane >> 5;                                  // which 32 bytes of the 64-byte K half
     const int swz = (fr_row >> kSw) & 7;                            // same for every row this lane reads
-    // byte offsets inside a slab for K-half 0 and 1, first and second chunk
-    const int offA = (wr * 128 + fr_row) * BK, offB = (wc * 128 + fr_row) * BK;
+    const int offA = (wr * 32 * NI + fr_row) * BK, offB = (wc * 32 * NJ + fr_row) * BK;
     const int ch00 = ((fr_half * 2) ^ swz) << 4, ch01 = ((fr_half * 2 + 1) ^ swz) << 4;
     const int ch10 = ((4 + fr_half * 2) ^ swz) << 4, ch11 = ((4 + fr_half * 2 + 1) ^ swz) << 4;
-    auto read_frags = [&](const uint8_t* slab, int off, int ks, v8i (&f)[4]) {
+    auto read_frags = [&](const uint8_t* slab, int off, int ks, auto& f) {
         const int c0 = ks ? ch10 : ch00, c1 = ks ? ch11 : ch01;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < (int)(sizeof(f) / sizeof(f[0])); ++i) {
             const uint8_t* p = slab + off + i * 32 * BK;
             v4i lo = *reinterpret_cast<const v4i*>(p + c0);
             v4i hi = *reinterpret_cast<const v4i*>(p + c1);
@@ -172,71 +201,57 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_256_kernel(
         }
     };
 
-    v16f acc[4][4];
+    v16f acc[NI][NJ];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    v8i a0[4], b0[4], a1[4], b1[4];        // fragment sets of the two 64-byte halves of a K step
+    v8i a0[NI], b0[NJ], a1[NI], b1[NJ];    // fragment sets of the two 64-byte halves of a K step
     const int nk = T / BK;
 
-    // L2 touch loads: lane l of wave w reads the first dword of row 64w + l of a slab still V::kTouchAhead
-    // steps ahead of the direct-to-LDS loads.  All CUs of an XCD walk K in lock-step, so without this
-    // every slab is first requested only ~1.5 steps before it is needed, less than an L2 miss takes.
+    // L2 touch loads: lane l of wave w reads the first dword of row l of the wave's share of a slab
+    // still V::kTouchAhead steps ahead of the direct-to-LDS loads.  All CUs of an XCD walk K in
+    // lock-step, so without this every slab is first requested only ~1.5 steps before it is needed,
+    // less than an L2 miss takes.
     constexpr int kTouch = V::kTouchAhead;
-    const int touch_voff = lane * T;
+    constexpr int kOutOfRange = 0x7FFFFF00;
+    const int touch_voffA = lane < 16 * NI ? lane * T : kOutOfRange;
+    const int touch_voffB = lane < 16 * NJ ? lane * T : kOutOfRange;
     int touchA[2] = {0, 0}, touchB[2] = {0, 0};   // results are only kept so that the loads stay tracked
     int touch_sink = 0;
 
     // One K step on the stage (curA, curB) while the other stage (nxtA, nxtB) is being filled:
-    //   first half : read the second-half fragments            | 16 MFMAs on the first-half fragments
+    //   first half : read the second-half fragments            | MFMAs on the first-half fragments
     //   barrier    : the next slab has landed, everybody is done reading the current one
     //   second half: start loading slab kt+2 into the current stage, read the first-half
-    //                fragments of slab kt+1                     | 16 MFMAs on the second-half fragments
+    //                fragments of slab kt+1                     | MFMAs on the second-half fragments
     // Loads that would start beyond the last slab are pointed outside the buffer range instead:
-    // the hardware then fetches nothing, and the stage they would fill is never read.
-    constexpr int kOutOfRange = 0x7FFFFF00;
+    // the hardware then fetches nothing (LDS receives zeros), and that stage is never used.
     auto k_step = [&](uint8_t* curA, uint8_t* curB, uint8_t* nxtA, uint8_t* nxtB, int kt, int parity) {
         read_frags(curA, offA, 1, a1);
         read_frags(curB, offB, 1, b1);
-        mma_4x4<FA, FB>(acc, a0, b0);
-        // fragment reads ride along with the first 8 MFMAs, so that they have landed by the 16th
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(kSchedMfma, 8, 0);
-        // the 16 direct-to-LDS loads of the previous step must have landed; its two touch loads, issued
+        mma_block<FA, FB, NI, NJ>(acc, a0, b0);
+        interleave<NI * NJ, kLoadsPerStep, 0, 0>();
+        // the direct-to-LDS loads of the previous step must have landed; its two touch loads, issued
         // after them, may still be in flight
         if constexpr (kTouch > 0) wait_vmcnt<2>(); else wait_vmcnt<0>();
         lds_barrier();
         __builtin_amdgcn_sched_barrier(0);
         issue_loads(curA, curB, kt + 2 < nk ? (kt + 2) * BK : kOutOfRange);
-        read_frags(nxtA, offA, 0, a0);          // past the last slab this reads stale bytes that are never used
+        read_frags(nxtA, offA, 0, a0);          // past the last slab this reads bytes that are never used
         read_frags(nxtB, offB, 0, b0);
-        mma_4x4<FA, FB>(acc, a1, b1);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 1);
-            __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 1);
-            __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, 1, 1);
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 1);
-            __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, 1, 1);
-        }
+        mma_block<FA, FB, NI, NJ>(acc, a1, b1);
+        interleave<NI * NJ, kLoadsPerStep, kLoadsPerStep, 1>();
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (kTouch > 0) {
             const int kp = kt + 2 + kTouch;
-            const int off = kp < nk ? ld_soff + kp * BK : kOutOfRange;
+            const int off = kp < nk ? kp * BK : kOutOfRange;
             touch_sink ^= touchA[parity] ^ touchB[parity];          // issued two steps ago: long landed
-            touchA[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voff, off, 0);
-            touchB[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voff, off, 0);
+            touchA[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, ld_soffA + off, 0);
+            touchB[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, ld_soffB + off, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -246,8 +261,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_256_kernel(
     lds_barrier();
     issue_loads(ldsA1, ldsB1, nk > 1 ? BK : kOutOfRange);
     if constexpr (kTouch > 0) {                   // keep "two touch loads are the newest" true from the start
-        touchA[1] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voff, 2 < nk ? ld_soff + 2 * BK : kOutOfRange, 0);
-        touchB[1] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voff, 2 < nk ? ld_soff + 2 * BK : kOutOfRange, 0);
+        const int off = 2 < nk ? 2 * BK : kOutOfRange;
+        touchA[1] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, ld_soffA + off, 0);
+        touchB[1] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, ld_soffB + off, 0);
     }
     read_frags(ldsA0, offA, 0, a0);
     read_frags(ldsB0, offB, 0, b0);
@@ -267,21 +283,23 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_256_kernel(
 
     // ---- epilogue.  Per 32x32 block a lane holds 4 groups of 4 consecutive columns of row (lane % 32).
     // Storing those 8-byte pieces directly scatters every store over 32 rows; instead each wave
-    // stages its 128x128 BF16 quadrant (32 KB) in one of the four slabs, which nobody reads any more,
-    // and writes it out as full 256-byte row segments, 16 bytes per lane.  Rows are 256 B in LDS with
-    // the 16-byte slot index XOR-ed with (row & 15), so both the 8-byte writes and the 16-byte reads
-    // spread over all banks.  The region is private to the wave and LDS executes a wave's accesses
-    // in order, so no barrier is needed.
+    // stages its quadrant (32 NI rows x 32 NJ BF16 columns, at most 32 KB) in one of the four slabs,
+    // which nobody reads any more, and writes it out as full row segments, 16 bytes per lane.  The
+    // 16-byte slot index of a staged row is rotated by the row number, so that the 8-byte writes of
+    // 32 rows and the 16-byte reads spread over the banks.  The region is private to the wave and LDS
+    // executes a wave's accesses in order, so no barrier is needed.
     const float inv_a = 1.0f / *d_sA, inv_b = 1.0f / *d_sB;
     unsigned mag = 0;
     if (!accumulate) {
+        constexpr int kSlots = 4 * NJ;                                       // 16-byte slots per staged row
+        constexpr int kPitch = 16 * kSlots;
         uint8_t* stage = wave == 0 ? ldsA0 : wave == 1 ? ldsB0 : wave == 2 ? ldsA1 : ldsB1;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < NI; ++i) {
             const int row = i * 32 + fr_row;
-            uint8_t* srow = stage + row * 256;
+            uint8_t* srow = stage + row * kPitch;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < NJ; ++j) {
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int col = j * 32 + g * 8 + fr_half * 4;            // multiple of 4
@@ -290,27 +308,28 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_256_kernel(
                     for (int e = 0; e < 4; ++e) y[e] = acc[i][j][4 * g + e] * inv_a * inv_b;
                     bf16x4 o = __builtin_convertvector(y, bf16x4);
                     mag = bf16_mag_max4(mag, o);
-                    *reinterpret_cast<bf16x4*>(srow + ((((col >> 3) ^ (row & 15)) << 4) | ((col & 7) << 1))) = o;
+                    const int slot = ((col >> 3) + row) % kSlots;
+                    *reinterpret_cast<bf16x4*>(srow + ((slot << 4) | ((col & 7) << 1))) = o;
                 }
             }
         }
-        const int slot = lane & 15, sub = lane >> 4;                          // 16 lanes per row, 4 rows per pass
-        uint16_t* cbase = C + (size_t)(tr * BM + wr * 128) * Cn + tc * BN + wc * 128 + slot * 8;
-#pragma unroll 8
-        for (int it = 0; it < 32; ++it) {
-            const int row = it * 4 + sub;
-            v4u v = *reinterpret_cast<const v4u*>(stage + row * 256 + ((slot ^ (row & 15)) << 4));
-            *reinterpret_cast<v4u*>(cbase + (size_t)row * Cn) = v;
+        uint16_t* cbase = C + (size_t)(tr * BM + wr * 32 * NI) * Cn + tc * BN + wc * 32 * NJ;
+        constexpr int kPieces = 32 * NI * kSlots;                            // 16-byte pieces of the quadrant
+#pragma unroll 4
+        for (int p = lane; p < kPieces; p += kWave) {
+            const int row = p / kSlots, sl = p % kSlots;
+            v4u v = *reinterpret_cast<const v4u*>(stage + row * kPitch + (((sl + row) % kSlots) << 4));
+            *reinterpret_cast<v4u*>(cbase + (size_t)row * Cn + sl * 8) = v;
         }
     } else {
         // BF16 accumulation needs the old value before the single rounding: straight from the registers.
-        const int row_base = tr * BM + wr * 128 + fr_row;
-        const int col_base = tc * BN + wc * 128 + fr_half * 4;
+        const int row_base = tr * BM + wr * 32 * NI + fr_row;
+        const int col_base = tc * BN + wc * 32 * NJ + fr_half * 4;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < NI; ++i) {
             uint16_t* crow = C + (size_t)(row_base + i * 32) * Cn + col_base;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < NJ; ++j) {
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     uint16_t* dst = crow + j * 32 + g * 8;
@@ -413,36 +432,82 @@ __global__ void gemm_amax_reset_kernel(unsigned* amax_bits) {
     if (threadIdx.x == 0 && blockIdx.x == 0) *amax_bits = 0u;
 }
 
+// ---- host side: tile choice and launch
+struct TileChoice {
+    int ni, nj;       // 0, 0: no tuned tile divides the problem, use the generic kernel
+};
+
+// Picks the wave tile NI x NJ (workgroup tile 64 NI x 64 NJ) that finishes soonest under a simple
+// model: every CU works through its share of the tiles, a tile costs NI * NJ MFMA blocks per K step
+// divided by the measured efficiency of that shape relative to 4 x 4 (smaller tiles read more LDS
+// and L2 bytes per MFMA; 2 x 2 tiles fit two workgroups per CU, which hide each other's stalls).
+static TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus) {
+    static const float eff[5][5] = {{0, 0, 0, 0, 0}, {0, 0, 0, 0, 0}, {0, 0, 0.90f, 0.74f, 0.77f},
+                                    {0, 0, 0.74f, 0.70f, 0.83f}, {0, 0, 0.77f, 0.83f, 1.00f}};
+    TileChoice best{0, 0};
+    if (T % BK != 0 || T >= (1ll << 23)) return best;
+    // Override for tests and tuning: LLMQ_GEMM_TILE=IxJ forces that wave tile where it divides the problem.
+    if (const char* force = getenv("LLMQ_GEMM_TILE")) {
+        const int ni = force[0] - '0', nj = force[0] && force[1] ? force[2] - '0' : 0;
+        if (ni >= 2 && ni <= 4 && nj >= 2 && nj <= 4 && R % (64 * ni) == 0 && C % (64 * nj) == 0) return TileChoice{ni, nj};
+    }
+    double best_cost = 0;
+    for (int ni = 4; ni >= 2; --ni)
+        for (int nj = 4; nj >= 2; --nj) {
+            if (R % (64 * ni) != 0 || C % (64 * nj) != 0) continue;
+            const int64_t tiles = (R / (64 * ni)) * (C / (64 * nj));
+            if (tiles >= (1ll << 30)) continue;
+            const int per_cu = (ni == 2 && nj == 2) ? 2 : 1;          // workgroups resident per CU
+            const int64_t slots = (int64_t)num_cus * per_cu;
+            const int64_t rounds = (tiles + slots - 1) / slots;
+            const double cost = (double)rounds * per_cu * ni * nj / eff[ni][nj];
+            if (best.ni == 0 || cost < best_cost * 0.999) { best = {ni, nj}; best_cost = cost; }
+        }
+    return best;
+}
+
+template <int FA, int FB, int NI, int NJ>
+static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
+                        const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
+                        hipStream_t stream) {
+    const int tiles_r = (int)(R / (64 * NI)), tiles_c = (int)(C / (64 * NJ));
+    const int nt = tiles_r * tiles_c;
+    const int grid = ((nt + kXcds - 1) / kXcds) * kXcds;
+    hipLaunchKernelGGL((gemm_tn_tile_kernel<FA, FB, NI, NJ>), dim3(grid), dim3(kGemmThreads), 0, stream,
+                       A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, accumulate, amax,
+                       tiles_r, tiles_c);
+}
+
 template <int FA, int FB>
 static void launch_one(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
                        const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
-                       hipStream_t stream) {
-    const bool tuned = R % BM == 0 && C % BN == 0 && T % BK == 0 &&
-                       (size_t)BM * T < (1ull << 31) && R * T < (1ll << 40) && C * T < (1ll << 40);
-    if (tuned) {
-        const int tiles_r = (int)(R / BM), tiles_c = (int)(C / BN);
-        const int nt = tiles_r * tiles_c;
-        const int grid = ((nt + kXcds - 1) / kXcds) * kXcds;
-        hipLaunchKernelGGL((gemm_tn_256_kernel<FA, FB>), dim3(grid), dim3(kGemmThreads), 0, stream,
-                           A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB,
-                           accumulate, amax, tiles_r, tiles_c);
-    } else {
-        dim3 grid((unsigned)((C + 31) / 32), (unsigned)((R + 31) / 32));
-        hipLaunchKernelGGL((gemm_tn_generic_kernel<FA, FB>), grid, dim3(256), 0, stream,
-                           A, B, reinterpret_cast<uint16_t*>(c), R, C, T, sA, sB, accumulate, amax);
+                       hipStream_t stream, int num_cus) {
+    const TileChoice tc = choose_tile(R, C, T, num_cus);
+#define LLMQ_TILE_CASE(I, J)                                                                      \
+    case I * 8 + J:                                                                               \
+        launch_tile<FA, FB, I, J>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream);            \
+        return;
+    switch (tc.ni * 8 + tc.nj) {
+        LLMQ_TILE_CASE(4, 4) LLMQ_TILE_CASE(4, 3) LLMQ_TILE_CASE(4, 2)
+        LLMQ_TILE_CASE(3, 4) LLMQ_TILE_CASE(3, 3) LLMQ_TILE_CASE(3, 2)
+        LLMQ_TILE_CASE(2, 4) LLMQ_TILE_CASE(2, 3) LLMQ_TILE_CASE(2, 2)
+        default: break;
     }
+#undef LLMQ_TILE_CASE
+    dim3 grid((unsigned)((C + 31) / 32), (unsigned)((R + 31) / 32));
+    hipLaunchKernelGGL((gemm_tn_generic_kernel<FA, FB>), grid, dim3(256), 0, stream,
+                       A, B, reinterpret_cast<uint16_t*>(c), R, C, T, sA, sB, accumulate, amax);
 }
 
 int launch_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64_t R, int64_t C,
                    int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16,
-                   int accumulate, float* d_amax_c, hipStream_t stream, int num_cus) {
-    (void)num_cus;
+                   int accumulate, float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus) {
     unsigned* amax = reinterpret_cast<unsigned*>(d_amax_c);
-    if (amax) hipLaunchKernelGGL(gemm_amax_reset_kernel, dim3(1), dim3(64), 0, stream, amax);
-    if (fmtA == 0 && fmtB == 0) launch_one<0, 0>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream);
-    else if (fmtA == 1 && fmtB == 0) launch_one<1, 0>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream);
-    else if (fmtA == 0 && fmtB == 1) launch_one<0, 1>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream);
-    else launch_one<1, 1>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream);
+    if (amax && !amax_is_zeroed) hipLaunchKernelGGL(gemm_amax_reset_kernel, dim3(1), dim3(64), 0, stream, amax);
+    if (fmtA == 0 && fmtB == 0) launch_one<0, 0>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus);
+    else if (fmtA == 1 && fmtB == 0) launch_one<1, 0>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus);
+    else if (fmtA == 0 && fmtB == 1) launch_one<0, 1>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus);
+    else launch_one<1, 1>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus);
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 

@@ -7,12 +7,15 @@
 namespace llmq {
 
 // Each returns 0 or LLMQ_ERR_DEVICE (-6).  Arguments are validated by the callers in api.hip.
-int launch_amax(const void* x, size_t n, int fmt, float* d_amax, float* d_scale, hipStream_t stream,
-                int num_cus);
+constexpr int kAmaxMaxPartials = 1024;      // the absmax workspace holds one 32-bit word per block
+int launch_amax(const void* x, size_t n, int fmt, float* d_amax, float* d_scale, void* ws,
+                hipStream_t stream, int num_cus);
+// zero_word: if not NULL, one 32-bit word the kernel also clears (the absmax accumulator of the GEMM
+// that follows in the same call, which saves a launch).
 int launch_quantize(const void* x, int64_t rows, int64_t cols, const float* d_scale, int fmt,
-                    uint8_t* q, uint8_t* q_t, hipStream_t stream);
+                    uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream);
 int launch_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64_t R, int64_t C,
                    int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16,
-                   int accumulate, float* d_amax_c, hipStream_t stream, int num_cus);
+                   int accumulate, float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus);
 
 }  // namespace llmq

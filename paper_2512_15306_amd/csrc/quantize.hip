@@ -16,12 +16,19 @@ namespace llmq {
 
 constexpr int kQThreads = 256;
 constexpr int kPatchRows = 16;
-constexpr int kPatchCols = 8;
-constexpr int kLanesR = 8;                               // lanes of a wave stacked along rows
-constexpr int kLanesC = kWave / kLanesR;                 // lanes of a wave side by side
-constexpr int kWaveRows = kPatchRows * kLanesR;          // 128
-constexpr int kWaveCols = kPatchCols * kLanesC;          // 64
-constexpr int kBlockCols = kWaveCols * (kQThreads / kWave);   // 256: the four waves sit side by side
+
+// Shape of the work of one wavefront: every lane owns a patch of 16 rows x kPatchCols columns,
+// kLanesR lanes are stacked along rows (16 * kLanesR rows per wave, which is also the length in
+// bytes of the contiguous pieces written to the transposed tensor) and 64 / kLanesR lanes sit side
+// by side along columns.  The four waves of a workgroup sit side by side along columns.
+struct QuantTuning {
+    static constexpr int kPatchCols = 8;     // 8 or 16 (one or two 16-byte loads per row)
+    static constexpr int kLanesR = 8;
+    static constexpr bool kLoadsFirst = true;    // issue every load of the patch before the first conversion
+    static constexpr bool kNtLoad = true;        // streaming hint on the loads
+    static constexpr bool kNtStore = false;      // streaming hint on the stores
+    static constexpr bool kBlocksDownRows = true;    // consecutive workgroups walk down rows instead of along columns
+};
 
 template <int FMT>
 __device__ inline unsigned cvt_pair(float a, float b, unsigned old, bool high) {
@@ -65,48 +72,70 @@ __device__ inline void transpose4x4_bytes(const unsigned w[4], unsigned o[4]) {
     o[3] = __builtin_amdgcn_perm(t23h, t01h, 0x07060302u);
 }
 
-template <int FMT, bool TRANSPOSE>
+template <int FMT, bool TRANSPOSE, class V = QuantTuning>
 __global__ __launch_bounds__(kQThreads) void quantize_patch_kernel(
     const uint16_t* __restrict__ x, int64_t rows, int64_t cols, const float* __restrict__ d_scale,
-    uint8_t* __restrict__ q, uint8_t* __restrict__ qt) {
+    uint8_t* __restrict__ q, uint8_t* __restrict__ qt, unsigned* __restrict__ zero_word) {
+    if (zero_word && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *zero_word = 0u;
+    constexpr int PC = V::kPatchCols, LR = V::kLanesR, LC = kWave / LR;
+    constexpr int NV = PC / 8;                              // 16-byte loads per row of the patch
+    constexpr int kWaveRows = kPatchRows * LR, kWaveCols = PC * LC;
+    constexpr int kBlockCols = kWaveCols * (kQThreads / kWave);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const int64_t r0 = (int64_t)blockIdx.y * kWaveRows + (lane % kLanesR) * kPatchRows;
-    const int64_t c0 = (int64_t)blockIdx.x * kBlockCols + wave * kWaveCols + (lane / kLanesR) * kPatchCols;
-    if (r0 >= rows || c0 >= cols) return;       // rows % 16 == 0 and cols % 8 == 0: a patch is all in or all out
+    const unsigned brow = V::kBlocksDownRows ? blockIdx.x : blockIdx.y;
+    const unsigned bcol = V::kBlocksDownRows ? blockIdx.y : blockIdx.x;
+    const int64_t r0 = (int64_t)brow * kWaveRows + (lane % LR) * kPatchRows;
+    const int64_t c0 = (int64_t)bcol * kBlockCols + wave * kWaveCols + (lane / LR) * PC;
+    if (r0 >= rows || c0 >= cols) return;       // rows % 16 == 0 and cols % PC == 0: a patch is all in or all out
     const float s = *d_scale;
-    v4u in[kPatchRows];
+    v4u in[kPatchRows][NV];
     const uint16_t* src = x + r0 * cols + c0;
 #pragma unroll
     for (int i = 0; i < kPatchRows; ++i)
-        in[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(src + (int64_t)i * cols));
-    unsigned lo[kPatchRows], hi[kPatchRows];
 #pragma unroll
-    for (int i = 0; i < kPatchRows; ++i) quantize8<FMT>(in[i], s, lo[i], hi[i]);
+        for (int v = 0; v < NV; ++v)
+            in[i][v] = V::kNtLoad ? __builtin_nontemporal_load(reinterpret_cast<const v4u*>(src + (int64_t)i * cols) + v)
+                                       : *(reinterpret_cast<const v4u*>(src + (int64_t)i * cols) + v);
+    if constexpr (V::kLoadsFirst) __builtin_amdgcn_sched_barrier(0);
+    unsigned w[kPatchRows][2 * NV];             // the patch as FP8 bytes: w[row][k] = columns 4k .. 4k+3
+#pragma unroll
+    for (int i = 0; i < kPatchRows; ++i)
+#pragma unroll
+        for (int v = 0; v < NV; ++v) quantize8<FMT>(in[i][v], s, w[i][2 * v], w[i][2 * v + 1]);
     uint8_t* dst = q + r0 * cols + c0;
 #pragma unroll
     for (int i = 0; i < kPatchRows; ++i) {
-        v2u v = {lo[i], hi[i]};
-        __builtin_nontemporal_store(v, reinterpret_cast<v2u*>(dst + (int64_t)i * cols));
+        if constexpr (NV == 1) {
+            v2u v = {w[i][0], w[i][1]};
+            if constexpr (V::kNtStore) __builtin_nontemporal_store(v, reinterpret_cast<v2u*>(dst + (int64_t)i * cols));
+            else *reinterpret_cast<v2u*>(dst + (int64_t)i * cols) = v;
+        } else {
+            v4u v = {w[i][0], w[i][1], w[i][2], w[i][3]};
+            if constexpr (V::kNtStore) __builtin_nontemporal_store(v, reinterpret_cast<v4u*>(dst + (int64_t)i * cols));
+            else *reinterpret_cast<v4u*>(dst + (int64_t)i * cols) = v;
+        }
     }
     if constexpr (TRANSPOSE) {
         // column j of the patch -> 16 consecutive bytes of row (c0 + j) of the transposed tensor
-        unsigned col[kPatchCols][4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            unsigned o[4];
-            transpose4x4_bytes(&lo[4 * t], o);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) col[c][t] = o[c];
-            transpose4x4_bytes(&hi[4 * t], o);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) col[4 + c][t] = o[c];
-        }
         uint8_t* dt = qt + c0 * rows + r0;
 #pragma unroll
-        for (int j = 0; j < kPatchCols; ++j) {
-            v4u v = {col[j][0], col[j][1], col[j][2], col[j][3]};
-            __builtin_nontemporal_store(v, reinterpret_cast<v4u*>(dt + (int64_t)j * rows));
+        for (int k = 0; k < 2 * NV; ++k) {      // four columns at a time
+            unsigned col[4][4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {       // four rows at a time
+                unsigned blk[4] = {w[4 * t][k], w[4 * t + 1][k], w[4 * t + 2][k], w[4 * t + 3][k]};
+                unsigned o[4];
+                transpose4x4_bytes(blk, o);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) col[c][t] = o[c];
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                v4u v = {col[c][0], col[c][1], col[c][2], col[c][3]};
+                if constexpr (V::kNtStore) __builtin_nontemporal_store(v, reinterpret_cast<v4u*>(dt + (int64_t)(4 * k + c) * rows));
+                else *reinterpret_cast<v4u*>(dt + (int64_t)(4 * k + c) * rows) = v;
+            }
         }
     }
 }
@@ -115,7 +144,8 @@ __global__ __launch_bounds__(kQThreads) void quantize_patch_kernel(
 template <int FMT>
 __global__ __launch_bounds__(256) void quantize_generic_kernel(
     const uint16_t* __restrict__ x, int64_t rows, int64_t cols, const float* __restrict__ d_scale,
-    uint8_t* __restrict__ q, uint8_t* __restrict__ qt) {
+    uint8_t* __restrict__ q, uint8_t* __restrict__ qt, unsigned* __restrict__ zero_word) {
+    if (zero_word && blockIdx.x == 0 && threadIdx.x == 0) *zero_word = 0u;
     const int64_t n = rows * cols;
     const float s = *d_scale;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
@@ -129,25 +159,34 @@ __global__ __launch_bounds__(256) void quantize_generic_kernel(
     }
 }
 
+template <class V>
+static void launch_patch(const uint16_t* xb, int64_t rows, int64_t cols, const float* d_scale, int fmt,
+                         uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream) {
+    constexpr int kWaveRows = kPatchRows * V::kLanesR;
+    constexpr int kBlockCols = V::kPatchCols * (kWave / V::kLanesR) * (kQThreads / kWave);
+    const unsigned gc = (unsigned)((cols + kBlockCols - 1) / kBlockCols), gr = (unsigned)((rows + kWaveRows - 1) / kWaveRows);
+    dim3 grid(V::kBlocksDownRows ? gr : gc, V::kBlocksDownRows ? gc : gr);
+    dim3 block(kQThreads);
+    if (fmt == 0) {
+        if (q_t) hipLaunchKernelGGL((quantize_patch_kernel<0, true, V>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word);
+        else hipLaunchKernelGGL((quantize_patch_kernel<0, false, V>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word);
+    } else {
+        if (q_t) hipLaunchKernelGGL((quantize_patch_kernel<1, true, V>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word);
+        else hipLaunchKernelGGL((quantize_patch_kernel<1, false, V>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word);
+    }
+}
+
 int launch_quantize(const void* x, int64_t rows, int64_t cols, const float* d_scale, int fmt,
-                    uint8_t* q, uint8_t* q_t, hipStream_t stream) {
+                    uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream) {
     const uint16_t* xb = reinterpret_cast<const uint16_t*>(x);
-    if (rows % kPatchRows == 0 && cols % kPatchCols == 0) {
-        dim3 grid((unsigned)((cols + kBlockCols - 1) / kBlockCols), (unsigned)((rows + kWaveRows - 1) / kWaveRows));
-        dim3 block(kQThreads);
-        if (fmt == 0) {
-            if (q_t) hipLaunchKernelGGL((quantize_patch_kernel<0, true>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t);
-            else hipLaunchKernelGGL((quantize_patch_kernel<0, false>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t);
-        } else {
-            if (q_t) hipLaunchKernelGGL((quantize_patch_kernel<1, true>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t);
-            else hipLaunchKernelGGL((quantize_patch_kernel<1, false>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t);
-        }
+    if (rows % kPatchRows == 0 && cols % QuantTuning::kPatchCols == 0) {
+        launch_patch<QuantTuning>(xb, rows, cols, d_scale, fmt, q, q_t, zero_word, stream);
     } else {
         int64_t n = rows * cols;
         int64_t blocks = (n + 255) / 256;
         if (blocks > 65536) blocks = 65536;
-        if (fmt == 0) hipLaunchKernelGGL((quantize_generic_kernel<0>), dim3((unsigned)blocks), dim3(256), 0, stream, xb, rows, cols, d_scale, q, q_t);
-        else hipLaunchKernelGGL((quantize_generic_kernel<1>), dim3((unsigned)blocks), dim3(256), 0, stream, xb, rows, cols, d_scale, q, q_t);
+        if (fmt == 0) hipLaunchKernelGGL((quantize_generic_kernel<0>), dim3((unsigned)blocks), dim3(256), 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word);
+        else hipLaunchKernelGGL((quantize_generic_kernel<1>), dim3((unsigned)blocks), dim3(256), 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word);
     }
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }

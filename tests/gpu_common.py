@@ -22,7 +22,8 @@ def np_f32_bits(v) -> int:
 def gpu_amax(x: torch.Tensor, fmt: int, want_scale=True):
     a = torch.full((1,), -1.0, device=x.device, dtype=torch.float32)
     s = torch.full((1,), -1.0, device=x.device, dtype=torch.float32) if want_scale else None
-    llmq.llmq_amax(x, fmt, a, s)
+    ws = torch.full((llmq.llmq_amax_workspace_bytes(),), 0xFF, device=x.device, dtype=torch.uint8)   # garbage on entry
+    llmq.llmq_amax(x, fmt, a, s, ws)
     return a, s
 
 

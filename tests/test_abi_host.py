@@ -44,12 +44,16 @@ def test_argument_errors_are_reported_before_any_launch():
     ok_ptr = 0x10000          # never dereferenced: every call below fails validation on the host
     odd_ptr = 0x10008
     n = ctypes.c_size_t
-    assert L.llmq_amax(None, 8, 0, ok_ptr, ok_ptr, None) == -1
-    assert L.llmq_amax(ok_ptr, 8, 0, None, ok_ptr, None) == -1
-    assert L.llmq_amax(ok_ptr, 0, 0, ok_ptr, ok_ptr, None) == -2
-    assert L.llmq_amax(ok_ptr, 8, 2, ok_ptr, ok_ptr, None) == -4
-    assert L.llmq_amax(odd_ptr, 8, 0, ok_ptr, ok_ptr, None) == -3
-    assert L.llmq_amax(ok_ptr, 8, 0, ok_ptr + 2, ok_ptr, None) == -3
+    aw = llmq.llmq_amax_workspace_bytes()
+    assert aw >= 1024
+    assert L.llmq_amax(None, 8, 0, ok_ptr, ok_ptr, ok_ptr, n(aw), None) == -1
+    assert L.llmq_amax(ok_ptr, 8, 0, None, ok_ptr, ok_ptr, n(aw), None) == -1
+    assert L.llmq_amax(ok_ptr, 8, 0, ok_ptr, ok_ptr, None, n(aw), None) == -1
+    assert L.llmq_amax(ok_ptr, 0, 0, ok_ptr, ok_ptr, ok_ptr, n(aw), None) == -2
+    assert L.llmq_amax(ok_ptr, 8, 2, ok_ptr, ok_ptr, ok_ptr, n(aw), None) == -4
+    assert L.llmq_amax(odd_ptr, 8, 0, ok_ptr, ok_ptr, ok_ptr, n(aw), None) == -3
+    assert L.llmq_amax(ok_ptr, 8, 0, ok_ptr + 2, ok_ptr, ok_ptr, n(aw), None) == -3
+    assert L.llmq_amax(ok_ptr, 8, 0, ok_ptr, ok_ptr, ok_ptr, n(aw - 1), None) == -5
     assert L.llmq_quantize_fp8(ok_ptr, 4, 4, None, 0, ok_ptr, ok_ptr, None) == -1
     assert L.llmq_quantize_fp8(ok_ptr, 0, 4, ok_ptr, 0, ok_ptr, ok_ptr, None) == -2
     assert L.llmq_quantize_fp8(ok_ptr, 4, -1, ok_ptr, 0, ok_ptr, ok_ptr, None) == -2
@@ -79,4 +83,4 @@ def test_binding_refuses_cpu_tensors():
     x = torch.zeros(8, dtype=torch.bfloat16)
     a = torch.zeros(1)
     with pytest.raises(ValueError):
-        llmq.llmq_amax(x, 0, a, a)
+        llmq.llmq_amax(x, 0, a, a, torch.zeros(4096, dtype=torch.uint8))

@@ -63,6 +63,25 @@ def test_gemm_tn_within_tolerance(R, C, T, fa, fb):
     assert torch.equal(c2.view(torch.int16), c.view(torch.int16))
 
 
+@pytest.mark.parametrize("tile", ["4x4", "4x3", "4x2", "3x4", "3x3", "3x2", "2x4", "2x3", "2x2"])
+def test_every_tuned_tile_shape(tile, monkeypatch):
+    """Each wave-tile instantiation of the tuned kernel, forced through the tuning override, on a
+    problem of 2 x 3 workgroup tiles with an odd number of K steps, mixed formats, fused absmax."""
+    ni, nj = int(tile[0]), int(tile[2])
+    R, C, T = 2 * 64 * ni, 3 * 64 * nj, 640
+    print("tile %s R=%d C=%d T=%d" % (tile, R, C, T), flush=True)
+    monkeypatch.setenv("LLMQ_GEMM_TILE", tile)
+    A = _rand_codes((R, T), 1, 41 + ni)
+    B = _rand_codes((C, T), 0, 43 + nj)
+    c, am = _run_gemm(A, 1, B, 0, 1.9, 0.7, want_amax=True)
+    monkeypatch.delenv("LLMQ_GEMM_TILE")
+    y, S = oracle.gemm_tn(A, 1, B, 0, 1.9, 0.7)
+    assert_gemm_close(c, y, S, "tile " + tile)
+    assert am.item() == c.float().abs().max().item()
+    c2, _ = _run_gemm(A, 1, B, 0, 1.9, 0.7)          # the shape the library picks by itself: same bytes
+    assert torch.equal(c2.view(torch.int16), c.view(torch.int16))
+
+
 @pytest.mark.parametrize("R,C,T", [(33, 17, 130), (256, 512, 384)])
 def test_gemm_accumulate_in_bf16(R, C, T):
     A = _rand_codes((R, T), 1, 5)
