@@ -76,10 +76,12 @@ constexpr int kSchedMfma = 0x008, kSchedVmemRead = 0x020, kSchedDsRead = 0x100;
 
 // Tuning knobs of the tuned kernel.
 struct GemmTuning {
-    // K steps ahead of the direct-to-LDS loads at which each wave touches one dword per 128-byte
-    // line of its share of the slabs, to pull them into L2 early (0 = no touching).  Measured
-    // round-robin against 0 on MI355X: no gain on the block shapes, a loss on large squares.
-    static constexpr int kTouchAhead = 0;
+    // Whether the kernel contains the L2 touch loads at all (their distance is a run-time argument).
+    static constexpr bool kTouch = true;
+    // One workgroup touches 1 / kTouchShareA of the lines of its A slab and 1 / kTouchShareB of its B
+    // slab: the workgroups that run side by side on an XCD (4 tile columns x 8 tile rows at a time)
+    // share each slab and cover it together.
+    static constexpr int kTouchShareA = 4, kTouchShareB = 8;
     // Development aid: a tuning struct with kProfile = true also provides
     //   static __device__ void record(int block, int slot, long long value)
     // and gets cycle stamps of the phases of wave 0 of every workgroup.
@@ -131,7 +133,7 @@ template <int FA, int FB, int NI, int NJ, class V = GemmTuning>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ C,
     int Cn, int T, const float* __restrict__ d_sA, const float* __restrict__ d_sB,
-    int accumulate, unsigned* __restrict__ amax_bits, int tiles_r, int tiles_c) {
+    int accumulate, unsigned* __restrict__ amax_bits, int tiles_r, int tiles_c, int touch_ahead) {
     constexpr int BM = 64 * NI, BN = 64 * NJ;
     constexpr int kSlabA = BM * BK, kSlabB = BN * BK;
     // One array per stage and operand: distinct LDS objects let the compiler see that the
@@ -212,14 +214,18 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
     v8i a0[NI], b0[NJ], a1[NI], b1[NJ];    // fragment sets of the two 64-byte halves of a K step
     const int nk = T / BK;
 
-    // L2 touch loads: lane l of wave w reads the first dword of row l of the wave's share of a slab
-    // still V::kTouchAhead steps ahead of the direct-to-LDS loads.  All CUs of an XCD walk K in
-    // lock-step, so without this every slab is first requested only ~1.5 steps before it is needed,
-    // less than an L2 miss takes.
-    constexpr int kTouch = V::kTouchAhead;
+    // L2 touch loads: a wave reads the first dword of some rows of a slab that is still touch_ahead
+    // steps ahead of the direct-to-LDS loads (touch_ahead <= 0: nothing is fetched).  All CUs of an
+    // XCD walk K in lock-step, so without this every slab is first requested only ~1.5 steps before
+    // it is needed, less than a miss to HBM takes when the operands are not in the last-level cache.
+    // The workgroup touches rows [g * BM / shareA, (g + 1) * BM / shareA) of the A slab, g = tile
+    // column mod shareA, and likewise of the B slab with the tile row and shareB; each wave takes a quarter.
+    constexpr bool kTouch = V::kTouch;
+    constexpr int kShareA = V::kTouchShareA, kShareB = V::kTouchShareB;
     constexpr int kOutOfRange = 0x7FFFFF00;
-    const int touch_voffA = lane < 16 * NI ? lane * T : kOutOfRange;
-    const int touch_voffB = lane < 16 * NJ ? lane * T : kOutOfRange;
+    constexpr int kRowsA = BM / kShareA / 4, kRowsB = BN / kShareB / 4;     // rows per wave
+    const int touch_voffA = lane < kRowsA ? (((tc % kShareA) * 4 + wave) * kRowsA + lane) * T : kOutOfRange;
+    const int touch_voffB = lane < kRowsB ? (((tr % kShareB) * 4 + wave) * kRowsB + lane) * T : kOutOfRange;
     int touchA[2] = {0, 0}, touchB[2] = {0, 0};   // results are only kept so that the loads stay tracked
     int touch_sink = 0;
 
@@ -237,7 +243,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         interleave<NI * NJ, kLoadsPerStep, 0, 0>();
         // the direct-to-LDS loads of the previous step must have landed; its two touch loads, issued
         // after them, may still be in flight
-        if constexpr (kTouch > 0) wait_vmcnt<2>(); else wait_vmcnt<0>();
+        if constexpr (kTouch) wait_vmcnt<2>(); else wait_vmcnt<0>();
         lds_barrier();
         __builtin_amdgcn_sched_barrier(0);
         issue_loads(curA, curB, kt + 2 < nk ? (kt + 2) * BK : kOutOfRange);
@@ -246,12 +252,12 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         mma_block<FA, FB, NI, NJ>(acc, a1, b1);
         interleave<NI * NJ, kLoadsPerStep, kLoadsPerStep, 1>();
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (kTouch > 0) {
-            const int kp = kt + 2 + kTouch;
-            const int off = kp < nk ? kp * BK : kOutOfRange;
+        if constexpr (kTouch) {
+            const int kp = kt + 2 + touch_ahead;
+            const int off = (touch_ahead > 0 && kp < nk) ? kp * BK : kOutOfRange;
             touch_sink ^= touchA[parity] ^ touchB[parity];          // issued two steps ago: long landed
-            touchA[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, ld_soffA + off, 0);
-            touchB[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, ld_soffB + off, 0);
+            touchA[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, off, 0);
+            touchB[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, off, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -260,10 +266,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
     wait_vmcnt<0>();
     lds_barrier();
     issue_loads(ldsA1, ldsB1, nk > 1 ? BK : kOutOfRange);
-    if constexpr (kTouch > 0) {                   // keep "two touch loads are the newest" true from the start
-        const int off = 2 < nk ? 2 * BK : kOutOfRange;
-        touchA[1] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, ld_soffA + off, 0);
-        touchB[1] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, ld_soffB + off, 0);
+    if constexpr (kTouch) {                       // keep "two touch loads are the newest" true from the start
+        const int off = (touch_ahead > 0 && 2 < nk) ? 2 * BK : kOutOfRange;
+        touchA[1] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, off, 0);
+        touchB[1] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, off, 0);
     }
     read_frags(ldsA0, offA, 0, a0);
     read_frags(ldsB0, offB, 0, b0);
@@ -275,7 +281,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
     }
     if (kt < nk) k_step(ldsA0, ldsB0, ldsA1, ldsB1, kt, 0);
     wait_vmcnt<0>();                               // nothing may still be landing in LDS when the wave ends
-    if constexpr (kTouch > 0) {
+    if constexpr (kTouch) {
         touch_sink ^= touchA[0] ^ touchB[0] ^ touchA[1] ^ touchB[1];
         asm volatile("" ::"v"(touch_sink));
     }
@@ -466,6 +472,12 @@ static TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus) {
     return best;
 }
 
+// Distance of the L2 touch loads in K steps; LLMQ_GEMM_TOUCH overrides it for tuning.
+static int touch_ahead() {
+    if (const char* e = getenv("LLMQ_GEMM_TOUCH")) return atoi(e);
+    return 2;
+}
+
 template <int FA, int FB, int NI, int NJ>
 static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
                         const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
@@ -475,7 +487,7 @@ static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C
     const int grid = ((nt + kXcds - 1) / kXcds) * kXcds;
     hipLaunchKernelGGL((gemm_tn_tile_kernel<FA, FB, NI, NJ>), dim3(grid), dim3(kGemmThreads), 0, stream,
                        A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, accumulate, amax,
-                       tiles_r, tiles_c);
+                       tiles_r, tiles_c, touch_ahead());
 }
 
 template <int FA, int FB>
