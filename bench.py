@@ -22,6 +22,10 @@ if ROOT not in sys.path:
 
 PEAK_FP8_TFLOPS = 5000.0      # MI355X dense FP8 MFMA, published
 PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E, published
+# L2 <-> fabric bytes per GEMM launch (fetched + written, averaged over the step's launches), from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by a plain 1 GiB copy
+# (profiles/bench_config2_gemm_quantize_amax.md); None where not measured.
+MEASURED_GEMM_TRAFFIC_BYTES = {2: 226.0e6}
 
 
 def parse():
@@ -33,6 +37,8 @@ def parse():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--prequantized-w", action="store_true",
                    help="weights quantized once outside the timed region (reused across micro-steps)")
+    p.add_argument("--calibrate-copy", action="store_true",
+                   help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return p.parse_args()
 
 
@@ -79,11 +85,16 @@ def run_step(states, prequantized_w):
 
 
 def run_gemms_only(states):
+    """The three GEMM launches of every linear on the operands the step left in the workspace, through
+    the same entry points as the step (all REUSE flags set: nothing is quantized)."""
     from paper_2512_15306_amd import llmq
     for s in states:
-        llmq.llmq_fp8_gemm_tn(s.view(0), 0, s.view(2), 0, s.sx, s.sw, s.Y, False, s.ay)
-        llmq.llmq_fp8_gemm_tn(s.view(4), 1, s.view(3), 0, s.sd, s.sw, s.dX, False, s.adx)
-        llmq.llmq_fp8_gemm_tn(s.view(5), 1, s.view(1), 0, s.sd, s.sx, s.dW, False, None)
+        M, K, N = s.M, s.K, s.N
+        llmq.llmq_fp8_linear_fwd(None, None, M, N, K, s.sx, s.sw, s.Y, None, s.ws, llmq.REUSE_X | llmq.REUSE_W)
+        llmq.llmq_fp8_linear_dgrad(None, None, M, N, K, s.sd, s.sw, llmq.E5M2, s.dX, None, s.ws,
+                                   llmq.REUSE_DY | llmq.REUSE_W)
+        llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, s.sd, s.sx, llmq.E5M2, s.dW, False, s.ws,
+                                   llmq.REUSE_X | llmq.REUSE_DY)
 
 
 def run_quant_only(states):
@@ -117,7 +128,17 @@ def cpu_baseline(cfg):
     from paper_2512_15306_amd import synth
     li = 1 if len(cfg.linears) > 1 else 0
     lin = cfg.linears[li]
-    Ms = min(cfg.M, max(64, int(2048 * (3072 * 3072) / (lin.K * lin.N))))
+    # size the sample for roughly 15 s on this host: time a 32-row slab of the forward GEMM first
+    import numpy as np
+    probe = np.zeros((32, lin.K), np.uint8)
+    wprobe = np.zeros((lin.N, lin.K), np.uint8)
+    oracle.gemm_tn(probe[:1], 0, wprobe[:8], 0, 1.0, 1.0)      # load the library
+    t0 = time.perf_counter()
+    oracle.gemm_tn(probe, 0, wprobe, 0, 1.0, 1.0)
+    per_row = (time.perf_counter() - t0) / 32 * 3.0             # three GEMMs per token row
+    Ms = int(min(cfg.M, max(64, 15.0 / max(per_row, 1e-9))))
+    Ms -= Ms % 16
+    del probe, wprobe
     x = synth.bf16_bits(synth.make_x(cfg, li, M=Ms))
     w = synth.bf16_bits(synth.make_w(cfg, li))
     dy = synth.bf16_bits(synth.make_dy(cfg, li, M=Ms))
@@ -156,6 +177,13 @@ def main():
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
     states = [LinearState(cfg, li, dev) for li in range(len(cfg.linears))]
+    if args.calibrate_copy:
+        src = torch.full((1 << 30,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if args.prequantized_w:
         for s in states:
             llmq.llmq_amax(s.W, llmq.E4M3, s.aw, s.sw, s.aws)
@@ -192,9 +220,9 @@ def main():
         "gemm_only_pct_fp8_peak": round(100.0 * gemm_tflops / PEAK_FP8_TFLOPS, 2),
         "quantize_gbps": round(qbytes / (ms_quant * 1e-3) / 1e9, 1),
         "quantize_pct_hbm_peak": round(100.0 * qbytes / (ms_quant * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2),
-        "roofline": {"kernel": "gemm_tn_256_kernel", "bound": "mfma", "achieved": round(gemm_tflops, 2),
+        "roofline": {"kernel": "gemm_tn_tile_kernel", "bound": "mfma", "achieved": round(gemm_tflops, 2),
                      "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_FP8_TFLOPS, 4),
-                     "traffic": None, "launches_per_step": n_gemm,
+                     "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(cfg.index), "launches_per_step": n_gemm,
                      "avg_launch_ms": round(ms_gemm / n_gemm, 5),
                      "flops_per_launch": flops / n_gemm},
     }
