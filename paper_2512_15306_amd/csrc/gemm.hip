@@ -466,8 +466,11 @@ static TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus) {
             const int per_cu = (ni == 2 && nj == 2) ? 2 : 1;          // workgroups resident per CU
             const int64_t slots = (int64_t)num_cus * per_cu;
             const int64_t rounds = (tiles + slots - 1) / slots;
-            const double cost = (double)rounds * per_cu * ni * nj / eff[ni][nj];
-            if (best.ni == 0 || cost < best_cost * 0.999) { best = {ni, nj}; best_cost = cost; }
+            // two resident 2 x 2 workgroups overlap each other's prologue and epilogue, which pays most
+            // when the contraction is short
+            const double e = per_cu == 2 ? (T <= 4096 ? 0.92 : 0.82) : eff[ni][nj];
+            const double cost = (double)rounds * per_cu * ni * nj / e;
+            if (best.ni == 0 || cost < best_cost * 0.97) { best = {ni, nj}; best_cost = cost; }   // larger tile on near ties
         }
     return best;
 }
