@@ -82,6 +82,9 @@ struct GemmTuning {
     // slab: the workgroups that run side by side on an XCD (4 tile columns x 8 tile rows at a time)
     // share each slab and cover it together.
     static constexpr int kTouchShareA = 4, kTouchShareB = 8;
+    // Fragment reads ride along with the first 1 / kDsSpread of a half step's MFMAs, the direct-to-LDS
+    // loads with the first 1 / kVmSpread.
+    static constexpr int kDsSpread = 2, kVmSpread = 1;
     // Development aid: a tuning struct with kProfile = true also provides
     //   static __device__ void record(int block, int slot, long long value)
     // and gets cycle stamps of the phases of wave 0 of every workgroup.
@@ -113,19 +116,19 @@ __device__ inline void mma_block(v16f (&acc)[NI][NJ], const v8i (&a)[NI], const 
             acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[i][j], FB, FA, 0, 0, 0, 0);
 }
 
-// Interleave NM MFMAs with ND LDS reads (all within the first half of the MFMAs, so that they have
-// landed when the MFMAs end) and NV global loads (spread over all MFMAs).
-template <int NM, int ND, int NV, int SYNC, int M = 0>
+// Interleave NM MFMAs with ND LDS reads, spread over the first NM / DS_SPREAD MFMAs (so that they have
+// landed when the MFMAs end), and NV global loads, spread over the first NM / VM_SPREAD.
+template <int NM, int ND, int NV, int DS_SPREAD, int VM_SPREAD, int SYNC, int M = 0>
 __device__ inline void interleave() {
     if constexpr (M < NM) {
-        constexpr int kHalf = (NM + 1) / 2;
-        constexpr int kDsPer = (ND + kHalf - 1) / kHalf;
-        constexpr int kVmPer = (NV + NM - 1) / NM;
+        constexpr int kDsSpan = (NM + DS_SPREAD - 1) / DS_SPREAD, kVmSpan = (NM + VM_SPREAD - 1) / VM_SPREAD;
+        constexpr int kDsPer = (ND + kDsSpan - 1) / kDsSpan;
+        constexpr int kVmPer = (NV + kVmSpan - 1) / kVmSpan;
         constexpr int kDsLeft = ND - M * kDsPer, kVmLeft = NV - M * kVmPer;
         __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, SYNC);
         if constexpr (kDsLeft > 0) __builtin_amdgcn_sched_group_barrier(kSchedDsRead, kDsLeft < kDsPer ? kDsLeft : kDsPer, SYNC);
         if constexpr (kVmLeft > 0) __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, kVmLeft < kVmPer ? kVmLeft : kVmPer, SYNC);
-        interleave<NM, ND, NV, SYNC, M + 1>();
+        interleave<NM, ND, NV, DS_SPREAD, VM_SPREAD, SYNC, M + 1>();
     }
 }
 
@@ -240,7 +243,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         read_frags(curA, offA, 1, a1);
         read_frags(curB, offB, 1, b1);
         mma_block<FA, FB, NI, NJ>(acc, a0, b0);
-        interleave<NI * NJ, kLoadsPerStep, 0, 0>();
+        interleave<NI * NJ, kLoadsPerStep, 0, V::kDsSpread, V::kVmSpread, 0>();
         // the direct-to-LDS loads of the previous step must have landed; its two touch loads, issued
         // after them, may still be in flight
         if constexpr (kTouch) wait_vmcnt<2>(); else wait_vmcnt<0>();
@@ -250,7 +253,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         read_frags(nxtA, offA, 0, a0);          // past the last slab this reads bytes that are never used
         read_frags(nxtB, offB, 0, b0);
         mma_block<FA, FB, NI, NJ>(acc, a1, b1);
-        interleave<NI * NJ, kLoadsPerStep, kLoadsPerStep, 1>();
+        interleave<NI * NJ, kLoadsPerStep, kLoadsPerStep, V::kDsSpread, V::kVmSpread, 1>();
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (kTouch) {
             const int kp = kt + 2 + touch_ahead;
