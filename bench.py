@@ -37,8 +37,6 @@ def parse():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--prequantized-w", action="store_true",
                    help="weights quantized once outside the timed region (reused across micro-steps)")
-    p.add_argument("--calibrate-copy", action="store_true",
-                   help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return p.parse_args()
 
 
@@ -121,12 +119,31 @@ def timed(fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
+def measure_peaks(dev):
+    """What this chip sustains: the GEMM's MFMA instruction from registers (constant and random operand
+    bits) and a plain 1 GiB copy.  Reported next to the published peaks."""
+    import torch
+    from paper_2512_15306_amd import llmq
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    out = {}
+    for name, rnd in (("mfma_fp8_const_bits_tflops", False), ("mfma_fp8_random_bits_tflops", True)):
+        flops = llmq.llmq_calibrate_mfma(0, 0, rnd, 2000, sink)
+        ms = timed(lambda: llmq.llmq_calibrate_mfma(0, 0, rnd, 20000, sink), 3)
+        out[name] = round(flops * 10 / (ms * 1e-3) / 1e12, 1)
+    src = torch.full((1 << 30,), 7, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    llmq.llmq_calibrate_copy(src, dst)
+    ms = timed(lambda: llmq.llmq_calibrate_copy(src, dst), 5)
+    out["hbm_copy_gbps"] = round(2.0 * src.numel() / (ms * 1e-3) / 1e9, 1)
+    return out
+
+
 def cpu_baseline(cfg):
-    """The oracle as it stands on a bounded sample: the 'o' projection (second linear) restricted to
-    the first rows of the token dimension, whole path (3 absmax, 3 quantize+transpose, 3 fp64 GEMMs)."""
+    """The oracle as it stands on a bounded sample: the largest linear of the block restricted to the
+    first rows of the token dimension, whole path (3 absmax, 3 quantize+transpose, 3 fp64 GEMMs)."""
     import oracle
     from paper_2512_15306_amd import synth
-    li = 1 if len(cfg.linears) > 1 else 0
+    li = max(range(len(cfg.linears)), key=lambda i: cfg.linears[i].K * cfg.linears[i].N)   # the largest linear
     lin = cfg.linears[li]
     # size the sample for roughly 15 s on this host: time a 32-row slab of the forward GEMM first
     import numpy as np
@@ -177,13 +194,7 @@ def main():
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
     states = [LinearState(cfg, li, dev) for li in range(len(cfg.linears))]
-    if args.calibrate_copy:
-        src = torch.full((1 << 30,), 7, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+    peaks = measure_peaks(dev)
     if args.prequantized_w:
         for s in states:
             llmq.llmq_amax(s.W, llmq.E4M3, s.aw, s.sw, s.aws)
@@ -220,6 +231,9 @@ def main():
         "gemm_only_pct_fp8_peak": round(100.0 * gemm_tflops / PEAK_FP8_TFLOPS, 2),
         "quantize_gbps": round(qbytes / (ms_quant * 1e-3) / 1e9, 1),
         "quantize_pct_hbm_peak": round(100.0 * qbytes / (ms_quant * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2),
+        "measured_peaks": peaks,
+        "gemm_only_pct_measured_random_bits_peak": round(100.0 * gemm_tflops / peaks["mfma_fp8_random_bits_tflops"], 2),
+        "quantize_pct_measured_copy": round(100.0 * qbytes / (ms_quant * 1e-3) / 1e9 / peaks["hbm_copy_gbps"], 2),
         "roofline": {"kernel": "gemm_tn_tile_kernel", "bound": "mfma", "achieved": round(gemm_tflops, 2),
                      "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_FP8_TFLOPS, 4),
                      "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(cfg.index), "launches_per_step": n_gemm,

@@ -147,6 +147,22 @@ int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, i
                           const float* d_scale_dy, const float* d_scale_x, int fmt_dy,
                           void* dW, int accumulate, void* ws, size_t ws_bytes, int flags, void* stream);
 
+/*
+ * Peak calibration (the paper's appendix "A note on MFU" measures the attainable peak with a large-matmul
+ * micro-benchmark instead of trusting the spec sheet).  Both calls only enqueue; the caller times them.
+ *
+ * llmq_calibrate_mfma: a register-only loop of the GEMM's FP8 MFMA instruction (4 x 4 block pattern, one
+ *   workgroup of 4 waves per CU, `iters` passes of 16 MFMAs per wave) with operand registers holding
+ *   constants (random_bits == 0) or random FP8 bits (random_bits != 0; the matrix cores are power-limited and
+ *   sustain a lower clock on random bits, as on real quantized data).  d_sink: [1] float, device, practically
+ *   never written.  *flops (host pointer, may be NULL) receives the FLOP count of the launch.
+ * llmq_calibrate_copy: plain device copy of `bytes` (multiple of 16, 16-byte aligned pointers): 2 * bytes of
+ *   HBM traffic.
+ */
+int llmq_calibrate_mfma(int fmtA, int fmtB, int random_bits, int iters, float* d_sink, double* flops,
+                        void* stream);
+int llmq_calibrate_copy(const void* src, void* dst, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -191,4 +191,23 @@ int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, i
                                 dW, accumulate, nullptr, false, s, num_cus());
 }
 
+int llmq_calibrate_mfma(int fmtA, int fmtB, int random_bits, int iters, float* d_sink, double* flops,
+                        void* stream) {
+    if (!d_sink) return LLMQ_ERR_NULL;
+    if (!fmt_ok(fmtA) || !fmt_ok(fmtB)) return LLMQ_ERR_FORMAT;
+    if (iters < 1 || iters > (1 << 24)) return LLMQ_ERR_SHAPE;
+    if (!aligned(d_sink, 4)) return LLMQ_ERR_ALIGN;
+    // workgroups x waves x iterations x 16 MFMAs x 2 * 32 * 32 * 64 FLOP
+    if (flops) *flops = (double)num_cus() * 4.0 * iters * 16.0 * 2.0 * 32 * 32 * 64;
+    return llmq::launch_calibrate_mfma(fmtA, fmtB, random_bits != 0, iters, d_sink, static_cast<hipStream_t>(stream),
+                                       num_cus());
+}
+
+int llmq_calibrate_copy(const void* src, void* dst, size_t bytes, void* stream) {
+    if (!src || !dst) return LLMQ_ERR_NULL;
+    if (bytes < 16 || bytes % 16 != 0 || bytes >= ((size_t)1 << 40)) return LLMQ_ERR_SHAPE;
+    if (!aligned(src, 16) || !aligned(dst, 16)) return LLMQ_ERR_ALIGN;
+    return llmq::launch_calibrate_copy(src, dst, bytes, static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

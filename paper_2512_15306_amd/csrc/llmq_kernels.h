@@ -18,4 +18,8 @@ int launch_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64
                    int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16,
                    int accumulate, float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus);
 
+int launch_calibrate_mfma(int fmtA, int fmtB, int random_bits, int iters, float* d_sink, hipStream_t stream,
+                          int num_cus);
+int launch_calibrate_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);
+
 }  // namespace llmq

@@ -23,7 +23,8 @@ _lib = None
 
 EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "llmq_amax", "llmq_quantize_fp8", "llmq_fp8_gemm_tn",
            "llmq_fp8_linear_workspace_bytes", "llmq_fp8_linear_workspace_offsets",
-           "llmq_fp8_linear_fwd", "llmq_fp8_linear_dgrad", "llmq_fp8_linear_wgrad"]
+           "llmq_fp8_linear_fwd", "llmq_fp8_linear_dgrad", "llmq_fp8_linear_wgrad",
+           "llmq_calibrate_mfma", "llmq_calibrate_copy"]
 
 
 class LlmqError(RuntimeError):
@@ -65,6 +66,10 @@ def lib() -> ctypes.CDLL:
     L.llmq_fp8_linear_dgrad.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, vp, vp, vp, sz, i32, vp]
     L.llmq_fp8_linear_wgrad.restype = i32
     L.llmq_fp8_linear_wgrad.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, vp, i32, vp, sz, i32, vp]
+    L.llmq_calibrate_mfma.restype = i32
+    L.llmq_calibrate_mfma.argtypes = [i32, i32, i32, i32, vp, c.POINTER(c.c_double), vp]
+    L.llmq_calibrate_copy.restype = i32
+    L.llmq_calibrate_copy.argtypes = [vp, vp, sz, vp]
     _lib = L
     return L
 
@@ -168,3 +173,18 @@ def llmq_fp8_linear_wgrad(dY, X, M: int, N: int, K: int, d_scale_dy, d_scale_x, 
                                        _dev(dW, torch.bfloat16, "dW"), int(bool(accumulate)),
                                        _dev(ws, torch.uint8, "ws"), ws.numel(), flags, _stream()),
            "llmq_fp8_linear_wgrad")
+
+
+def llmq_calibrate_mfma(fmtA: int, fmtB: int, random_bits: bool, iters: int, d_sink: torch.Tensor) -> float:
+    """Enqueue the register-only MFMA loop; returns the FLOP count of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(lib().llmq_calibrate_mfma(fmtA, fmtB, int(bool(random_bits)), iters, _dev(d_sink, torch.float32, "d_sink"),
+                                     ctypes.byref(flops), _stream()), "llmq_calibrate_mfma")
+    return flops.value
+
+
+def llmq_calibrate_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    if src.numel() * src.element_size() != dst.numel() * dst.element_size():
+        raise ValueError("sizes differ")
+    _check(lib().llmq_calibrate_copy(_dev(src, None, "src"), _dev(dst, None, "dst"), src.numel() * src.element_size(),
+                                     _stream()), "llmq_calibrate_copy")
