@@ -24,8 +24,9 @@ PEAK_FP8_TFLOPS = 5000.0      # MI355X dense FP8 MFMA, published
 PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E, published
 # L2 <-> fabric bytes per GEMM launch (fetched + written, averaged over the step's launches), from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by a plain 1 GiB copy
-# (profiles/bench_config2_gemm_quantize_amax.md); None where not measured.
-MEASURED_GEMM_TRAFFIC_BYTES = {2: 226.0e6}
+# (profiles/bench_config<N>_gemm_quantize_amax.md); None where not measured.  They include hits in the
+# memory-side last-level cache: the 8 XCDs have private L2s and each re-reads the operands of its tiles.
+MEASURED_GEMM_TRAFFIC_BYTES = {2: 225.8e6, 3: 1006.4e6, 5: 3971.8e6}
 
 
 def parse():

@@ -85,6 +85,7 @@ struct GemmTuning {
     // Fragment reads ride along with the first 1 / kDsSpread of a half step's MFMAs, the direct-to-LDS
     // loads with the first 1 / kVmSpread.
     static constexpr int kDsSpread = 2, kVmSpread = 1;
+    static constexpr bool kNtStoreC = false;     // streaming hint on the output stores
     // Development aid: a tuning struct with kProfile = true also provides
     //   static __device__ void record(int block, int slot, long long value)
     // and gets cycle stamps of the phases of wave 0 of every workgroup.
@@ -328,7 +329,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         for (int p = lane; p < kPieces; p += kWave) {
             const int row = p / kSlots, sl = p % kSlots;
             v4u v = *reinterpret_cast<const v4u*>(stage + row * kPitch + (((sl + row) % kSlots) << 4));
-            *reinterpret_cast<v4u*>(cbase + (size_t)row * Cn + sl * 8) = v;
+            if constexpr (V::kNtStoreC) __builtin_nontemporal_store(v, reinterpret_cast<v4u*>(cbase + (size_t)row * Cn + sl * 8));
+            else *reinterpret_cast<v4u*>(cbase + (size_t)row * Cn + sl * 8) = v;
         }
     } else {
         // BF16 accumulation needs the old value before the single rounding: straight from the registers.
@@ -484,6 +486,12 @@ static int touch_ahead() {
     return 2;
 }
 
+// The same for 2 x 2 tiles, where two workgroups share a CU and already cover each other's waits.
+static int touch_ahead_pair() {
+    if (const char* e = getenv("LLMQ_GEMM_TOUCH_PAIR")) return atoi(e);
+    return 0;
+}
+
 template <int FA, int FB, int NI, int NJ>
 static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
                         const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
@@ -493,7 +501,7 @@ static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C
     const int grid = ((nt + kXcds - 1) / kXcds) * kXcds;
     hipLaunchKernelGGL((gemm_tn_tile_kernel<FA, FB, NI, NJ>), dim3(grid), dim3(kGemmThreads), 0, stream,
                        A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, accumulate, amax,
-                       tiles_r, tiles_c, touch_ahead());
+                       tiles_r, tiles_c, (NI == 2 && NJ == 2) ? touch_ahead_pair() : touch_ahead());
 }
 
 template <int FA, int FB>
