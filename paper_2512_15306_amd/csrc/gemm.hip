@@ -57,14 +57,14 @@ __device__ inline unsigned bf16_mag_max4(unsigned m, bf16x4 v) {
 }
 
 // Linear workgroup id -> output tile, XCD-aware.  Returns false for the padding ids.
-__device__ inline bool tile_of_block(int pid, int tiles_r, int tiles_c, int& tr, int& tc) {
+__device__ inline bool tile_of_block(int pid, int tiles_r, int tiles_c, int band_rows, int& tr, int& tc) {
     const int nt = tiles_r * tiles_c;
     const int per_xcd = (nt + kXcds - 1) / kXcds;
     const int id = (pid % kXcds) * per_xcd + pid / kXcds;
     if (id >= nt) return false;
-    const int band = kBandRows * tiles_c;
-    const int first = (id / band) * kBandRows;
-    const int h = tiles_r - first < kBandRows ? tiles_r - first : kBandRows;
+    const int band = band_rows * tiles_c;
+    const int first = (id / band) * band_rows;
+    const int h = tiles_r - first < band_rows ? tiles_r - first : band_rows;
     const int in_band = id % band;
     tr = first + in_band % h;
     tc = in_band / h;
@@ -137,7 +137,7 @@ template <int FA, int FB, int NI, int NJ, class V = GemmTuning>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ C,
     int Cn, int T, const float* __restrict__ d_sA, const float* __restrict__ d_sB,
-    int accumulate, unsigned* __restrict__ amax_bits, int tiles_r, int tiles_c, int touch_ahead) {
+    int accumulate, unsigned* __restrict__ amax_bits, int tiles_r, int tiles_c, int touch_ahead, int band_rows) {
     constexpr int BM = 64 * NI, BN = 64 * NJ;
     constexpr int kSlabA = BM * BK, kSlabB = BN * BK;
     // One array per stage and operand: distinct LDS objects let the compiler see that the
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
     __shared__ __attribute__((aligned(1024))) uint8_t ldsB1[kSlabB];
     __shared__ unsigned s_amax[kGemmThreads / kWave];
     int tr, tc;
-    if (!tile_of_block(blockIdx.x, tiles_r, tiles_c, tr, tc)) return;   // uniform over the workgroup
+    if (!tile_of_block(blockIdx.x, tiles_r, tiles_c, band_rows, tr, tc)) return;   // uniform over the workgroup
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -486,6 +486,12 @@ static int touch_ahead() {
     return 2;
 }
 
+// Height of the bands of tiles, in tile rows; LLMQ_GEMM_BAND overrides it for tuning.
+static int band_rows() {
+    if (const char* e = getenv("LLMQ_GEMM_BAND")) { const int v = atoi(e); if (v >= 1 && v <= 64) return v; }
+    return kBandRows;
+}
+
 // The same for 2 x 2 tiles, where two workgroups share a CU and already cover each other's waits.
 static int touch_ahead_pair() {
     if (const char* e = getenv("LLMQ_GEMM_TOUCH_PAIR")) return atoi(e);
@@ -501,7 +507,7 @@ static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C
     const int grid = ((nt + kXcds - 1) / kXcds) * kXcds;
     hipLaunchKernelGGL((gemm_tn_tile_kernel<FA, FB, NI, NJ>), dim3(grid), dim3(kGemmThreads), 0, stream,
                        A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, accumulate, amax,
-                       tiles_r, tiles_c, (NI == 2 && NJ == 2) ? touch_ahead_pair() : touch_ahead());
+                       tiles_r, tiles_c, (NI == 2 && NJ == 2) ? touch_ahead_pair() : touch_ahead(), band_rows());
 }
 
 template <int FA, int FB>
