@@ -47,15 +47,6 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
 }
 
-__device__ inline unsigned bf16_mag_max4(unsigned m, bf16x4 v) {
-    v2u w = __builtin_bit_cast(v2u, v);
-    unsigned a = w[0] & 0x7FFF7FFFu, b = w[1] & 0x7FFF7FFFu;
-    unsigned x = (a & 0xFFFFu) > (a >> 16) ? (a & 0xFFFFu) : (a >> 16);
-    unsigned y = (b & 0xFFFFu) > (b >> 16) ? (b & 0xFFFFu) : (b >> 16);
-    x = x > y ? x : y;
-    return m > x ? m : x;
-}
-
 // Linear workgroup id -> output tile, XCD-aware.  Returns false for the padding ids.
 __device__ inline bool tile_of_block(int pid, int tiles_r, int tiles_c, int band_rows, int& tr, int& tc) {
     const int nt = tiles_r * tiles_c;
@@ -133,11 +124,11 @@ __device__ inline void interleave() {
     }
 }
 
-template <int FA, int FB, int NI, int NJ, class V = GemmTuning>
+template <int FA, int FB, int NI, int NJ, bool ACCUM, class V = GemmTuning>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ C,
     int Cn, int T, const float* __restrict__ d_sA, const float* __restrict__ d_sB,
-    int accumulate, unsigned* __restrict__ amax_bits, int tiles_r, int tiles_c, int touch_ahead, int band_rows) {
+    unsigned* __restrict__ amax_bits, int tiles_r, int tiles_c, int touch_ahead, int band_rows) {
     constexpr int BM = 64 * NI, BN = 64 * NJ;
     constexpr int kSlabA = BM * BK, kSlabB = BN * BK;
     // One array per stage and operand: distinct LDS objects let the compiler see that the
@@ -163,6 +154,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         }
     };
     stamp(0);
+    const float scale_a = *d_sA, scale_b = *d_sB;     // requested now, needed in the epilogue
 
     // ---- global -> LDS: one instruction moves 8 rows x 128 B.  Wave w moves rows [16 NI w, 16 NI (w+1))
     // of the A slab with 2 NI instructions and rows [16 NJ w, ...) of the B slab with 2 NJ.
@@ -266,15 +258,16 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         }
     };
 
+    // both stages are requested at once; only the first has to have landed before the first fragments
     issue_loads(ldsA0, ldsB0, 0);
-    wait_vmcnt<0>();
-    lds_barrier();
     issue_loads(ldsA1, ldsB1, nk > 1 ? BK : kOutOfRange);
     if constexpr (kTouch) {                       // keep "two touch loads are the newest" true from the start
         const int off = (touch_ahead > 0 && 2 < nk) ? 2 * BK : kOutOfRange;
         touchA[1] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, off, 0);
         touchB[1] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, off, 0);
     }
+    wait_vmcnt<kLoadsPerStep + (kTouch ? 2 : 0)>();
+    lds_barrier();
     read_frags(ldsA0, offA, 0, a0);
     read_frags(ldsB0, offB, 0, b0);
     stamp(1);
@@ -298,12 +291,48 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
     // 16-byte slot index of a staged row is rotated by the row number, so that the 8-byte writes of
     // 32 rows and the 16-byte reads spread over the banks.  The region is private to the wave and LDS
     // executes a wave's accesses in order, so no barrier is needed.
-    const float inv_a = 1.0f / *d_sA, inv_b = 1.0f / *d_sB;
-    unsigned mag = 0;
-    if (!accumulate) {
+    // De-scale with one multiply by 1 / (sA sB) unless that product leaves the normal range (degenerate
+    // scales such as FLT_MAX for an all-zero tensor), in which case the two factors are applied in turn.
+    const float inv_a = 1.0f / scale_a, inv_b = 1.0f / scale_b;
+    const float inv_ab = inv_a * inv_b;
+    const bool one_mul = inv_ab >= 1.17549435e-38f && inv_ab <= 3.402823466e+38f;
+    const float m1 = one_mul ? inv_ab : inv_a;
+    if (!one_mul) {                       // rare and uniform: apply the second factor to the accumulators first
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] *= inv_b;
+    }
+    auto descale4 = [&](const v16f& block, int g) -> v4f {
+        v4f y;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = block[4 * g + e] * m1;
+        return y;
+    };
+    // The output absmax is taken in fp32 before rounding: rounding to BF16 is monotonic, so the BF16
+    // rounding of the largest |y| is the largest rounded magnitude.
+    float maxabs = 0.0f;
+    auto track4 = [&](const v4f& y) {
+        maxabs = __builtin_fmaxf(__builtin_fmaxf(maxabs, __builtin_fabsf(y[0])), __builtin_fabsf(y[1]));
+        maxabs = __builtin_fmaxf(__builtin_fmaxf(maxabs, __builtin_fabsf(y[2])), __builtin_fabsf(y[3]));
+    };
+    if constexpr (!ACCUM) {
         constexpr int kSlots = 4 * NJ;                                       // 16-byte slots per staged row
         constexpr int kPitch = 16 * kSlots;
+        constexpr bool kPow2 = (kSlots & (kSlots - 1)) == 0;
         uint8_t* stage = wave == 0 ? ldsA0 : wave == 1 ? ldsB0 : wave == 2 ? ldsA1 : ldsB1;
+        // byte offset inside a staged row of the 8 bytes this lane writes for column group c8 = col / 8;
+        // with a power-of-two slot count it does not depend on the row block (32 rows apart)
+        int slot_off[kSlots];
+        if constexpr (kPow2) {
+#pragma unroll
+            for (int c8 = 0; c8 < kSlots; ++c8) slot_off[c8] = (((c8 + fr_row) & (kSlots - 1)) << 4) | (fr_half << 3);
+        }
+        uint16_t* cbase = C + (size_t)(tr * BM + wr * 32 * NI) * Cn + tc * BN + wc * 32 * NJ;
+        constexpr int kBlockPieces = 32 * kSlots;                            // 16-byte pieces of one block of 32 rows
+        // one block of 32 rows at a time: while its stores are in flight the next block is converted
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int row = i * 32 + fr_row;
@@ -312,26 +341,23 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
             for (int j = 0; j < NJ; ++j) {
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int col = j * 32 + g * 8 + fr_half * 4;            // multiple of 4
-                    v4f y;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) y[e] = acc[i][j][4 * g + e] * inv_a * inv_b;
+                    const v4f y = descale4(acc[i][j], g);
+                    track4(y);
                     bf16x4 o = __builtin_convertvector(y, bf16x4);
-                    mag = bf16_mag_max4(mag, o);
-                    const int slot = ((col >> 3) + row) % kSlots;
-                    *reinterpret_cast<bf16x4*>(srow + ((slot << 4) | ((col & 7) << 1))) = o;
+                    const int c8 = j * 4 + g;                                // columns 8 c8 + 4 fr_half + 0..3
+                    const int off = kPow2 ? slot_off[c8] : ((((c8 + row) % kSlots) << 4) | (fr_half << 3));
+                    *reinterpret_cast<bf16x4*>(srow + off) = o;
                 }
             }
+#pragma unroll
+            for (int p = lane; p < kBlockPieces; p += kWave) {
+                const int r = i * 32 + p / kSlots, sl = p % kSlots;
+                v4u v = *reinterpret_cast<const v4u*>(stage + r * kPitch + (((sl + r) % kSlots) << 4));
+                if constexpr (V::kNtStoreC) __builtin_nontemporal_store(v, reinterpret_cast<v4u*>(cbase + (size_t)r * Cn + sl * 8));
+                else *reinterpret_cast<v4u*>(cbase + (size_t)r * Cn + sl * 8) = v;
+            }
         }
-        uint16_t* cbase = C + (size_t)(tr * BM + wr * 32 * NI) * Cn + tc * BN + wc * 32 * NJ;
-        constexpr int kPieces = 32 * NI * kSlots;                            // 16-byte pieces of the quadrant
-#pragma unroll 4
-        for (int p = lane; p < kPieces; p += kWave) {
-            const int row = p / kSlots, sl = p % kSlots;
-            v4u v = *reinterpret_cast<const v4u*>(stage + row * kPitch + (((sl + row) % kSlots) << 4));
-            if constexpr (V::kNtStoreC) __builtin_nontemporal_store(v, reinterpret_cast<v4u*>(cbase + (size_t)row * Cn + sl * 8));
-            else *reinterpret_cast<v4u*>(cbase + (size_t)row * Cn + sl * 8) = v;
-        }
+        if constexpr (V::kProfile) stamp(4);
     } else {
         // BF16 accumulation needs the old value before the single rounding: straight from the registers.
         const int row_base = tr * BM + wr * 32 * NI + fr_row;
@@ -344,21 +370,19 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     uint16_t* dst = crow + j * 32 + g * 8;
-                    v4f y;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) y[e] = acc[i][j][4 * g + e] * inv_a * inv_b;
+                    v4f y = descale4(acc[i][j], g);
                     v2u old = *reinterpret_cast<const v2u*>(dst);
                     y[0] += __uint_as_float(old[0] << 16);
                     y[1] += __uint_as_float(old[0] & 0xFFFF0000u);
                     y[2] += __uint_as_float(old[1] << 16);
                     y[3] += __uint_as_float(old[1] & 0xFFFF0000u);
-                    bf16x4 o = __builtin_convertvector(y, bf16x4);
-                    mag = bf16_mag_max4(mag, o);
-                    *reinterpret_cast<bf16x4*>(dst) = o;
+                    track4(y);
+                    *reinterpret_cast<bf16x4*>(dst) = __builtin_convertvector(y, bf16x4);
                 }
             }
         }
     }
+    unsigned mag = (unsigned)__builtin_bit_cast(uint16_t, (__bf16)maxabs);   // non-negative: magnitude bits
     if (amax_bits) {
         mag = wave_max_u32(mag);
         if (lane == 0) s_amax[wave] = mag;
@@ -372,6 +396,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         }
     }
     if constexpr (V::kProfile) {
+        stamp(5);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         stamp(3);
     }
@@ -505,9 +530,15 @@ static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C
     const int tiles_r = (int)(R / (64 * NI)), tiles_c = (int)(C / (64 * NJ));
     const int nt = tiles_r * tiles_c;
     const int grid = ((nt + kXcds - 1) / kXcds) * kXcds;
-    hipLaunchKernelGGL((gemm_tn_tile_kernel<FA, FB, NI, NJ>), dim3(grid), dim3(kGemmThreads), 0, stream,
-                       A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, accumulate, amax,
-                       tiles_r, tiles_c, (NI == 2 && NJ == 2) ? touch_ahead_pair() : touch_ahead(), band_rows());
+    const int touch = (NI == 2 && NJ == 2) ? touch_ahead_pair() : touch_ahead();
+    if (accumulate)
+        hipLaunchKernelGGL((gemm_tn_tile_kernel<FA, FB, NI, NJ, true>), dim3(grid), dim3(kGemmThreads), 0, stream,
+                           A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c,
+                           touch, band_rows());
+    else
+        hipLaunchKernelGGL((gemm_tn_tile_kernel<FA, FB, NI, NJ, false>), dim3(grid), dim3(kGemmThreads), 0, stream,
+                           A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c,
+                           touch, band_rows());
 }
 
 template <int FA, int FB>
