@@ -277,7 +277,11 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         k_step(ldsA1, ldsB1, ldsA0, ldsB0, kt + 1, 1);
     }
     if (kt < nk) k_step(ldsA0, ldsB0, ldsA1, ldsB1, kt, 0);
-    wait_vmcnt<0>();                               // nothing may still be landing in LDS when the wave ends
+    // Every wave waits for its own direct-to-LDS loads (the out-of-range ones of the last two steps
+    // still write zeros into the slabs), then all meet: after this barrier nothing lands in LDS any
+    // more and nobody reads the slabs, so the epilogue may reuse them.
+    wait_vmcnt<0>();
+    lds_barrier();
     if constexpr (kTouch) {
         touch_sink ^= touchA[0] ^ touchB[0] ^ touchA[1] ^ touchB[1];
         asm volatile("" ::"v"(touch_sink));
@@ -290,7 +294,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
     // which nobody reads any more, and writes it out as full row segments, 16 bytes per lane.  The
     // 16-byte slot index of a staged row is rotated by the row number, so that the 8-byte writes of
     // 32 rows and the 16-byte reads spread over the banks.  The region is private to the wave and LDS
-    // executes a wave's accesses in order, so no barrier is needed.
+    // executes a wave's accesses in order, so no further barrier is needed.
     // De-scale with one multiply by 1 / (sA sB) unless that product leaves the normal range (degenerate
     // scales such as FLT_MAX for an all-zero tensor), in which case the two factors are applied in turn.
     const float inv_a = 1.0f / scale_a, inv_b = 1.0f / scale_b;

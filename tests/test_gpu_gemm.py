@@ -257,3 +257,92 @@ def test_full_size_linears_on_sampled_outputs(cfg_i, li):
         err = np.abs(got - y)
         assert np.all(err <= GEMM_TOL * S), (name, err.max(), (GEMM_TOL * S)[err.argmax()])
         assert np.isfinite(got).all() and np.abs(got).max() > 0
+
+
+def test_all_tile_shapes_give_the_same_bytes_run_after_run():
+    """Every wave-tile instantiation accumulates each output in the same order, so they must agree
+    byte for byte, and every repetition with itself (more workgroups than CUs, few K steps: the
+    situation in which a late direct-to-LDS zero fill once overwrote a staged output tile)."""
+    import os
+    R = C = 3072
+    for T in (256, 384, 1152):
+        A = _rand_codes((R, T), 0, 7 + T)
+        B = _rand_codes((C, T), 0, 9 + T)
+        Ad, Bd = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+        dsa, dsb = _scales(1.7, 0.3)
+        ref = None
+        try:
+            for tile in ["4x4", "2x2", "4x3", "3x4", "3x3", "4x2", "2x4", "3x2", "2x3"]:
+                os.environ["LLMQ_GEMM_TILE"] = tile
+                for rep in range(3):
+                    c = torch.full((R, C), float("nan"), dtype=torch.bfloat16, device=DEV)
+                    llmq.llmq_fp8_gemm_tn(Ad, 0, Bd, 0, dsa, dsb, c, False, None)
+                    if ref is None:
+                        ref = c
+                    else:
+                        same = torch.equal(c.view(torch.int16), ref.view(torch.int16))
+                        assert same, "tile %s repetition %d differs (T=%d)" % (tile, rep, T)
+        finally:
+            os.environ.pop("LLMQ_GEMM_TILE", None)
+        rr, cc = _sample_positions(R, C, 512, 3)
+        y, S = oracle.gemm_tn_sampled(A, 0, B, 0, 1.7, 0.3, rr, cc)
+        got = ref[torch.from_numpy(rr).to(DEV), torch.from_numpy(cc).to(DEV)].cpu().to(torch.float64).numpy()
+        assert np.all(np.abs(got - y) <= GEMM_TOL * S)
+
+
+def _block_step(cfg, states):
+    for s in states:
+        M, K, N = s["M"], s["K"], s["N"]
+        llmq.llmq_amax(s["X"], 0, s["f"][0:1], s["f"][1:2], s["aws"])
+        llmq.llmq_amax(s["W"], 0, s["f"][2:3], s["f"][3:4], s["aws"])
+        llmq.llmq_fp8_linear_fwd(s["X"], s["W"], M, N, K, s["f"][1:2], s["f"][3:4], s["Y"], s["f"][6:7], s["ws"])
+        llmq.llmq_amax(s["dY"], 1, s["f"][4:5], s["f"][5:6], s["aws"])
+        llmq.llmq_fp8_linear_dgrad(s["dY"], None, M, N, K, s["f"][5:6], s["f"][3:4], 1, s["dX"], s["f"][7:8], s["ws"],
+                                   llmq.REUSE_W)
+        llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, s["f"][5:6], s["f"][1:2], 1, s["dW"], False, s["ws"],
+                                   llmq.REUSE_X | llmq.REUSE_DY)
+
+
+def test_whole_block_step_is_deterministic_and_replays_from_a_graph():
+    """Config 2's whole step (12 absmax, 12 quantize, 12 GEMM launches): same bytes on every run
+    (Section 3 "Reproducibility"), and the same bytes again when the step is captured in a HIP graph and
+    replayed several times with eager work in between."""
+    cfg = synth.CONFIGS[2]
+    states = []
+    for li, lin in enumerate(cfg.linears):
+        M, K, N = cfg.M, lin.K, lin.N
+        states.append(dict(M=M, K=K, N=N, X=synth.make_x(cfg, li, device=DEV), W=synth.make_w(cfg, li, device=DEV),
+                           dY=synth.make_dy(cfg, li, device=DEV),
+                           ws=torch.zeros(llmq.llmq_fp8_linear_workspace_bytes(M, N, K), dtype=torch.uint8, device=DEV),
+                           aws=torch.empty(llmq.llmq_amax_workspace_bytes(), dtype=torch.uint8, device=DEV),
+                           f=torch.zeros(8, dtype=torch.float32, device=DEV),
+                           Y=torch.empty((M, N), dtype=torch.bfloat16, device=DEV),
+                           dX=torch.empty((M, K), dtype=torch.bfloat16, device=DEV),
+                           dW=torch.empty((N, K), dtype=torch.bfloat16, device=DEV)))
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [s[k].clone() for s in states for k in ("Y", "dX", "dW", "f", "ws")]
+
+    def scrub():
+        for s in states:
+            for k in ("Y", "dX", "dW", "f"):
+                s[k].zero_()
+
+    def same(a, b):
+        return all(torch.equal(x.view(torch.uint8), y.view(torch.uint8)) for x, y in zip(a, b))
+
+    _block_step(cfg, states)
+    ref = snapshot()
+    for rep in range(3):
+        scrub()
+        _block_step(cfg, states)
+        assert same(ref, snapshot()), "eager run %d differs" % rep
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        _block_step(cfg, states)
+    for rep in range(3):
+        scrub()                                   # eager work and a synchronisation between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        assert same(ref, snapshot()), "graph replay %d differs" % rep
