@@ -70,6 +70,18 @@ def _load():
     lib.oracle_gemm_tn_sampled.argtypes = [u8p, c.c_int, u8p, c.c_int, c.c_int64, c.c_int64,
                                            c.c_int64, c.c_float, c.c_float, i64p, i64p,
                                            c.c_int64, f64p, f64p]
+    lib.oracle_sigmoid_exact.restype = c.c_double
+    lib.oracle_sigmoid_exact.argtypes = [c.c_double]
+    lib.oracle_sigmoid_f32.restype = c.c_float
+    lib.oracle_sigmoid_f32.argtypes = [c.c_float]
+    lib.oracle_swiglu_fwd.restype = None
+    lib.oracle_swiglu_fwd.argtypes = [u16p, c.c_int64, c.c_int64, u16p]
+    lib.oracle_swiglu_fwd_exact.restype = None
+    lib.oracle_swiglu_fwd_exact.argtypes = [u16p, c.c_int64, c.c_int64, f64p]
+    lib.oracle_swiglu_bwd.restype = None
+    lib.oracle_swiglu_bwd.argtypes = [u16p, u16p, c.c_int64, c.c_int64, u16p]
+    lib.oracle_swiglu_bwd_exact.restype = None
+    lib.oracle_swiglu_bwd_exact.argtypes = [u16p, u16p, c.c_int64, c.c_int64, f64p]
     lib.oracle_num_threads.restype = c.c_int
     lib.oracle_num_threads.argtypes = []
     _lib = lib
@@ -176,6 +188,60 @@ def gemm_tn_sampled(A, fmtA, B, fmtB, sA, sB, rr, cc):
                                    _ptr(rr, ctypes.c_int64), _ptr(cc, ctypes.c_int64), rr.size,
                                    _ptr(y, ctypes.c_double), _ptr(S, ctypes.c_double))
     return y, S
+
+
+def sigmoid_exact(g: float) -> float:
+    return float(_load().oracle_sigmoid_exact(float(g)))
+
+
+def sigmoid_f32(g) -> np.float32:
+    """The binary32 evaluation of the logistic function that the SwiGLU oracle uses."""
+    return np.float32(_load().oracle_sigmoid_f32(ctypes.c_float(float(g))))
+
+
+def _gu_shape(gu_bits):
+    gu = _as(gu_bits, np.uint16)
+    if gu.ndim != 2 or gu.shape[1] % 2:
+        raise ValueError("GU must be [M, 2I]")
+    return gu, gu.shape[0], gu.shape[1] // 2
+
+
+def swiglu_fwd(gu_bits: np.ndarray) -> np.ndarray:
+    """h[M, I] as BF16 bit patterns from GU[M, 2I] (gate columns first, then up)."""
+    gu, M, I = _gu_shape(gu_bits)
+    h = np.empty((M, I), np.uint16)
+    _load().oracle_swiglu_fwd(_ptr(gu, ctypes.c_uint16), M, I, _ptr(h, ctypes.c_uint16))
+    return h
+
+
+def swiglu_fwd_exact(gu_bits: np.ndarray) -> np.ndarray:
+    gu, M, I = _gu_shape(gu_bits)
+    h = np.empty((M, I), np.float64)
+    _load().oracle_swiglu_fwd_exact(_ptr(gu, ctypes.c_uint16), M, I, _ptr(h, ctypes.c_double))
+    return h
+
+
+def swiglu_bwd(dh_bits: np.ndarray, gu_bits: np.ndarray) -> np.ndarray:
+    """dGU[M, 2I] as BF16 bit patterns from dh[M, I] and GU[M, 2I]."""
+    gu, M, I = _gu_shape(gu_bits)
+    dh = _as(dh_bits, np.uint16)
+    if dh.shape != (M, I):
+        raise ValueError("dh must be [M, I]")
+    out = np.empty((M, 2 * I), np.uint16)
+    _load().oracle_swiglu_bwd(_ptr(dh, ctypes.c_uint16), _ptr(gu, ctypes.c_uint16), M, I,
+                              _ptr(out, ctypes.c_uint16))
+    return out
+
+
+def swiglu_bwd_exact(dh_bits: np.ndarray, gu_bits: np.ndarray) -> np.ndarray:
+    gu, M, I = _gu_shape(gu_bits)
+    dh = _as(dh_bits, np.uint16)
+    if dh.shape != (M, I):
+        raise ValueError("dh must be [M, I]")
+    out = np.empty((M, 2 * I), np.float64)
+    _load().oracle_swiglu_bwd_exact(_ptr(dh, ctypes.c_uint16), _ptr(gu, ctypes.c_uint16), M, I,
+                                    _ptr(out, ctypes.c_double))
+    return out
 
 
 def num_threads() -> int:

@@ -29,9 +29,15 @@
  *   GEMM   fp64 accumulation of exact products of the decoded FP8 values,
  *          divided by (double)sA * (double)sB.
  *
+ *   - Section 3, kernel-fusion paragraph and "Activation checkpointing": the
+ *     non-linearity (SwiGLU) also returns the absmax of its result, and under
+ *     recomputation, with the absmax known, emits the FP8 bytes directly.
+ *
  * Parity status: every function below is pinned by tests/test_oracle_*.py
  * (closed forms of the formats, an independent library cast, brute force on
- * small integer inputs, algebraic invariants).
+ * small integer inputs, algebraic invariants; for SwiGLU the binary64
+ * definition, a library SiLU, identities of the logistic function and finite
+ * differences for the backward pass).
  */
 #include <float.h>
 #include <math.h>
@@ -233,6 +239,123 @@ void oracle_gemm_tn_sampled(const uint8_t* A, int fmtA, const uint8_t* B, int fm
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < n; ++i)
         dot_tn(A + rr[i] * T, da, B + cc[i] * T, db, T, den, y ? y + i : NULL, S ? S + i : NULL);
+}
+
+/* ---- SwiGLU with its extra outputs (Section 3, kernel-fusion paragraph) ----------- */
+
+/*
+ * The paper keeps the non-linearities in BF16 and gives each of them an extra output, the absmax of
+ * its result, so that the FP8 conversion of the next matmul's input needs no reduction pass of its
+ * own; when the absmax is already known (recomputation during backward, Section 3 "Activation
+ * checkpointing") the conversion itself is fused into the non-linearity.  Neither changes a value:
+ * the absmax is oracle_amax_bf16 of the BF16 result and the fused bytes are oracle_quantize of it,
+ * so the oracle only needs the non-linearity; the callers compose.
+ *
+ * Layout reading: the gate+up projection writes GU [M, 2I]; columns [0, I) are the gate g, columns
+ * [I, 2I) are the up branch u; h[m,i] = silu(g) * u with silu(g) = g * sigma(g), sigma(g) = 1/(1+e^-g).
+ * The backward pass maps dh [M, I] to dGU [M, 2I] in the same layout:
+ *   d/du = dh * silu(g),   d/dg = dh * u * sigma(g) * (1 + g * (1 - sigma(g))).
+ *
+ * Two versions of each:
+ *   *_exact  the definition in binary64 (what the result approximates);
+ *   the plain names: the binary32 evaluation whose BF16 rounding decides the stored bits (and through
+ *   them the absmax and the FP8 codes).  The paper does not fix the arithmetic of the non-linearity
+ *   beyond "BF16 in, BF16 out", so it is fixed here, in IEEE binary32 operations only (each rounded to
+ *   nearest even, nothing contracted except the fused multiply-adds written out), which any machine
+ *   reproduces bit for bit:
+ *     1. a  = -min(max(g, -100), 86)
+ *     2. n  = rint(a * LOG2E)                        ties to even
+ *     3. r  = fma(n, -LN2_HI, a);  r = fma(n, -LN2_LO, r)
+ *     4. p  = 1 + r(1 + r(1/2 + r(1/6 + r(1/24 + r(1/120 + r/720)))))     Horner, one fma per level
+ *     5. e  = p * 2^n                                exact scaling; overflows to +Inf for g <= -89, which
+ *                                                    makes sg and h zero where |silu(g)| < 2^-121
+ *     6. sg = 1 / (1 + e)                            one addition, one division
+ *     7. h  = bf16( (g * sg) * u )                   two multiplications, one rounding to BF16
+ *   backward, with sg as above:
+ *     du = bf16( dh * (g * sg) ),   dg = bf16( ((dh * u) * sg) * fma(g, 1 - sg, 1) ).
+ *   The constants are the binary32 numbers nearest to log2(e), ln 2 (HI), ln 2 - HI (LO) and 1/k!.
+ *   Non-finite inputs are outside the contract.
+ */
+static const float SW_LOG2E = 0x1.715476p+0f;
+static const float SW_LN2_HI = 0x1.62e430p-1f;
+static const float SW_LN2_LO = -0x1.05c610p-29f;
+static const float SW_C2 = 0x1.000000p-1f, SW_C3 = 0x1.555556p-3f, SW_C4 = 0x1.555556p-5f,
+                   SW_C5 = 0x1.111112p-7f, SW_C6 = 0x1.6c16c2p-10f;
+
+double oracle_sigmoid_exact(double g) { return 1.0 / (1.0 + exp(-g)); }
+
+float oracle_sigmoid_f32(float g) {
+    float a = -fminf(fmaxf(g, -100.0f), 86.0f);
+    float n = rintf(a * SW_LOG2E);
+    float r = fmaf(n, -SW_LN2_HI, a);
+    r = fmaf(n, -SW_LN2_LO, r);
+    float p = SW_C6;
+    p = fmaf(p, r, SW_C5);
+    p = fmaf(p, r, SW_C4);
+    p = fmaf(p, r, SW_C3);
+    p = fmaf(p, r, SW_C2);
+    p = fmaf(p, r, 1.0f);
+    p = fmaf(p, r, 1.0f);
+    float e = ldexpf(p, (int)n);
+    float d = 1.0f + e;
+    return 1.0f / d;
+}
+
+/* h [M, I] (BF16 bit patterns) from GU [M, 2I]. */
+void oracle_swiglu_fwd(const uint16_t* gu, int64_t M, int64_t I, uint16_t* h) {
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t i = 0; i < I; ++i) {
+            float g = oracle_bf16_to_f32(gu[m * 2 * I + i]);
+            float u = oracle_bf16_to_f32(gu[m * 2 * I + I + i]);
+            float silu = g * oracle_sigmoid_f32(g);
+            float v = silu * u;
+            h[m * I + i] = oracle_f64_to_bf16((double)v);
+        }
+}
+
+void oracle_swiglu_fwd_exact(const uint16_t* gu, int64_t M, int64_t I, double* h) {
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t i = 0; i < I; ++i) {
+            double g = oracle_bf16_to_f32(gu[m * 2 * I + i]);
+            double u = oracle_bf16_to_f32(gu[m * 2 * I + I + i]);
+            h[m * I + i] = g * oracle_sigmoid_exact(g) * u;
+        }
+}
+
+/* dGU [M, 2I] (BF16 bit patterns) from dh [M, I] and GU [M, 2I]. */
+void oracle_swiglu_bwd(const uint16_t* dh, const uint16_t* gu, int64_t M, int64_t I, uint16_t* dgu) {
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t i = 0; i < I; ++i) {
+            float g = oracle_bf16_to_f32(gu[m * 2 * I + i]);
+            float u = oracle_bf16_to_f32(gu[m * 2 * I + I + i]);
+            float d = oracle_bf16_to_f32(dh[m * I + i]);
+            float sg = oracle_sigmoid_f32(g);
+            float silu = g * sg;
+            float du = d * silu;
+            float one_minus = 1.0f - sg;
+            float t = fmaf(g, one_minus, 1.0f);
+            float dg = d * u;
+            dg = dg * sg;
+            dg = dg * t;
+            dgu[m * 2 * I + i] = oracle_f64_to_bf16((double)dg);
+            dgu[m * 2 * I + I + i] = oracle_f64_to_bf16((double)du);
+        }
+}
+
+void oracle_swiglu_bwd_exact(const uint16_t* dh, const uint16_t* gu, int64_t M, int64_t I, double* dgu) {
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t i = 0; i < I; ++i) {
+            double g = oracle_bf16_to_f32(gu[m * 2 * I + i]);
+            double u = oracle_bf16_to_f32(gu[m * 2 * I + I + i]);
+            double d = oracle_bf16_to_f32(dh[m * I + i]);
+            double sg = oracle_sigmoid_exact(g);
+            dgu[m * 2 * I + i] = d * u * sg * (1.0 + g * (1.0 - sg));
+            dgu[m * 2 * I + I + i] = d * g * sg;
+        }
 }
 
 /* Threads the OpenMP loops above will use (reported by the benchmark). */
