@@ -148,6 +148,50 @@ int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, i
                           void* dW, int accumulate, void* ws, size_t ws_bytes, int flags, void* stream);
 
 /*
+ * Scale from an absmax that a fused producer left on the device (the d_amax_* outputs of the calls above):
+ *   d_scale[0] = min(FMAX(fmt) / d_amax[0], FLT_MAX), the same rule and rounding as llmq_amax.
+ */
+int llmq_scale_from_amax(const float* d_amax, int fmt, float* d_scale, void* stream);
+
+/*
+ * SwiGLU with the extra outputs of the FP8 pipeline (Section 3, kernel-fusion paragraph: every
+ * non-linearity also returns the absmax of its result; Section 3 "Activation checkpointing": with the
+ * absmax known, as in recomputation during backward, the FP8 conversion is fused into the non-linearity).
+ *
+ *   GU [M, 2I] BF16, the output of the gate+up projection: columns [0, I) are the gate g, columns
+ *   [I, 2I) the up branch u.   h[m,i] = bf16( silu(g) * u ),  silu(g) = g * sg,  sg = 1 / (1 + e^-g).
+ *   The value is evaluated in IEEE binary32, operation by operation (so that the BF16 bits, and with them
+ *   the absmax and the FP8 codes, are reproducible anywhere):
+ *     a = -min(max(g, -100), 86);  n = rint(a * LOG2E);  r = fma(n, -LN2_HI, a);  r = fma(n, -LN2_LO, r);
+ *     p = 1 + r(1 + r(1/2 + r(1/6 + r(1/24 + r(1/120 + r/720)))))  (Horner, one fma per level);
+ *     e = p * 2^n;  sg = 1 / (1 + e);  h = bf16( (g * sg) * u ),  one RNE rounding to BF16.
+ *   LOG2E, LN2_HI, LN2_LO, 1/k! are the binary32 numbers nearest to log2 e, ln 2, ln 2 - LN2_HI, 1/k!.
+ *   Against the exact function the result is within half a BF16 ulp (+ 2^-20 relative); for g <= -89,
+ *   where |silu(g)| < 2^-121, it is +-0.  Non-finite inputs are outside the contract.
+ *
+ * llmq_swiglu_fwd: writes h [M, I] (BF16), d_amax_h[0] = max |h| and, if d_scale_h is not NULL, the scale of
+ *   h for format fmt (as llmq_amax would for h, bit for bit).  ws: device scratch of at least
+ *   llmq_swiglu_workspace_bytes(M, I) bytes, 4-byte aligned, contents irrelevant on entry (per-workgroup
+ *   partial results, reduced by a second kernel: no atomics).
+ * llmq_swiglu_fwd_fp8: the scale is known (kept from the forward pass): writes q [M, I] = the FP8 codes
+ *   llmq_quantize_fp8 would produce from h with *d_scale_h, q_t [I, M] their transposed copy if not NULL,
+ *   and h itself only if h_bf16 is not NULL.  With q and q_t pointing at the Xq / Xq_t sections of a linear
+ *   workspace, the down projection then runs with LLMQ_REUSE_X.
+ * llmq_swiglu_bwd: dh [M, I], GU [M, 2I] -> dGU [M, 2I] (same column layout):
+ *     dGU[m, I+i] = bf16( dh * (g * sg) ),   dGU[m, i] = bf16( ((dh * u) * sg) * fma(g, 1 - sg, 1) ),
+ *   plus absmax and, if wanted, scale (format fmt) of dGU, which is the dY of the gate+up projection.
+ * M, I >= 1, I < 2^24; GU, h, dh, dGU 16-byte aligned and I % 8 == 0 for that to hold for every row (other
+ * I, and M not a multiple of 4, or of 16 with q_t, take a slower generic kernel).
+ */
+size_t llmq_swiglu_workspace_bytes(int64_t M, int64_t I);
+int llmq_swiglu_fwd(const void* gu_bf16, int64_t M, int64_t I, void* h_bf16, int fmt,
+                    float* d_amax_h, float* d_scale_h, void* ws, size_t ws_bytes, void* stream);
+int llmq_swiglu_fwd_fp8(const void* gu_bf16, int64_t M, int64_t I, const float* d_scale_h, int fmt,
+                        uint8_t* q, uint8_t* q_t, void* h_bf16, void* stream);
+int llmq_swiglu_bwd(const void* dh_bf16, const void* gu_bf16, int64_t M, int64_t I, void* dgu_bf16, int fmt,
+                    float* d_amax_dgu, float* d_scale_dgu, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Peak calibration (the paper's appendix "A note on MFU" measures the attainable peak with a large-matmul
  * micro-benchmark instead of trusting the spec sheet).  Both calls only enqueue; the caller times them.
  *

@@ -17,21 +17,6 @@ namespace llmq {
 constexpr int kAmaxThreads = 256;
 constexpr int kAmaxUnroll = 8;          // 16-byte loads in flight per lane
 
-__device__ inline unsigned pk_max_mag(unsigned acc, unsigned w) {
-    v2us a = __builtin_bit_cast(v2us, acc);
-    v2us b = __builtin_bit_cast(v2us, w & 0x7FFF7FFFu);
-    return __builtin_bit_cast(unsigned, __builtin_elementwise_max(a, b));
-}
-
-__device__ inline unsigned block_max_u32(unsigned m, unsigned* s_part) {
-    m = wave_max_u32(m);
-    if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x / kWave] = m;
-    __syncthreads();
-#pragma unroll
-    for (int w = 0; w < kAmaxThreads / kWave; ++w) m = m > s_part[w] ? m : s_part[w];
-    return m;
-}
-
 // partial[b] = largest BF16 magnitude pattern (15 bits) seen by block b
 __global__ __launch_bounds__(kAmaxThreads) void amax_partial_kernel(
     const v4u* __restrict__ x, size_t n_vec, const uint16_t* __restrict__ tail, int n_tail,
@@ -65,7 +50,7 @@ __global__ __launch_bounds__(kAmaxThreads) void amax_partial_kernel(
     }
     m0 = pk_max_mag(pk_max_mag(m0, m1), pk_max_mag(m2, m3));
     unsigned m = (m0 & 0xFFFFu) > (m0 >> 16) ? (m0 & 0xFFFFu) : (m0 >> 16);
-    m = block_max_u32(m, s_part);
+    m = block_max_u32<kAmaxThreads>(m, s_part);
     if (threadIdx.x == 0) partial[blockIdx.x] = m;
 }
 
@@ -79,7 +64,7 @@ __global__ __launch_bounds__(kAmaxThreads) void amax_final_kernel(
         unsigned v = partial[i];
         m = m > v ? m : v;
     }
-    m = block_max_u32(m, s_part);
+    m = block_max_u32<kAmaxThreads>(m, s_part);
     if (threadIdx.x == 0) {
         const float a = __uint_as_float(amax_bits_from_bf16_mag(m));
         *d_amax = a;
@@ -89,6 +74,24 @@ __global__ __launch_bounds__(kAmaxThreads) void amax_final_kernel(
             *d_scale = s;
         }
     }
+}
+
+__global__ void scale_from_amax_kernel(const float* __restrict__ d_amax, float* __restrict__ d_scale, float fmax) {
+    float s = fmax / *d_amax;
+    if (__builtin_isinf(s)) s = 3.402823466e+38f;
+    *d_scale = s;
+}
+
+int launch_scale_from_amax(const float* d_amax, int fmt, float* d_scale, hipStream_t stream) {
+    hipLaunchKernelGGL(scale_from_amax_kernel, dim3(1), dim3(1), 0, stream, d_amax, d_scale, fp8_max(fmt));
+    return hipGetLastError() == hipSuccess ? 0 : -6;
+}
+
+int launch_amax_final(const unsigned* partial, int n_partial, int fmt, float* d_amax, float* d_scale,
+                      hipStream_t stream) {
+    hipLaunchKernelGGL(amax_final_kernel, dim3(1), dim3(kAmaxThreads), 0, stream, partial, n_partial,
+                       d_amax, d_scale, fp8_max(fmt));
+    return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
 int launch_amax(const void* x, size_t n, int fmt, float* d_amax, float* d_scale, void* ws,
@@ -105,9 +108,7 @@ int launch_amax(const void* x, size_t n, int fmt, float* d_amax, float* d_scale,
     hipLaunchKernelGGL(amax_partial_kernel, dim3((unsigned)blocks), dim3(kAmaxThreads), 0, stream,
                        reinterpret_cast<const v4u*>(x), n_vec,
                        reinterpret_cast<const uint16_t*>(x) + n_vec * 8, n_tail, partial);
-    hipLaunchKernelGGL(amax_final_kernel, dim3(1), dim3(kAmaxThreads), 0, stream, partial, (int)blocks,
-                       d_amax, d_scale, fp8_max(fmt));
-    return hipGetLastError() == hipSuccess ? 0 : -6;
+    return launch_amax_final(partial, (int)blocks, fmt, d_amax, d_scale, stream);
 }
 
 }  // namespace llmq

@@ -1,5 +1,5 @@
 // C ABI of the FP8 linear path: argument checks and launch sequencing only; all arithmetic is in
-// the kernels (amax.hip, quantize.hip, gemm.hip).  Declarations and contracts: include/llmq.h.
+// the kernels (amax.hip, quantize.hip, gemm.hip, swiglu.hip).  Declarations and contracts: include/llmq.h.
 #include <hip/hip_runtime.h>
 
 #include "../../include/llmq.h"
@@ -51,6 +51,11 @@ int check_linear(int64_t M, int64_t N, int64_t K, const void* ws, size_t ws_byte
     if (!ws) return LLMQ_ERR_NULL;
     if (!aligned(ws, 256)) return LLMQ_ERR_ALIGN;
     if (ws_bytes < ws_layout(M, N, K).total) return LLMQ_ERR_WORKSPACE;
+    return LLMQ_OK;
+}
+
+int check_swiglu_shape(int64_t M, int64_t I) {
+    if (!dim_ok(M) || !dim_ok(I) || I >= ((int64_t)1 << 24) || M * I >= kMaxElems / 2) return LLMQ_ERR_SHAPE;
     return LLMQ_OK;
 }
 
@@ -189,6 +194,58 @@ int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, i
     // dW[n,k] = sum_m dYq_t[n,m] * Xq_t[k,m]
     return llmq::launch_gemm_tn(base + l.dyqt, fmt_dy, base + l.xqt, LLMQ_E4M3, N, K, M, d_scale_dy, d_scale_x,
                                 dW, accumulate, nullptr, false, s, num_cus());
+}
+
+int llmq_scale_from_amax(const float* d_amax, int fmt, float* d_scale, void* stream) {
+    if (!d_amax || !d_scale) return LLMQ_ERR_NULL;
+    if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
+    if (!aligned(d_amax, 4) || !aligned(d_scale, 4)) return LLMQ_ERR_ALIGN;
+    return llmq::launch_scale_from_amax(d_amax, fmt, d_scale, static_cast<hipStream_t>(stream));
+}
+
+size_t llmq_swiglu_workspace_bytes(int64_t M, int64_t I) {
+    if (check_swiglu_shape(M, I) != LLMQ_OK) return 0;
+    return (size_t)llmq::swiglu_blocks(M, I) * sizeof(unsigned);
+}
+
+int llmq_swiglu_fwd(const void* gu_bf16, int64_t M, int64_t I, void* h_bf16, int fmt, float* d_amax_h,
+                    float* d_scale_h, void* ws, size_t ws_bytes, void* stream) {
+    if (!gu_bf16 || !h_bf16 || !d_amax_h || !ws) return LLMQ_ERR_NULL;
+    int st = check_swiglu_shape(M, I);
+    if (st != LLMQ_OK) return st;
+    if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
+    if (!aligned(gu_bf16, 16) || !aligned(h_bf16, 16) || !aligned(d_amax_h, 4) || !aligned(d_scale_h, 4) ||
+        !aligned(ws, 4))
+        return LLMQ_ERR_ALIGN;
+    if (ws_bytes < llmq_swiglu_workspace_bytes(M, I)) return LLMQ_ERR_WORKSPACE;
+    return llmq::launch_swiglu_fwd(gu_bf16, M, I, h_bf16, static_cast<unsigned*>(ws), fmt, d_amax_h, d_scale_h,
+                                   nullptr, 0, nullptr, nullptr, static_cast<hipStream_t>(stream));
+}
+
+int llmq_swiglu_fwd_fp8(const void* gu_bf16, int64_t M, int64_t I, const float* d_scale_h, int fmt, uint8_t* q,
+                        uint8_t* q_t, void* h_bf16, void* stream) {
+    if (!gu_bf16 || !d_scale_h || !q) return LLMQ_ERR_NULL;
+    int st = check_swiglu_shape(M, I);
+    if (st != LLMQ_OK) return st;
+    if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
+    if (!aligned(gu_bf16, 16) || !aligned(h_bf16, 16) || !aligned(q, 16) || !aligned(q_t, 16) || !aligned(d_scale_h, 4))
+        return LLMQ_ERR_ALIGN;
+    return llmq::launch_swiglu_fwd(gu_bf16, M, I, h_bf16, nullptr, fmt, nullptr, nullptr, d_scale_h, fmt, q, q_t,
+                                   static_cast<hipStream_t>(stream));
+}
+
+int llmq_swiglu_bwd(const void* dh_bf16, const void* gu_bf16, int64_t M, int64_t I, void* dgu_bf16, int fmt,
+                    float* d_amax_dgu, float* d_scale_dgu, void* ws, size_t ws_bytes, void* stream) {
+    if (!dh_bf16 || !gu_bf16 || !dgu_bf16 || !d_amax_dgu || !ws) return LLMQ_ERR_NULL;
+    int st = check_swiglu_shape(M, I);
+    if (st != LLMQ_OK) return st;
+    if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
+    if (!aligned(dh_bf16, 16) || !aligned(gu_bf16, 16) || !aligned(dgu_bf16, 16) || !aligned(d_amax_dgu, 4) ||
+        !aligned(d_scale_dgu, 4) || !aligned(ws, 4))
+        return LLMQ_ERR_ALIGN;
+    if (ws_bytes < llmq_swiglu_workspace_bytes(M, I)) return LLMQ_ERR_WORKSPACE;
+    return llmq::launch_swiglu_bwd(dh_bf16, gu_bf16, M, I, dgu_bf16, static_cast<unsigned*>(ws), fmt, d_amax_dgu,
+                                   d_scale_dgu, static_cast<hipStream_t>(stream));
 }
 
 int llmq_calibrate_mfma(int fmtA, int fmtB, int random_bits, int iters, float* d_sink, double* flops,

@@ -10,6 +10,11 @@ namespace llmq {
 constexpr int kAmaxMaxPartials = 1024;      // the absmax workspace holds one 32-bit word per block
 int launch_amax(const void* x, size_t n, int fmt, float* d_amax, float* d_scale, void* ws,
                 hipStream_t stream, int num_cus);
+// Second stage of every absmax reduction: the maximum of n_partial BF16 magnitude patterns (one per
+// workgroup of the first stage) becomes d_amax and, if d_scale is not NULL, the scale for fmt.
+int launch_amax_final(const unsigned* partial, int n_partial, int fmt, float* d_amax, float* d_scale,
+                      hipStream_t stream);
+int launch_scale_from_amax(const float* d_amax, int fmt, float* d_scale, hipStream_t stream);
 // zero_word: if not NULL, one 32-bit word the kernel also clears (the absmax accumulator of the GEMM
 // that follows in the same call, which saves a launch).
 int launch_quantize(const void* x, int64_t rows, int64_t cols, const float* d_scale, int fmt,
@@ -17,6 +22,15 @@ int launch_quantize(const void* x, int64_t rows, int64_t cols, const float* d_sc
 int launch_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64_t R, int64_t C,
                    int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16,
                    int accumulate, float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus);
+
+// SwiGLU with its extra outputs.  h, d_amax (with partial, the per-workgroup scratch), q and q_t are
+// optional; q_fmt is only read when q is given.  swiglu_blocks() is the number of scratch words.
+int64_t swiglu_blocks(int64_t M, int64_t I);
+int launch_swiglu_fwd(const void* gu, int64_t M, int64_t I, void* h, unsigned* partial, int amax_fmt,
+                      float* d_amax, float* d_scale, const float* d_qscale, int q_fmt, uint8_t* q, uint8_t* q_t,
+                      hipStream_t stream);
+int launch_swiglu_bwd(const void* dh, const void* gu, int64_t M, int64_t I, void* dgu, unsigned* partial,
+                      int amax_fmt, float* d_amax, float* d_scale, hipStream_t stream);
 
 int launch_calibrate_mfma(int fmtA, int fmtB, int random_bits, int iters, float* d_sink, hipStream_t stream,
                           int num_cus);

@@ -30,48 +30,6 @@ struct QuantTuning {
     static constexpr bool kBlocksDownRows = true;    // consecutive workgroups walk down rows instead of along columns
 };
 
-template <int FMT>
-__device__ inline unsigned cvt_pair(float a, float b, unsigned old, bool high) {
-    constexpr float fmax = FMT == 0 ? 448.0f : 57344.0f;
-    a = __builtin_amdgcn_fmed3f(a, -fmax, fmax);         // saturate; the cast below rounds to nearest even
-    b = __builtin_amdgcn_fmed3f(b, -fmax, fmax);
-    if constexpr (FMT == 0) {
-        return high ? (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, true)
-                    : (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, false);
-    } else {
-        return high ? (unsigned)__builtin_amdgcn_cvt_pk_bf8_f32(a, b, (int)old, true)
-                    : (unsigned)__builtin_amdgcn_cvt_pk_bf8_f32(a, b, (int)old, false);
-    }
-}
-
-// Four BF16 pairs (one 16-byte load) -> eight FP8 codes in two dwords.
-template <int FMT>
-__device__ inline void quantize8(const v4u& r, float s, unsigned& lo, unsigned& hi) {
-    float f[8];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        f[2 * j] = __uint_as_float(r[j] << 16) * s;            // even element: low half of the dword
-        f[2 * j + 1] = __uint_as_float(r[j] & 0xFFFF0000u) * s;
-    }
-    lo = cvt_pair<FMT>(f[0], f[1], 0u, false);
-    lo = cvt_pair<FMT>(f[2], f[3], lo, true);
-    hi = cvt_pair<FMT>(f[4], f[5], 0u, false);
-    hi = cvt_pair<FMT>(f[6], f[7], hi, true);
-}
-
-// w[r] holds bytes (r,0..3) of a 4x4 byte block; returns o[c] = bytes (0..3,c).
-__device__ inline void transpose4x4_bytes(const unsigned w[4], unsigned o[4]) {
-    // v_perm_b32 selects from the 8 bytes {first operand: 4..7, second operand: 0..3}
-    unsigned t01l = __builtin_amdgcn_perm(w[1], w[0], 0x05010400u);   // w0.0 w1.0 w0.1 w1.1
-    unsigned t01h = __builtin_amdgcn_perm(w[1], w[0], 0x07030602u);   // w0.2 w1.2 w0.3 w1.3
-    unsigned t23l = __builtin_amdgcn_perm(w[3], w[2], 0x05010400u);
-    unsigned t23h = __builtin_amdgcn_perm(w[3], w[2], 0x07030602u);
-    o[0] = __builtin_amdgcn_perm(t23l, t01l, 0x05040100u);
-    o[1] = __builtin_amdgcn_perm(t23l, t01l, 0x07060302u);
-    o[2] = __builtin_amdgcn_perm(t23h, t01h, 0x05040100u);
-    o[3] = __builtin_amdgcn_perm(t23h, t01h, 0x07060302u);
-}
-
 template <int FMT, bool TRANSPOSE, class V = QuantTuning>
 __global__ __launch_bounds__(kQThreads) void quantize_patch_kernel(
     const uint16_t* __restrict__ x, int64_t rows, int64_t cols, const float* __restrict__ d_scale,

@@ -24,7 +24,8 @@ _lib = None
 EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "llmq_amax", "llmq_quantize_fp8", "llmq_fp8_gemm_tn",
            "llmq_fp8_linear_workspace_bytes", "llmq_fp8_linear_workspace_offsets",
            "llmq_fp8_linear_fwd", "llmq_fp8_linear_dgrad", "llmq_fp8_linear_wgrad",
-           "llmq_calibrate_mfma", "llmq_calibrate_copy"]
+           "llmq_scale_from_amax", "llmq_swiglu_workspace_bytes", "llmq_swiglu_fwd", "llmq_swiglu_fwd_fp8",
+           "llmq_swiglu_bwd", "llmq_calibrate_mfma", "llmq_calibrate_copy"]
 
 
 class LlmqError(RuntimeError):
@@ -66,6 +67,16 @@ def lib() -> ctypes.CDLL:
     L.llmq_fp8_linear_dgrad.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, vp, vp, vp, sz, i32, vp]
     L.llmq_fp8_linear_wgrad.restype = i32
     L.llmq_fp8_linear_wgrad.argtypes = [vp, vp, i64, i64, i64, vp, vp, i32, vp, i32, vp, sz, i32, vp]
+    L.llmq_scale_from_amax.restype = i32
+    L.llmq_scale_from_amax.argtypes = [vp, i32, vp, vp]
+    L.llmq_swiglu_workspace_bytes.restype = sz
+    L.llmq_swiglu_workspace_bytes.argtypes = [i64, i64]
+    L.llmq_swiglu_fwd.restype = i32
+    L.llmq_swiglu_fwd.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp, sz, vp]
+    L.llmq_swiglu_fwd_fp8.restype = i32
+    L.llmq_swiglu_fwd_fp8.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp, vp]
+    L.llmq_swiglu_bwd.restype = i32
+    L.llmq_swiglu_bwd.argtypes = [vp, vp, i64, i64, vp, i32, vp, vp, vp, sz, vp]
     L.llmq_calibrate_mfma.restype = i32
     L.llmq_calibrate_mfma.argtypes = [i32, i32, i32, i32, vp, c.POINTER(c.c_double), vp]
     L.llmq_calibrate_copy.restype = i32
@@ -173,6 +184,52 @@ def llmq_fp8_linear_wgrad(dY, X, M: int, N: int, K: int, d_scale_dy, d_scale_x, 
                                        _dev(dW, torch.bfloat16, "dW"), int(bool(accumulate)),
                                        _dev(ws, torch.uint8, "ws"), ws.numel(), flags, _stream()),
            "llmq_fp8_linear_wgrad")
+
+
+def llmq_scale_from_amax(d_amax: torch.Tensor, fmt: int, d_scale: torch.Tensor) -> None:
+    _check(lib().llmq_scale_from_amax(_dev(d_amax, torch.float32, "d_amax"), fmt, _dev(d_scale, torch.float32, "d_scale"),
+                                      _stream()), "llmq_scale_from_amax")
+
+
+def llmq_swiglu_workspace_bytes(M: int, I: int) -> int:
+    return int(lib().llmq_swiglu_workspace_bytes(M, I))
+
+
+def _swiglu_dims(gu: torch.Tensor) -> Tuple[int, int]:
+    if gu.dim() != 2 or gu.shape[1] % 2:
+        raise ValueError("GU must be [M, 2I]")
+    return int(gu.shape[0]), int(gu.shape[1]) // 2
+
+
+def llmq_swiglu_fwd(gu: torch.Tensor, h: torch.Tensor, fmt: int, d_amax_h: torch.Tensor,
+                    d_scale_h: Optional[torch.Tensor], ws: torch.Tensor) -> None:
+    M, I = _swiglu_dims(gu)
+    if h.numel() != M * I:
+        raise ValueError("h must be [M, I]")
+    _check(lib().llmq_swiglu_fwd(_dev(gu, torch.bfloat16, "gu"), M, I, _dev(h, torch.bfloat16, "h"), fmt,
+                                 _dev(d_amax_h, torch.float32, "d_amax_h"), _dev(d_scale_h, torch.float32, "d_scale_h"),
+                                 _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()), "llmq_swiglu_fwd")
+
+
+def llmq_swiglu_fwd_fp8(gu: torch.Tensor, d_scale_h: torch.Tensor, fmt: int, q: torch.Tensor,
+                        q_t: Optional[torch.Tensor], h: Optional[torch.Tensor] = None) -> None:
+    M, I = _swiglu_dims(gu)
+    if q.numel() != M * I or (q_t is not None and q_t.numel() != M * I) or (h is not None and h.numel() != M * I):
+        raise ValueError("output size does not match [M, I]")
+    _check(lib().llmq_swiglu_fwd_fp8(_dev(gu, torch.bfloat16, "gu"), M, I, _dev(d_scale_h, torch.float32, "d_scale_h"),
+                                     fmt, _dev(q, torch.uint8, "q"), _dev(q_t, torch.uint8, "q_t"),
+                                     _dev(h, torch.bfloat16, "h"), _stream()), "llmq_swiglu_fwd_fp8")
+
+
+def llmq_swiglu_bwd(dh: torch.Tensor, gu: torch.Tensor, dgu: torch.Tensor, fmt: int, d_amax_dgu: torch.Tensor,
+                    d_scale_dgu: Optional[torch.Tensor], ws: torch.Tensor) -> None:
+    M, I = _swiglu_dims(gu)
+    if dh.numel() != M * I or dgu.numel() != 2 * M * I:
+        raise ValueError("dh must be [M, I] and dGU [M, 2I]")
+    _check(lib().llmq_swiglu_bwd(_dev(dh, torch.bfloat16, "dh"), _dev(gu, torch.bfloat16, "gu"), M, I,
+                                 _dev(dgu, torch.bfloat16, "dgu"), fmt, _dev(d_amax_dgu, torch.float32, "d_amax_dgu"),
+                                 _dev(d_scale_dgu, torch.float32, "d_scale_dgu"), _dev(ws, torch.uint8, "ws"),
+                                 ws.numel(), _stream()), "llmq_swiglu_bwd")
 
 
 def llmq_calibrate_mfma(fmtA: int, fmtB: int, random_bits: bool, iters: int, d_sink: torch.Tensor) -> float:

@@ -63,7 +63,7 @@ CONFIGS: Dict[int, Config] = {
 
 
 def tensor_seed(config: int, linear: int, which: int) -> int:
-    """which: 0 = X, 1 = W, 2 = dY, 3 = outlier-channel permutation."""
+    """which: 0 = X, 1 = W, 2 = dY, 3 = outlier-channel permutation, 4 = GU (SwiGLU input), 5 = dh."""
     return BASE_SEED + 1000 * config + 10 * linear + which
 
 
@@ -112,6 +112,30 @@ def make_dy(cfg: Config, li: int, device="cpu", M: Optional[int] = None) -> torc
     M = cfg.M if M is None else M
     dy = _randn((M, lin.N), device, tensor_seed(cfg.index, li, 2)) * cfg.dy_std
     return dy.to(torch.bfloat16)
+
+
+def swiglu_dims(cfg: Config) -> Tuple[int, int]:
+    """(M, I) of the block's SwiGLU: I is the width of the down projection's input."""
+    gate_up = next(l for l in cfg.linears if l.name == "gate_up")
+    return cfg.M, gate_up.N // 2
+
+
+def make_gu(cfg: Config, device="cpu", M: Optional[int] = None) -> torch.Tensor:
+    """Output GU[M, 2I] of the gate+up projection in BF16: N(0, std) with the standard deviation a
+    product of unit-variance activations with the config's weights has, std = w_std * sqrt(K)."""
+    li = next(i for i, l in enumerate(cfg.linears) if l.name == "gate_up")
+    lin = cfg.linears[li]
+    M = cfg.M if M is None else M
+    gu = _randn((M, lin.N), device, tensor_seed(cfg.index, li, 4)) * (cfg.w_std * lin.K ** 0.5)
+    return gu.to(torch.bfloat16)
+
+
+def make_dh(cfg: Config, device="cpu", M: Optional[int] = None) -> torch.Tensor:
+    """Gradient dh[M, I] arriving at the SwiGLU output in BF16 (N(0, dy_std))."""
+    li = next(i for i, l in enumerate(cfg.linears) if l.name == "gate_up")
+    M = cfg.M if M is None else M
+    dh = _randn((M, cfg.linears[li].N // 2), device, tensor_seed(cfg.index, li, 5)) * cfg.dy_std
+    return dh.to(torch.bfloat16)
 
 
 def linear_flops(cfg: Config) -> int:
