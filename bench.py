@@ -139,6 +139,38 @@ def measure_peaks(dev):
     return out
 
 
+def measure_swiglu(cfg, dev, reps):
+    """The block's SwiGLU with its fused outputs (next to the linears, not part of the step's FLOP count):
+    forward writing h + absmax, recompute mode writing FP8 bytes (both layouts) instead of h, backward
+    writing dGU + absmax.  GB/s on algorithmic bytes: 6, 6 and 10 per element of h."""
+    import torch
+    from paper_2512_15306_amd import llmq, synth
+    M, I = synth.swiglu_dims(cfg)
+    gu, dh = synth.make_gu(cfg, device=dev), synth.make_dh(cfg, device=dev)
+    h = torch.empty((M, I), dtype=torch.bfloat16, device=dev)
+    dgu = torch.empty((M, 2 * I), dtype=torch.bfloat16, device=dev)
+    q = torch.empty((M, I), dtype=torch.uint8, device=dev)
+    qt = torch.empty((I, M), dtype=torch.uint8, device=dev)
+    f = torch.zeros(4, dtype=torch.float32, device=dev)
+    ws = torch.empty(llmq.llmq_swiglu_workspace_bytes(M, I), dtype=torch.uint8, device=dev)
+    aws = torch.empty(llmq.llmq_amax_workspace_bytes(), dtype=torch.uint8, device=dev)
+    n = float(M) * I
+    legs = {
+        "fwd_h_absmax": (6.0, lambda: llmq.llmq_swiglu_fwd(gu, h, llmq.E4M3, f[0:1], f[1:2], ws)),
+        "fwd_fp8_both_layouts": (6.0, lambda: llmq.llmq_swiglu_fwd_fp8(gu, f[1:2], llmq.E4M3, q, qt, None)),
+        "bwd_dgu_absmax": (10.0, lambda: llmq.llmq_swiglu_bwd(dh, gu, dgu, llmq.E5M2, f[2:3], f[3:4], ws)),
+        "separate_absmax_of_h": (2.0, lambda: llmq.llmq_amax(h, llmq.E4M3, f[0:1], f[1:2], aws)),
+        "separate_quantize_of_h": (4.0, lambda: llmq.llmq_quantize_fp8(h, f[1:2], llmq.E4M3, q, qt)),
+    }
+    out = {"M": M, "I": I}
+    for name, (bpe, fn) in legs.items():
+        fn()
+        ms = timed(fn, reps)
+        out[name] = {"ms": round(ms, 4), "gbps": round(bpe * n / (ms * 1e-3) / 1e9, 1),
+                     "pct_hbm_peak": round(100.0 * bpe * n / (ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2)}
+    return out
+
+
 def cpu_baseline(cfg):
     """The oracle as it stands on a bounded sample: the largest linear of the block restricted to the
     first rows of the token dimension, whole path (3 absmax, 3 quantize+transpose, 3 fp64 GEMMs)."""
@@ -241,6 +273,9 @@ def main():
                      "avg_launch_ms": round(ms_gemm / n_gemm, 5),
                      "flops_per_launch": flops / n_gemm},
     }
+    del states
+    torch.cuda.empty_cache()
+    out["swiglu"] = measure_swiglu(cfg, dev, reps)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))

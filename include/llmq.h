@@ -171,7 +171,7 @@ int llmq_scale_from_amax(const float* d_amax, int fmt, float* d_scale, void* str
  *
  * llmq_swiglu_fwd: writes h [M, I] (BF16), d_amax_h[0] = max |h| and, if d_scale_h is not NULL, the scale of
  *   h for format fmt (as llmq_amax would for h, bit for bit).  ws: device scratch of at least
- *   llmq_swiglu_workspace_bytes(M, I) bytes, 4-byte aligned, contents irrelevant on entry (per-workgroup
+ *   llmq_swiglu_workspace_bytes(M, I) bytes, 16-byte aligned, contents irrelevant on entry (per-workgroup
  *   partial results, reduced by a second kernel: no atomics).
  * llmq_swiglu_fwd_fp8: the scale is known (kept from the forward pass): writes q [M, I] = the FP8 codes
  *   llmq_quantize_fp8 would produce from h with *d_scale_h, q_t [I, M] their transposed copy if not NULL,

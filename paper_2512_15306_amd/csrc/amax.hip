@@ -76,6 +76,51 @@ __global__ __launch_bounds__(kAmaxThreads) void amax_final_kernel(
     }
 }
 
+// The same for many partial results (producers that write one per workgroup of a 2-D grid): 1024 lanes,
+// four independent 16-byte loads in flight per lane, so that tens of thousands of words take a few
+// memory round trips instead of one per word and lane.
+constexpr int kAmaxWideThreads = 1024;
+__global__ __launch_bounds__(kAmaxWideThreads) void amax_final_wide_kernel(
+    const unsigned* __restrict__ partial, int n_partial, float* __restrict__ d_amax,
+    float* __restrict__ d_scale, float fmax) {
+    __shared__ unsigned s_part[kAmaxWideThreads / kWave];
+    unsigned m = 0;
+    const int n_vec = n_partial / 4;
+    const v4u* pv = reinterpret_cast<const v4u*>(partial);
+    int i = threadIdx.x;
+    for (; i + 3 * kAmaxWideThreads < n_vec; i += 4 * kAmaxWideThreads) {
+        v4u r[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r[j] = pv[i + j * kAmaxWideThreads];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            unsigned a = r[j][0] > r[j][1] ? r[j][0] : r[j][1], b = r[j][2] > r[j][3] ? r[j][2] : r[j][3];
+            a = a > b ? a : b;
+            m = m > a ? m : a;
+        }
+    }
+    for (; i < n_vec; i += kAmaxWideThreads) {
+        v4u r = pv[i];
+        unsigned a = r[0] > r[1] ? r[0] : r[1], b = r[2] > r[3] ? r[2] : r[3];
+        a = a > b ? a : b;
+        m = m > a ? m : a;
+    }
+    if ((int)threadIdx.x < n_partial - 4 * n_vec) {
+        unsigned v = partial[4 * n_vec + threadIdx.x];
+        m = m > v ? m : v;
+    }
+    m = block_max_u32<kAmaxWideThreads>(m, s_part);
+    if (threadIdx.x == 0) {
+        const float a = __uint_as_float(amax_bits_from_bf16_mag(m));
+        *d_amax = a;
+        if (d_scale) {
+            float s = fmax / a;
+            if (__builtin_isinf(s)) s = 3.402823466e+38f;
+            *d_scale = s;
+        }
+    }
+}
+
 __global__ void scale_from_amax_kernel(const float* __restrict__ d_amax, float* __restrict__ d_scale, float fmax) {
     float s = fmax / *d_amax;
     if (__builtin_isinf(s)) s = 3.402823466e+38f;
@@ -89,8 +134,12 @@ int launch_scale_from_amax(const float* d_amax, int fmt, float* d_scale, hipStre
 
 int launch_amax_final(const unsigned* partial, int n_partial, int fmt, float* d_amax, float* d_scale,
                       hipStream_t stream) {
-    hipLaunchKernelGGL(amax_final_kernel, dim3(1), dim3(kAmaxThreads), 0, stream, partial, n_partial,
-                       d_amax, d_scale, fp8_max(fmt));
+    if (n_partial <= kAmaxMaxPartials)
+        hipLaunchKernelGGL(amax_final_kernel, dim3(1), dim3(kAmaxThreads), 0, stream, partial, n_partial,
+                           d_amax, d_scale, fp8_max(fmt));
+    else        // partial is 16-byte aligned in that case (checked by the callers that can get here)
+        hipLaunchKernelGGL(amax_final_wide_kernel, dim3(1), dim3(kAmaxWideThreads), 0, stream, partial, n_partial,
+                           d_amax, d_scale, fp8_max(fmt));
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 

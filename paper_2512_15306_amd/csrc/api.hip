@@ -215,7 +215,7 @@ int llmq_swiglu_fwd(const void* gu_bf16, int64_t M, int64_t I, void* h_bf16, int
     if (st != LLMQ_OK) return st;
     if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
     if (!aligned(gu_bf16, 16) || !aligned(h_bf16, 16) || !aligned(d_amax_h, 4) || !aligned(d_scale_h, 4) ||
-        !aligned(ws, 4))
+        !aligned(ws, 16))
         return LLMQ_ERR_ALIGN;
     if (ws_bytes < llmq_swiglu_workspace_bytes(M, I)) return LLMQ_ERR_WORKSPACE;
     return llmq::launch_swiglu_fwd(gu_bf16, M, I, h_bf16, static_cast<unsigned*>(ws), fmt, d_amax_h, d_scale_h,
@@ -241,7 +241,7 @@ int llmq_swiglu_bwd(const void* dh_bf16, const void* gu_bf16, int64_t M, int64_t
     if (st != LLMQ_OK) return st;
     if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
     if (!aligned(dh_bf16, 16) || !aligned(gu_bf16, 16) || !aligned(dgu_bf16, 16) || !aligned(d_amax_dgu, 4) ||
-        !aligned(d_scale_dgu, 4) || !aligned(ws, 4))
+        !aligned(d_scale_dgu, 4) || !aligned(ws, 16))
         return LLMQ_ERR_ALIGN;
     if (ws_bytes < llmq_swiglu_workspace_bytes(M, I)) return LLMQ_ERR_WORKSPACE;
     return llmq::launch_swiglu_bwd(dh_bf16, gu_bf16, M, I, dgu_bf16, static_cast<unsigned*>(ws), fmt, d_amax_dgu,

@@ -278,10 +278,15 @@ static int64_t generic_blocks(int64_t M, int64_t I) {
     return b > kSwGenericMaxBlocks ? kSwGenericMaxBlocks : b;
 }
 
-// Workgroups of the absmax-producing launches (forward with h, backward) = partial results written.
+// Workgroups of the absmax-producing launches (forward with h, backward): an upper bound of the partial
+// results written, which is what the scratch is sized for.
 int64_t swiglu_blocks(int64_t M, int64_t I) {
     if (!patch_ok(M, I, 4)) return generic_blocks(M, I);
     return ((M + 4 * kSwLanesR - 1) / (4 * kSwLanesR)) * ((I + kSwBlockCols - 1) / kSwBlockCols);
+}
+
+static int64_t patch_blocks(int64_t M, int64_t I, int pr) {
+    return ((M + pr * kSwLanesR - 1) / (pr * kSwLanesR)) * ((I + kSwBlockCols - 1) / kSwBlockCols);
 }
 
 template <int PR, bool WRITE_H, bool AMAX, int QFMT, bool TRANSPOSE>
@@ -317,14 +322,20 @@ int launch_swiglu_fwd(const void* gu_, int64_t M, int64_t I, void* h_, unsigned*
         else launch_fwd_fp8<1>(gu, M, I, h, d_qscale, q, q_t, stream);
         return hipGetLastError() == hipSuccess ? 0 : -6;
     }
-    if (patch_ok(M, I, 4)) {
+    int64_t n_partial;
+    if (patch_ok(M, I, 8)) {                   // 8 rows per lane: more bytes in flight, half the partial results
+        launch_fwd_patch<8, true, true, -1, false>(gu, M, I, h, partial, nullptr, nullptr, nullptr, stream);
+        n_partial = patch_blocks(M, I, 8);
+    } else if (patch_ok(M, I, 4)) {
         launch_fwd_patch<4, true, true, -1, false>(gu, M, I, h, partial, nullptr, nullptr, nullptr, stream);
+        n_partial = patch_blocks(M, I, 4);
     } else {
         hipLaunchKernelGGL((swiglu_fwd_generic_kernel<-1>), dim3((unsigned)generic_blocks(M, I)), dim3(kSwThreads), 0,
                            stream, gu, M, I, h, partial, (const float*)nullptr, (uint8_t*)nullptr, (uint8_t*)nullptr);
+        n_partial = generic_blocks(M, I);
     }
     if (hipGetLastError() != hipSuccess) return -6;
-    return launch_amax_final(partial, (int)swiglu_blocks(M, I), amax_fmt, d_amax, d_scale, stream);
+    return launch_amax_final(partial, (int)n_partial, amax_fmt, d_amax, d_scale, stream);
 }
 
 int launch_swiglu_bwd(const void* dh, const void* gu, int64_t M, int64_t I, void* dgu, unsigned* partial,
