@@ -82,6 +82,15 @@ def _load():
     lib.oracle_swiglu_bwd.argtypes = [u16p, u16p, c.c_int64, c.c_int64, u16p]
     lib.oracle_swiglu_bwd_exact.restype = None
     lib.oracle_swiglu_bwd_exact.argtypes = [u16p, u16p, c.c_int64, c.c_int64, f64p]
+    f32p = c.POINTER(c.c_float)
+    lib.oracle_residual_add.restype = None
+    lib.oracle_residual_add.argtypes = [u16p, u16p, c.c_size_t, u16p]
+    lib.oracle_rms_rstd.restype = None
+    lib.oracle_rms_rstd.argtypes = [u16p, c.c_int64, c.c_int64, c.c_double, f64p]
+    lib.oracle_rmsnorm_exact.restype = None
+    lib.oracle_rmsnorm_exact.argtypes = [u16p, u16p, c.c_int64, c.c_int64, c.c_double, f64p]
+    lib.oracle_rmsnorm_apply.restype = None
+    lib.oracle_rmsnorm_apply.argtypes = [u16p, u16p, f32p, c.c_int64, c.c_int64, u16p]
     lib.oracle_num_threads.restype = c.c_int
     lib.oracle_num_threads.argtypes = []
     _lib = lib
@@ -242,6 +251,48 @@ def swiglu_bwd_exact(dh_bits: np.ndarray, gu_bits: np.ndarray) -> np.ndarray:
     _load().oracle_swiglu_bwd_exact(_ptr(dh, ctypes.c_uint16), _ptr(gu, ctypes.c_uint16), M, I,
                                     _ptr(out, ctypes.c_double))
     return out
+
+
+def residual_add(res_bits: np.ndarray, x_bits: np.ndarray) -> np.ndarray:
+    """bf16(res + x) element-wise, as BF16 bit patterns."""
+    r, x = _as(res_bits, np.uint16), _as(x_bits, np.uint16)
+    if r.shape != x.shape:
+        raise ValueError("shapes differ")
+    out = np.empty(r.shape, np.uint16)
+    _load().oracle_residual_add(_ptr(r, ctypes.c_uint16), _ptr(x, ctypes.c_uint16), r.size, _ptr(out, ctypes.c_uint16))
+    return out
+
+
+def rms_rstd(res_bits: np.ndarray, eps: float) -> np.ndarray:
+    """1 / sqrt(mean_c res^2 + eps) per row, binary64."""
+    r = _as(res_bits, np.uint16)
+    M, C = r.shape
+    out = np.empty((M,), np.float64)
+    _load().oracle_rms_rstd(_ptr(r, ctypes.c_uint16), M, C, float(eps), _ptr(out, ctypes.c_double))
+    return out
+
+
+def rmsnorm_exact(res_bits: np.ndarray, w_bits: np.ndarray, eps: float) -> np.ndarray:
+    r, w = _as(res_bits, np.uint16), _as(w_bits, np.uint16)
+    M, C = r.shape
+    if w.shape != (C,):
+        raise ValueError("w must be [C]")
+    y = np.empty((M, C), np.float64)
+    _load().oracle_rmsnorm_exact(_ptr(r, ctypes.c_uint16), _ptr(w, ctypes.c_uint16), M, C, float(eps),
+                                 _ptr(y, ctypes.c_double))
+    return y
+
+
+def rmsnorm_apply(res_bits: np.ndarray, w_bits: np.ndarray, rstd: np.ndarray) -> np.ndarray:
+    """y = bf16((res * rstd[m]) * w[c]) in binary32, as BF16 bit patterns."""
+    r, w, s = _as(res_bits, np.uint16), _as(w_bits, np.uint16), _as(rstd, np.float32)
+    M, C = r.shape
+    if w.shape != (C,) or s.shape != (M,):
+        raise ValueError("w must be [C] and rstd [M]")
+    y = np.empty((M, C), np.uint16)
+    _load().oracle_rmsnorm_apply(_ptr(r, ctypes.c_uint16), _ptr(w, ctypes.c_uint16), _ptr(s, ctypes.c_float),
+                                 M, C, _ptr(y, ctypes.c_uint16))
+    return y
 
 
 def num_threads() -> int:

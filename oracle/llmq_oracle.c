@@ -37,7 +37,8 @@
  * (closed forms of the formats, an independent library cast, brute force on
  * small integer inputs, algebraic invariants; for SwiGLU the binary64
  * definition, a library SiLU, identities of the logistic function and finite
- * differences for the backward pass).
+ * differences for the backward pass; for RMSNorm a library rms_norm in
+ * binary64, scaling invariance, constant rows and a library BF16 addition).
  */
 #include <float.h>
 #include <math.h>
@@ -355,6 +356,67 @@ void oracle_swiglu_bwd_exact(const uint16_t* dh, const uint16_t* gu, int64_t M, 
             double sg = oracle_sigmoid_exact(g);
             dgu[m * 2 * I + i] = d * u * sg * (1.0 + g * (1.0 - sg));
             dgu[m * 2 * I + I + i] = d * g * sg;
+        }
+}
+
+/* ---- RMSNorm joined with the residual addition (Section 3, kernel-fusion paragraph) -------- */
+
+/*
+ * The paper handles RMS-norm and the residual-stream addition in one kernel that also returns the absmax
+ * of the normalised output (the input of the next FP8 matmul); with the statistics kept from the forward
+ * pass the FP8 conversion is fused in under recomputation (Section 3 "Activation checkpointing").
+ *
+ *   res'[m,c] = bf16( res[m,c] + x[m,c] )                         residual stream, stored in BF16
+ *   ms[m]     = (1/C) sum_c res'[m,c]^2,   rstd[m] = 1 / sqrt(ms[m] + eps)
+ *   y[m,c]    = bf16( res'[m,c] * rstd[m] * w[c] )                w [C] BF16, the norm's weight
+ *
+ * Readings: the norm is taken of the BF16-rounded residual (what is stored, so that recomputing from the
+ * stored stream gives the same result); the addition is one binary32 addition of the two BF16 values,
+ * then one RNE rounding; rstd is a per-row statistic kept in binary32 alongside the absmax.
+ * The row reduction has no prescribed order, so it is not reproducible bit for bit: the oracle gives it
+ * in binary64 (oracle_rms_rstd) and the exact output in binary64 (oracle_rmsnorm_exact); the GPU's rstd
+ * is compared within a tolerance.  GIVEN a binary32 rstd, the normalisation is fixed operation by
+ * operation, y = bf16( (res' * rstd) * w ) with two binary32 multiplications (oracle_rmsnorm_apply), and
+ * is reproducible bit for bit; that is the recompute path (statistics in, FP8 bytes out).
+ */
+void oracle_residual_add(const uint16_t* res, const uint16_t* x, size_t n, uint16_t* out) {
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; ++i) {
+        float sum = oracle_bf16_to_f32(res[i]) + oracle_bf16_to_f32(x[i]);
+        out[i] = oracle_f64_to_bf16((double)sum);
+    }
+}
+
+void oracle_rms_rstd(const uint16_t* res, int64_t M, int64_t C, double eps, double* rstd) {
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        double ss = 0.0;
+        for (int64_t c = 0; c < C; ++c) {
+            double v = oracle_bf16_to_f32(res[m * C + c]);
+            ss += v * v;
+        }
+        rstd[m] = 1.0 / sqrt(ss / (double)C + eps);
+    }
+}
+
+void oracle_rmsnorm_exact(const uint16_t* res, const uint16_t* w, int64_t M, int64_t C, double eps, double* y) {
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        double r;
+        oracle_rms_rstd(res + m * C, 1, C, eps, &r);
+        for (int64_t c = 0; c < C; ++c)
+            y[m * C + c] = (double)oracle_bf16_to_f32(res[m * C + c]) * r * (double)oracle_bf16_to_f32(w[c]);
+    }
+}
+
+void oracle_rmsnorm_apply(const uint16_t* res, const uint16_t* w, const float* rstd, int64_t M, int64_t C,
+                          uint16_t* y) {
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t c = 0; c < C; ++c) {
+            float t = oracle_bf16_to_f32(res[m * C + c]) * rstd[m];
+            float v = t * oracle_bf16_to_f32(w[c]);
+            y[m * C + c] = oracle_f64_to_bf16((double)v);
         }
 }
 
