@@ -192,6 +192,39 @@ int llmq_swiglu_bwd(const void* dh_bf16, const void* gu_bf16, int64_t M, int64_t
                     float* d_amax_dgu, float* d_scale_dgu, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * RMSNorm joined with the residual addition, with the extra outputs of the FP8 pipeline (Section 3,
+ * kernel-fusion paragraph: one kernel for both, which also returns the absmax of the normalised output;
+ * Section 3 "Activation checkpointing": statistics kept from the forward pass let the recomputation emit
+ * FP8 directly).
+ *
+ *   res'[m,c] = bf16( res[m,c] + x[m,c] )       one binary32 addition, one RNE rounding; the stored stream
+ *   rstd[m]   = 1 / sqrt( (1/C) sum_c res'[m,c]^2 + eps )     of the BF16-rounded res'; binary32
+ *   y[m,c]    = bf16( (res'[m,c] * rstd[m]) * w[c] )          two binary32 multiplications, one rounding
+ *   res, x, res', y [M, C] BF16; w [C] BF16; rstd [M] float.
+ *
+ * llmq_rmsnorm_fwd: x may be NULL (no addition: res is normalised as it is and res_out is ignored);
+ *   otherwise res_out receives res' and may be the same buffer as res (in place).  Writes y, rstd (kept for
+ *   the backward pass / recomputation), d_amax_y = max |y| and, if not NULL, d_scale_y for format fmt, both
+ *   bit-identical to llmq_amax of y.  The row sum runs in binary32 in an order of the kernel's choosing, so
+ *   rstd is reproducible run to run but only equal to the exact value within 2^-20 relative; y then is the
+ *   formula above evaluated with that rstd.  ws: at least llmq_rmsnorm_workspace_bytes(M) bytes, 16-byte
+ *   aligned, contents irrelevant (per-workgroup partial absmax; no atomics).
+ * llmq_rmsnorm_apply_fp8: the recompute path.  res (the stored stream), w, rstd and the scale of y are
+ *   given; writes q [M, C] = the FP8 codes llmq_quantize_fp8 would produce from y with *d_scale_y, their
+ *   transposed copy q_t [C, M] if not NULL, and y itself only if y_bf16 is not NULL.  Element-wise, hence
+ *   reproducible bit for bit from its inputs.  rstd must be 16-byte aligned.
+ * M, C >= 1, C < 2^24.  C % 8 == 0 and C <= 8192 take the single-pass forward kernel; M % 16 == 0 (M % 4
+ * without q_t) and C % 8 == 0 the tuned recompute kernel; other shapes slower generic ones.
+ */
+size_t llmq_rmsnorm_workspace_bytes(int64_t M);
+int llmq_rmsnorm_fwd(const void* res_bf16, const void* x_bf16, const void* w_bf16, int64_t M, int64_t C,
+                     float eps, void* res_out_bf16, void* y_bf16, float* rstd, int fmt, float* d_amax_y,
+                     float* d_scale_y, void* ws, size_t ws_bytes, void* stream);
+int llmq_rmsnorm_apply_fp8(const void* res_bf16, const void* w_bf16, const float* rstd, int64_t M, int64_t C,
+                           const float* d_scale_y, int fmt, uint8_t* q, uint8_t* q_t, void* y_bf16,
+                           void* stream);
+
+/*
  * Peak calibration (the paper's appendix "A note on MFU" measures the attainable peak with a large-matmul
  * micro-benchmark instead of trusting the spec sheet).  Both calls only enqueue; the caller times them.
  *

@@ -1,5 +1,5 @@
 // C ABI of the FP8 linear path: argument checks and launch sequencing only; all arithmetic is in
-// the kernels (amax.hip, quantize.hip, gemm.hip, swiglu.hip).  Declarations and contracts: include/llmq.h.
+// the kernels (amax.hip, quantize.hip, gemm.hip, swiglu.hip, rmsnorm.hip).  Declarations and contracts: include/llmq.h.
 #include <hip/hip_runtime.h>
 
 #include "../../include/llmq.h"
@@ -246,6 +246,40 @@ int llmq_swiglu_bwd(const void* dh_bf16, const void* gu_bf16, int64_t M, int64_t
     if (ws_bytes < llmq_swiglu_workspace_bytes(M, I)) return LLMQ_ERR_WORKSPACE;
     return llmq::launch_swiglu_bwd(dh_bf16, gu_bf16, M, I, dgu_bf16, static_cast<unsigned*>(ws), fmt, d_amax_dgu,
                                    d_scale_dgu, static_cast<hipStream_t>(stream));
+}
+
+size_t llmq_rmsnorm_workspace_bytes(int64_t M) {
+    if (!dim_ok(M)) return 0;
+    return (size_t)llmq::rmsnorm_blocks(M) * sizeof(unsigned);
+}
+
+int llmq_rmsnorm_fwd(const void* res_bf16, const void* x_bf16, const void* w_bf16, int64_t M, int64_t C, float eps,
+                     void* res_out_bf16, void* y_bf16, float* rstd, int fmt, float* d_amax_y, float* d_scale_y,
+                     void* ws, size_t ws_bytes, void* stream) {
+    if (!res_bf16 || !w_bf16 || !y_bf16 || !rstd || !d_amax_y || !ws || (x_bf16 && !res_out_bf16)) return LLMQ_ERR_NULL;
+    if (!dim_ok(M) || !dim_ok(C) || C >= ((int64_t)1 << 24) || M * C >= kMaxElems) return LLMQ_ERR_SHAPE;
+    if (!(eps >= 0.0f) || eps > 3.402823466e+38f) return LLMQ_ERR_SHAPE;
+    if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
+    if (!aligned(res_bf16, 16) || !aligned(x_bf16, 16) || !aligned(w_bf16, 16) || !aligned(y_bf16, 16) ||
+        (x_bf16 && !aligned(res_out_bf16, 16)) || !aligned(rstd, 4) || !aligned(d_amax_y, 4) ||
+        !aligned(d_scale_y, 4) || !aligned(ws, 16))
+        return LLMQ_ERR_ALIGN;
+    if (ws_bytes < llmq_rmsnorm_workspace_bytes(M)) return LLMQ_ERR_WORKSPACE;
+    return llmq::launch_rmsnorm_fwd(res_bf16, x_bf16, w_bf16, M, C, eps, x_bf16 ? res_out_bf16 : nullptr, y_bf16, rstd,
+                                    static_cast<unsigned*>(ws), fmt, d_amax_y, d_scale_y,
+                                    static_cast<hipStream_t>(stream));
+}
+
+int llmq_rmsnorm_apply_fp8(const void* res_bf16, const void* w_bf16, const float* rstd, int64_t M, int64_t C,
+                           const float* d_scale_y, int fmt, uint8_t* q, uint8_t* q_t, void* y_bf16, void* stream) {
+    if (!res_bf16 || !w_bf16 || !rstd || !d_scale_y || !q) return LLMQ_ERR_NULL;
+    if (!dim_ok(M) || !dim_ok(C) || C >= ((int64_t)1 << 24) || M * C >= kMaxElems) return LLMQ_ERR_SHAPE;
+    if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
+    if (!aligned(res_bf16, 16) || !aligned(w_bf16, 16) || !aligned(rstd, 16) || !aligned(d_scale_y, 4) ||
+        !aligned(q, 16) || !aligned(q_t, 16) || !aligned(y_bf16, 16))
+        return LLMQ_ERR_ALIGN;
+    return llmq::launch_rmsnorm_apply_fp8(res_bf16, w_bf16, rstd, M, C, d_scale_y, fmt, q, q_t, y_bf16,
+                                          static_cast<hipStream_t>(stream));
 }
 
 int llmq_calibrate_mfma(int fmtA, int fmtB, int random_bits, int iters, float* d_sink, double* flops,

@@ -32,6 +32,16 @@ int launch_swiglu_fwd(const void* gu, int64_t M, int64_t I, void* h, unsigned* p
 int launch_swiglu_bwd(const void* dh, const void* gu, int64_t M, int64_t I, void* dgu, unsigned* partial,
                       int amax_fmt, float* d_amax, float* d_scale, hipStream_t stream);
 
+// RMSNorm + residual addition with absmax of the output (x, res_out optional together), and the
+// element-wise recompute path that turns res, rstd and a known scale into FP8 codes (q_t, y optional).
+// rmsnorm_blocks() is the number of scratch words of the forward launch.
+int64_t rmsnorm_blocks(int64_t M);
+int launch_rmsnorm_fwd(const void* res, const void* x, const void* w, int64_t M, int64_t C, float eps,
+                       void* res_out, void* y, float* rstd, unsigned* partial, int fmt, float* d_amax,
+                       float* d_scale, hipStream_t stream);
+int launch_rmsnorm_apply_fp8(const void* res, const void* w, const float* rstd, int64_t M, int64_t C,
+                             const float* d_qscale, int fmt, uint8_t* q, uint8_t* q_t, void* y, hipStream_t stream);
+
 int launch_calibrate_mfma(int fmtA, int fmtB, int random_bits, int iters, float* d_sink, hipStream_t stream,
                           int num_cus);
 int launch_calibrate_copy(const void* src, void* dst, size_t bytes, hipStream_t stream);

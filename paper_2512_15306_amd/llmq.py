@@ -25,7 +25,8 @@ EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "l
            "llmq_fp8_linear_workspace_bytes", "llmq_fp8_linear_workspace_offsets",
            "llmq_fp8_linear_fwd", "llmq_fp8_linear_dgrad", "llmq_fp8_linear_wgrad",
            "llmq_scale_from_amax", "llmq_swiglu_workspace_bytes", "llmq_swiglu_fwd", "llmq_swiglu_fwd_fp8",
-           "llmq_swiglu_bwd", "llmq_calibrate_mfma", "llmq_calibrate_copy"]
+           "llmq_swiglu_bwd", "llmq_rmsnorm_workspace_bytes", "llmq_rmsnorm_fwd", "llmq_rmsnorm_apply_fp8",
+           "llmq_calibrate_mfma", "llmq_calibrate_copy"]
 
 
 class LlmqError(RuntimeError):
@@ -77,6 +78,12 @@ def lib() -> ctypes.CDLL:
     L.llmq_swiglu_fwd_fp8.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp, vp]
     L.llmq_swiglu_bwd.restype = i32
     L.llmq_swiglu_bwd.argtypes = [vp, vp, i64, i64, vp, i32, vp, vp, vp, sz, vp]
+    L.llmq_rmsnorm_workspace_bytes.restype = sz
+    L.llmq_rmsnorm_workspace_bytes.argtypes = [i64]
+    L.llmq_rmsnorm_fwd.restype = i32
+    L.llmq_rmsnorm_fwd.argtypes = [vp, vp, vp, i64, i64, c.c_float, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+    L.llmq_rmsnorm_apply_fp8.restype = i32
+    L.llmq_rmsnorm_apply_fp8.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, vp, vp, vp]
     L.llmq_calibrate_mfma.restype = i32
     L.llmq_calibrate_mfma.argtypes = [i32, i32, i32, i32, vp, c.POINTER(c.c_double), vp]
     L.llmq_calibrate_copy.restype = i32
@@ -230,6 +237,36 @@ def llmq_swiglu_bwd(dh: torch.Tensor, gu: torch.Tensor, dgu: torch.Tensor, fmt: 
                                  _dev(dgu, torch.bfloat16, "dgu"), fmt, _dev(d_amax_dgu, torch.float32, "d_amax_dgu"),
                                  _dev(d_scale_dgu, torch.float32, "d_scale_dgu"), _dev(ws, torch.uint8, "ws"),
                                  ws.numel(), _stream()), "llmq_swiglu_bwd")
+
+
+def llmq_rmsnorm_workspace_bytes(M: int) -> int:
+    return int(lib().llmq_rmsnorm_workspace_bytes(M))
+
+
+def llmq_rmsnorm_fwd(res: torch.Tensor, x: Optional[torch.Tensor], w: torch.Tensor, eps: float,
+                     res_out: Optional[torch.Tensor], y: torch.Tensor, rstd: torch.Tensor, fmt: int,
+                     d_amax_y: torch.Tensor, d_scale_y: Optional[torch.Tensor], ws: torch.Tensor) -> None:
+    M, C = res.shape
+    if w.numel() != C or y.numel() != M * C or rstd.numel() != M or (x is not None and x.numel() != M * C) or \
+            (res_out is not None and res_out.numel() != M * C):
+        raise ValueError("shape mismatch")
+    _check(lib().llmq_rmsnorm_fwd(_dev(res, torch.bfloat16, "res"), _dev(x, torch.bfloat16, "x"),
+                                  _dev(w, torch.bfloat16, "w"), M, C, float(eps), _dev(res_out, torch.bfloat16, "res_out"),
+                                  _dev(y, torch.bfloat16, "y"), _dev(rstd, torch.float32, "rstd"), fmt,
+                                  _dev(d_amax_y, torch.float32, "d_amax_y"), _dev(d_scale_y, torch.float32, "d_scale_y"),
+                                  _dev(ws, torch.uint8, "ws"), ws.numel(), _stream()), "llmq_rmsnorm_fwd")
+
+
+def llmq_rmsnorm_apply_fp8(res: torch.Tensor, w: torch.Tensor, rstd: torch.Tensor, d_scale_y: torch.Tensor, fmt: int,
+                           q: torch.Tensor, q_t: Optional[torch.Tensor], y: Optional[torch.Tensor] = None) -> None:
+    M, C = res.shape
+    if w.numel() != C or rstd.numel() != M or q.numel() != M * C or (q_t is not None and q_t.numel() != M * C) or \
+            (y is not None and y.numel() != M * C):
+        raise ValueError("shape mismatch")
+    _check(lib().llmq_rmsnorm_apply_fp8(_dev(res, torch.bfloat16, "res"), _dev(w, torch.bfloat16, "w"),
+                                        _dev(rstd, torch.float32, "rstd"), M, C, _dev(d_scale_y, torch.float32, "d_scale_y"),
+                                        fmt, _dev(q, torch.uint8, "q"), _dev(q_t, torch.uint8, "q_t"),
+                                        _dev(y, torch.bfloat16, "y"), _stream()), "llmq_rmsnorm_apply_fp8")
 
 
 def llmq_calibrate_mfma(fmtA: int, fmtB: int, random_bits: bool, iters: int, d_sink: torch.Tensor) -> float:

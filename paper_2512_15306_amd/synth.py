@@ -63,7 +63,8 @@ CONFIGS: Dict[int, Config] = {
 
 
 def tensor_seed(config: int, linear: int, which: int) -> int:
-    """which: 0 = X, 1 = W, 2 = dY, 3 = outlier-channel permutation, 4 = GU (SwiGLU input), 5 = dh."""
+    """which: 0 = X, 1 = W, 2 = dY, 3 = outlier-channel permutation, 4 = GU (SwiGLU input), 5 = dh,
+    6 = branch output added to the residual stream, 7 = RMSNorm weight."""
     return BASE_SEED + 1000 * config + 10 * linear + which
 
 
@@ -136,6 +137,18 @@ def make_dh(cfg: Config, device="cpu", M: Optional[int] = None) -> torch.Tensor:
     M = cfg.M if M is None else M
     dh = _randn((M, cfg.linears[li].N // 2), device, tensor_seed(cfg.index, li, 5)) * cfg.dy_std
     return dh.to(torch.bfloat16)
+
+
+def make_norm_inputs(cfg: Config, device="cpu", M: Optional[int] = None):
+    """(res, x, w) of the RMSNorm in front of the block's first linear: the residual stream res[M, C]
+    with the config's activation distribution (outlier channels included), the branch output x[M, C]
+    added to it (N(0, 0.5)) and the norm's weight w[C] (1 + N(0, 0.1)); C is the hidden size."""
+    M = cfg.M if M is None else M
+    C = cfg.linears[0].K
+    res = make_x(cfg, 0, device=device, M=M)
+    x = (_randn((M, C), device, tensor_seed(cfg.index, 0, 6)) * 0.5).to(torch.bfloat16)
+    w = (1.0 + _randn((C,), device, tensor_seed(cfg.index, 0, 7)) * 0.1).to(torch.bfloat16)
+    return res, x, w
 
 
 def linear_flops(cfg: Config) -> int:
