@@ -171,6 +171,34 @@ def measure_swiglu(cfg, dev, reps):
     return out
 
 
+def measure_rmsnorm(cfg, dev, reps):
+    """RMSNorm + residual addition in front of the block's first linear: forward (res', y, rstd, absmax:
+    4 B read + 4 B written per element) and the recompute path (stored stream + statistics -> FP8 in both
+    layouts: 2 B read + 2 B written)."""
+    import torch
+    from paper_2512_15306_amd import llmq, synth
+    res, x, w = synth.make_norm_inputs(cfg, device=dev)
+    M, C = res.shape
+    res_out, y = torch.empty_like(res), torch.empty_like(res)
+    rstd = torch.empty(M, dtype=torch.float32, device=dev)
+    q = torch.empty((M, C), dtype=torch.uint8, device=dev)
+    qt = torch.empty((C, M), dtype=torch.uint8, device=dev)
+    f = torch.ones(2, dtype=torch.float32, device=dev)
+    ws = torch.empty(llmq.llmq_rmsnorm_workspace_bytes(M), dtype=torch.uint8, device=dev)
+    n = float(M) * C
+    legs = {
+        "fwd_add_norm_absmax": (8.0, lambda: llmq.llmq_rmsnorm_fwd(res, x, w, 1e-6, res_out, y, rstd, llmq.E4M3, f[0:1], f[1:2], ws)),
+        "recompute_fp8_both_layouts": (4.0, lambda: llmq.llmq_rmsnorm_apply_fp8(res_out, w, rstd, f[1:2], llmq.E4M3, q, qt, None)),
+    }
+    out = {"M": M, "C": C}
+    for name, (bpe, fn) in legs.items():
+        fn()
+        ms = timed(fn, reps)
+        out[name] = {"ms": round(ms, 4), "gbps": round(bpe * n / (ms * 1e-3) / 1e9, 1),
+                     "pct_hbm_peak": round(100.0 * bpe * n / (ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2)}
+    return out
+
+
 def cpu_baseline(cfg):
     """The oracle as it stands on a bounded sample: the largest linear of the block restricted to the
     first rows of the token dimension, whole path (3 absmax, 3 quantize+transpose, 3 fp64 GEMMs)."""
@@ -276,6 +304,7 @@ def main():
     del states
     torch.cuda.empty_cache()
     out["swiglu"] = measure_swiglu(cfg, dev, reps)
+    out["rmsnorm"] = measure_rmsnorm(cfg, dev, reps)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
