@@ -77,6 +77,9 @@ struct GemmTuning {
     // loads with the first 1 / kVmSpread.
     static constexpr int kDsSpread = 2, kVmSpread = 1;
     static constexpr bool kNtStoreC = false;     // streaming hint on the output stores
+    // Scheduling fences between the 32-row blocks of the epilogue: without them the compiler hoists every
+    // de-scale multiply to the front and parks the products in accumulator registers.
+    static constexpr bool kEpilogueFence = true;
     // Development aid: a tuning struct with kProfile = true also provides
     //   static __device__ void record(int block, int slot, long long value)
     // and gets cycle stamps of the phases of wave 0 of every workgroup.
@@ -85,6 +88,9 @@ struct GemmTuning {
     // (row >> kSwizzleShift) & 7.
     static constexpr int kSwizzleShift = 1;
 };
+
+template <bool B>
+struct BoolTag { static constexpr bool value = B; };
 
 template <int N>
 __device__ inline void wait_vmcnt() {
@@ -128,7 +134,7 @@ template <int FA, int FB, int NI, int NJ, bool ACCUM, class V = GemmTuning>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ C,
     int Cn, int T, const float* __restrict__ d_sA, const float* __restrict__ d_sB,
-    unsigned* __restrict__ amax_bits, int tiles_r, int tiles_c, int touch_ahead, int band_rows) {
+    unsigned* __restrict__ amax_bits, int tiles_r, int tiles_c, int touch_ahead, int band_rows, int next_stride) {
     constexpr int BM = 64 * NI, BN = 64 * NJ;
     constexpr int kSlabA = BM * BK, kSlabB = BN * BK;
     // One array per stage and operand: distinct LDS objects let the compiler see that the
@@ -287,6 +293,25 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         asm volatile("" ::"v"(touch_sink));
     }
     stamp(2);
+    // The workgroup that follows on this XCD (id + next_stride: same XCD, and dispatched about when this
+    // one retires) starts with two slabs of its own operands; one dword per 128-byte line of them is
+    // requested here, so that they reach the L2 while this workgroup is busy with its epilogue.
+    int next_touch[4] = {0, 0, 0, 0};
+    if constexpr (kTouch) {
+        int ntr, ntc;
+        if (next_stride > 0 && T >= 2 * BK && tile_of_block(blockIdx.x + next_stride, tiles_r, tiles_c, band_rows, ntr, ntc)) {
+            const uint8_t* na = A + ((size_t)ntr * BM + wave * (BM / 4) + lane) * T;
+            const uint8_t* nb = B + ((size_t)ntc * BN + wave * (BN / 4) + lane) * T;
+            if (lane < BM / 4) {
+                next_touch[0] = *reinterpret_cast<const int*>(na);
+                next_touch[1] = *reinterpret_cast<const int*>(na + BK);
+            }
+            if (lane < BN / 4) {
+                next_touch[2] = *reinterpret_cast<const int*>(nb);
+                next_touch[3] = *reinterpret_cast<const int*>(nb + BK);
+            }
+        }
+    }
 
     // ---- epilogue.  Per 32x32 block a lane holds 4 groups of 4 consecutive columns of row (lane % 32).
     // Storing those 8-byte pieces directly scatters every store over 32 rows; instead each wave
@@ -296,31 +321,29 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
     // 32 rows and the 16-byte reads spread over the banks.  The region is private to the wave and LDS
     // executes a wave's accesses in order, so no further barrier is needed.
     // De-scale with one multiply by 1 / (sA sB) unless that product leaves the normal range (degenerate
-    // scales such as FLT_MAX for an all-zero tensor), in which case the two factors are applied in turn.
+    // scales such as FLT_MAX for an all-zero tensor), in which case the two factors are applied in turn
+    // (a second copy of the epilogue, so that the usual path carries no trace of it).
     const float inv_a = 1.0f / scale_a, inv_b = 1.0f / scale_b;
     const float inv_ab = inv_a * inv_b;
     const bool one_mul = inv_ab >= 1.17549435e-38f && inv_ab <= 3.402823466e+38f;
     const float m1 = one_mul ? inv_ab : inv_a;
-    if (!one_mul) {                       // rare and uniform: apply the second factor to the accumulators first
-#pragma unroll
-        for (int i = 0; i < NI; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] *= inv_b;
-    }
-    auto descale4 = [&](const v16f& block, int g) -> v4f {
-        v4f y;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) y[e] = block[4 * g + e] * m1;
-        return y;
-    };
     // The output absmax is taken in fp32 before rounding: rounding to BF16 is monotonic, so the BF16
     // rounding of the largest |y| is the largest rounded magnitude.
     float maxabs = 0.0f;
     auto track4 = [&](const v4f& y) {
         maxabs = __builtin_fmaxf(__builtin_fmaxf(maxabs, __builtin_fabsf(y[0])), __builtin_fabsf(y[1]));
         maxabs = __builtin_fmaxf(__builtin_fmaxf(maxabs, __builtin_fabsf(y[2])), __builtin_fabsf(y[3]));
+    };
+    // The body exists twice, for one and for two de-scale multiplies; the choice is uniform over the grid.
+    auto write_out = [&](auto two_mul) {
+    auto descale4 = [&](const v16f& block, int g) -> v4f {
+        v4f y;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            y[e] = block[4 * g + e] * m1;
+            if constexpr (decltype(two_mul)::value) y[e] *= inv_b;
+        }
+        return y;
     };
     if constexpr (!ACCUM) {
         constexpr int kSlots = 4 * NJ;                                       // 16-byte slots per staged row
@@ -339,6 +362,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         // one block of 32 rows at a time: while its stores are in flight the next block is converted
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
+            if constexpr (V::kEpilogueFence) __builtin_amdgcn_sched_barrier(0);
             const int row = i * 32 + fr_row;
             uint8_t* srow = stage + row * kPitch;
 #pragma unroll
@@ -353,12 +377,23 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
                     *reinterpret_cast<bf16x4*>(srow + off) = o;
                 }
             }
+            // all pieces of the block are read back before the first is stored, so that the LDS round
+            // trips overlap instead of each store waiting for its own read
+            constexpr int kPiecesPerLane = kBlockPieces / kWave;
+            v4u piece[kPiecesPerLane];
 #pragma unroll
-            for (int p = lane; p < kBlockPieces; p += kWave) {
+            for (int k = 0; k < kPiecesPerLane; ++k) {
+                const int p = lane + k * kWave;
                 const int r = i * 32 + p / kSlots, sl = p % kSlots;
-                v4u v = *reinterpret_cast<const v4u*>(stage + r * kPitch + (((sl + r) % kSlots) << 4));
-                if constexpr (V::kNtStoreC) __builtin_nontemporal_store(v, reinterpret_cast<v4u*>(cbase + (size_t)r * Cn + sl * 8));
-                else *reinterpret_cast<v4u*>(cbase + (size_t)r * Cn + sl * 8) = v;
+                piece[k] = *reinterpret_cast<const v4u*>(stage + r * kPitch + (((sl + r) % kSlots) << 4));
+            }
+            if constexpr (V::kEpilogueFence) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < kPiecesPerLane; ++k) {
+                const int p = lane + k * kWave;
+                const int r = i * 32 + p / kSlots, sl = p % kSlots;
+                if constexpr (V::kNtStoreC) __builtin_nontemporal_store(piece[k], reinterpret_cast<v4u*>(cbase + (size_t)r * Cn + sl * 8));
+                else *reinterpret_cast<v4u*>(cbase + (size_t)r * Cn + sl * 8) = piece[k];
             }
         }
         if constexpr (V::kProfile) stamp(4);
@@ -386,6 +421,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
             }
         }
     }
+    };
+    if (one_mul) write_out(BoolTag<false>{}); else write_out(BoolTag<true>{});
+    if constexpr (kTouch) asm volatile("" ::"v"(next_touch[0] ^ next_touch[1] ^ next_touch[2] ^ next_touch[3]));
     unsigned mag = (unsigned)__builtin_bit_cast(uint16_t, (__bf16)maxabs);   // non-negative: magnitude bits
     if (amax_bits) {
         mag = wave_max_u32(mag);
@@ -527,22 +565,34 @@ static int touch_ahead_pair() {
     return 0;
 }
 
+// Whether a workgroup requests the first slabs of its successor; LLMQ_GEMM_TOUCH_NEXT=0 / 1 overrides it.
+static bool touch_next(bool by_default) {
+    if (const char* e = getenv("LLMQ_GEMM_TOUCH_NEXT")) return atoi(e) != 0;
+    return by_default;
+}
+
 template <int FA, int FB, int NI, int NJ>
 static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
                         const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
-                        hipStream_t stream) {
+                        hipStream_t stream, int num_cus) {
     const int tiles_r = (int)(R / (64 * NI)), tiles_c = (int)(C / (64 * NJ));
     const int nt = tiles_r * tiles_c;
     const int grid = ((nt + kXcds - 1) / kXcds) * kXcds;
     const int touch = (NI == 2 && NJ == 2) ? touch_ahead_pair() : touch_ahead();
+    // workgroups resident on the chip at once (a multiple of the XCD count): the distance to the
+    // workgroup that takes over a slot
+    // (measured: +3 % on a GEMM of 19 rounds of tiles, whose later workgroups otherwise start on cold
+    // operands; nothing or slightly less on GEMMs of 2-4 rounds, so it is used from 6 rounds on)
+    const int slots = (num_cus / kXcds) * kXcds * ((NI == 2 && NJ == 2) ? 2 : 1);
+    const int next_stride = touch_next(nt >= 6 * slots) ? slots : 0;
     if (accumulate)
         hipLaunchKernelGGL((gemm_tn_tile_kernel<FA, FB, NI, NJ, true>), dim3(grid), dim3(kGemmThreads), 0, stream,
                            A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c,
-                           touch, band_rows());
+                           touch, band_rows(), next_stride);
     else
         hipLaunchKernelGGL((gemm_tn_tile_kernel<FA, FB, NI, NJ, false>), dim3(grid), dim3(kGemmThreads), 0, stream,
                            A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c,
-                           touch, band_rows());
+                           touch, band_rows(), next_stride);
 }
 
 template <int FA, int FB>
@@ -552,7 +602,7 @@ static void launch_one(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C,
     const TileChoice tc = choose_tile(R, C, T, num_cus);
 #define LLMQ_TILE_CASE(I, J)                                                                      \
     case I * 8 + J:                                                                               \
-        launch_tile<FA, FB, I, J>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream);            \
+        launch_tile<FA, FB, I, J>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus);   \
         return;
     switch (tc.ni * 8 + tc.nj) {
         LLMQ_TILE_CASE(4, 4) LLMQ_TILE_CASE(4, 3) LLMQ_TILE_CASE(4, 2)
