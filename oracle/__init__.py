@@ -91,6 +91,10 @@ def _load():
     lib.oracle_rmsnorm_exact.argtypes = [u16p, u16p, c.c_int64, c.c_int64, c.c_double, f64p]
     lib.oracle_rmsnorm_apply.restype = None
     lib.oracle_rmsnorm_apply.argtypes = [u16p, u16p, f32p, c.c_int64, c.c_int64, u16p]
+    lib.oracle_gemm_bf16_tn.restype = None
+    lib.oracle_gemm_bf16_tn.argtypes = [u16p, u16p, c.c_int64, c.c_int64, c.c_int64, f64p, f64p]
+    lib.oracle_gemm_bf16_tn_sampled.restype = None
+    lib.oracle_gemm_bf16_tn_sampled.argtypes = [u16p, u16p, c.c_int64, i64p, i64p, c.c_int64, f64p, f64p]
     lib.oracle_num_threads.restype = c.c_int
     lib.oracle_num_threads.argtypes = []
     _lib = lib
@@ -293,6 +297,40 @@ def rmsnorm_apply(res_bits: np.ndarray, w_bits: np.ndarray, rstd: np.ndarray) ->
     _load().oracle_rmsnorm_apply(_ptr(r, ctypes.c_uint16), _ptr(w, ctypes.c_uint16), _ptr(s, ctypes.c_float),
                                  M, C, _ptr(y, ctypes.c_uint16))
     return y
+
+
+def gemm_bf16_tn(A_bits: np.ndarray, B_bits: np.ndarray):
+    """y[r,c] = sum_t A[r,t] B[c,t] on BF16 bit patterns, binary64, with the matching sum of |products|."""
+    A, B = _as(A_bits, np.uint16), _as(B_bits, np.uint16)
+    R, T = A.shape
+    C, T2 = B.shape
+    if T != T2:
+        raise ValueError("contraction lengths differ")
+    y = np.empty((R, C), np.float64)
+    S = np.empty((R, C), np.float64)
+    _load().oracle_gemm_bf16_tn(_ptr(A, ctypes.c_uint16), _ptr(B, ctypes.c_uint16), R, C, T,
+                                _ptr(y, ctypes.c_double), _ptr(S, ctypes.c_double))
+    return y, S
+
+
+def gemm_bf16_tn_sampled(A_bits, B_bits, rr, cc):
+    A, B = _as(A_bits, np.uint16), _as(B_bits, np.uint16)
+    R, T = A.shape
+    C, T2 = B.shape
+    if T != T2:
+        raise ValueError("contraction lengths differ")
+    rr = np.ascontiguousarray(rr, dtype=np.int64)
+    cc = np.ascontiguousarray(cc, dtype=np.int64)
+    if rr.shape != cc.shape or rr.ndim != 1:
+        raise ValueError("index lists must be 1-D and equally long")
+    if rr.size and (rr.min() < 0 or rr.max() >= R or cc.min() < 0 or cc.max() >= C):
+        raise IndexError("sample index out of range")
+    y = np.empty(rr.shape, np.float64)
+    S = np.empty(rr.shape, np.float64)
+    _load().oracle_gemm_bf16_tn_sampled(_ptr(A, ctypes.c_uint16), _ptr(B, ctypes.c_uint16), T,
+                                        _ptr(rr, ctypes.c_int64), _ptr(cc, ctypes.c_int64), rr.size,
+                                        _ptr(y, ctypes.c_double), _ptr(S, ctypes.c_double))
+    return y, S
 
 
 def num_threads() -> int:

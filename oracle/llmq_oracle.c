@@ -420,6 +420,45 @@ void oracle_rmsnorm_apply(const uint16_t* res, const uint16_t* w, const float* r
         }
 }
 
+/* ---- BF16 contraction: the baseline the FP8 path is compared with (Section 4, "Impact of FP8") ------ */
+
+/*
+ * The paper reports its FP8 results next to a pure BF16 run of the same model (speed-up column of
+ * Table 1).  The baseline GEMM has the same form as the FP8 one, on BF16 operands and without scales:
+ *   y[r,c] = sum_t A[r,t] * B[c,t],   S[r,c] = sum_t |A[r,t] * B[c,t]|,   A [R,T], B [C,T] BF16 bit patterns.
+ * Products of two BF16 numbers are exact in binary64; the sum is taken in binary64.
+ */
+void oracle_gemm_bf16_tn(const uint16_t* A, const uint16_t* B, int64_t R, int64_t C, int64_t T,
+                         double* y, double* S) {
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < R; ++r)
+        for (int64_t c = 0; c < C; ++c) {
+            double acc = 0.0, mag = 0.0;
+            for (int64_t t = 0; t < T; ++t) {
+                double prod = (double)oracle_bf16_to_f32(A[r * T + t]) * (double)oracle_bf16_to_f32(B[c * T + t]);
+                acc += prod;
+                mag += fabs(prod);
+            }
+            if (y) y[r * C + c] = acc;
+            if (S) S[r * C + c] = mag;
+        }
+}
+
+void oracle_gemm_bf16_tn_sampled(const uint16_t* A, const uint16_t* B, int64_t T,
+                                 const int64_t* rr, const int64_t* cc, int64_t n, double* y, double* S) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        double acc = 0.0, mag = 0.0;
+        for (int64_t t = 0; t < T; ++t) {
+            double prod = (double)oracle_bf16_to_f32(A[rr[i] * T + t]) * (double)oracle_bf16_to_f32(B[cc[i] * T + t]);
+            acc += prod;
+            mag += fabs(prod);
+        }
+        if (y) y[i] = acc;
+        if (S) S[i] = mag;
+    }
+}
+
 /* Threads the OpenMP loops above will use (reported by the benchmark). */
 #ifdef _OPENMP
 #include <omp.h>
