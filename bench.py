@@ -21,6 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP8_TFLOPS = 5000.0      # MI355X dense FP8 MFMA, published
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense BF16 MFMA, published
 PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E, published
 # L2 <-> fabric bytes per GEMM launch (fetched + written, averaged over the step's launches), from
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by a plain 1 GiB copy
@@ -137,6 +138,30 @@ def measure_peaks(dev):
     ms = timed(lambda: llmq.llmq_calibrate_copy(src, dst), 5)
     out["hbm_copy_gbps"] = round(2.0 * src.numel() / (ms * 1e-3) / 1e9, 1)
     return out
+
+
+def measure_bf16_baseline(cfg, dev, reps):
+    """The same three GEMMs per linear in BF16 (no quantization): what a BF16 run of the block spends on its
+    linears.  The kernel wants both operands contraction-contiguous, so the transposed copies a BF16
+    framework would not need (it would use other GEMM layouts) are made outside the timed region."""
+    import torch
+    from paper_2512_15306_amd import llmq, synth
+    ops = []
+    for li, lin in enumerate(cfg.linears):
+        X, W, dY = synth.make_x(cfg, li, device=dev), synth.make_w(cfg, li, device=dev), synth.make_dy(cfg, li, device=dev)
+        Xt, Wt, dYt = X.t().contiguous(), W.t().contiguous(), dY.t().contiguous()
+        M, K, N = cfg.M, lin.K, lin.N
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        dX = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+        dW = torch.empty((N, K), dtype=torch.bfloat16, device=dev)
+        ops += [(X, W, Y), (dY, Wt, dX), (dYt, Xt, dW)]
+
+    def run():
+        for a, b, c in ops:
+            llmq.llmq_bf16_gemm_tn(a, b, c)
+    run()
+    ms = timed(run, reps)
+    return ms
 
 
 def measure_swiglu(cfg, dev, reps):
@@ -303,6 +328,16 @@ def main():
     }
     del states
     torch.cuda.empty_cache()
+    ms_bf16 = measure_bf16_baseline(cfg, dev, reps)
+    torch.cuda.empty_cache()
+    bf16_tflops = flops / (ms_bf16 * 1e-3) / 1e12
+    out["bf16_baseline"] = {
+        "what": "fwd+dgrad+wgrad GEMMs of the same linears on BF16 operands (v_mfma_f32_32x32x16_bf16, same tile "
+                "kernel), no quantization, pre-transposed operands",
+        "ms_per_step": round(ms_bf16, 4), "tflops": round(bf16_tflops, 2),
+        "pct_bf16_peak": round(100.0 * bf16_tflops / PEAK_BF16_TFLOPS, 2),
+        "fp8_gemm_only_speedup": round(ms_bf16 / ms_gemm, 3),
+        "fp8_whole_step_speedup": round(ms_bf16 / ms_step, 3)}
     out["swiglu"] = measure_swiglu(cfg, dev, reps)
     out["rmsnorm"] = measure_rmsnorm(cfg, dev, reps)
     if not args.no_cpu_baseline:

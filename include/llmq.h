@@ -105,6 +105,18 @@ int llmq_fp8_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB,
                      void* c_bf16, int accumulate, float* d_amax_c, void* stream);
 
 /*
+ * BF16 baseline of the same contraction, for the FP8-versus-BF16 comparison the paper reports (Section 4,
+ * "Impact of FP8", speed-up column of Table 1): no quantization, no scales,
+ *   c[r,cc] = bf16( sum_t A[r,t] * B[cc,t] )   (+ c[r,cc] first when accumulate != 0)
+ * A [R,T], B [C,T] BF16 with the contraction index contiguous, binary32 accumulation on the matrix cores
+ * (v_mfma_f32_32x32x16_bf16 in the same tile kernel), one RNE rounding.  Error per element is bounded by
+ * 2^-8 |c| + T 2^-24 sum_t |A[r,t] B[cc,t]|.  Shapes with R, C multiples of 128 and T a multiple of 64
+ * take the tuned kernel, others a slow generic one.
+ */
+int llmq_bf16_gemm_tn(const void* A_bf16, const void* B_bf16, int64_t R, int64_t C, int64_t T,
+                      void* c_bf16, int accumulate, void* stream);
+
+/*
  * Workspace of the three linear-layer calls below, for one (M, N, K).  It holds the FP8 copies
  *   Xq [M,K], Xq_t [K,M], Wq [N,K], Wq_t [K,N], dYq [M,N], dYq_t [N,M]
  * in this order, each starting at a multiple of 256 bytes; llmq_fp8_linear_workspace_offsets() returns

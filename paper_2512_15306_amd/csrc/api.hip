@@ -114,6 +114,16 @@ int llmq_fp8_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int
                                 static_cast<hipStream_t>(stream), num_cus());
 }
 
+int llmq_bf16_gemm_tn(const void* A_bf16, const void* B_bf16, int64_t R, int64_t C, int64_t T, void* c_bf16,
+                      int accumulate, void* stream) {
+    if (!A_bf16 || !B_bf16 || !c_bf16) return LLMQ_ERR_NULL;
+    if (!dim_ok(R) || !dim_ok(C) || !dim_ok(T)) return LLMQ_ERR_SHAPE;
+    if (R * T >= kMaxElems || C * T >= kMaxElems || R * C >= kMaxElems) return LLMQ_ERR_SHAPE;
+    if (!aligned(A_bf16, 16) || !aligned(B_bf16, 16) || !aligned(c_bf16, 16)) return LLMQ_ERR_ALIGN;
+    return llmq::launch_gemm_bf16_tn(A_bf16, B_bf16, R, C, T, c_bf16, accumulate, static_cast<hipStream_t>(stream),
+                                     num_cus());
+}
+
 size_t llmq_fp8_linear_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     if (!dim_ok(M) || !dim_ok(N) || !dim_ok(K)) return 0;
     return ws_layout(M, N, K).total;

@@ -105,13 +105,29 @@ __device__ inline void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Operand kinds of the tuned kernel: 0 = E4M3, 1 = E5M2 (one byte per element, any mix), 2 = BF16 (both
+// operands; the baseline the FP8 path is compared with).  The kernel itself moves bytes: T is the length of
+// a row in bytes, and a lane's 32-byte fragment holds 32 FP8 or 16 BF16 contraction elements.
+constexpr int kFmtBf16 = 2;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
 template <int FA, int FB, int NI, int NJ>
 __device__ inline void mma_block(v16f (&acc)[NI][NJ], const v8i (&a)[NI], const v8i (&b)[NJ]) {
+    static_assert((FA == kFmtBf16) == (FB == kFmtBf16), "BF16 operands come in pairs");
 #pragma unroll
     for (int i = 0; i < NI; ++i)
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[i][j], FB, FA, 0, 0, 0, 0);
+        for (int j = 0; j < NJ; ++j) {
+            if constexpr (FA == kFmtBf16) {
+                // two v_mfma_f32_32x32x16_bf16, one per 16-byte half of the fragments
+                const v4i a_lo = {a[i][0], a[i][1], a[i][2], a[i][3]}, a_hi = {a[i][4], a[i][5], a[i][6], a[i][7]};
+                const v4i b_lo = {b[j][0], b[j][1], b[j][2], b[j][3]}, b_hi = {b[j][4], b[j][5], b[j][6], b[j][7]};
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b_lo), __builtin_bit_cast(bf16x8, a_lo), acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b_hi), __builtin_bit_cast(bf16x8, a_hi), acc[i][j], 0, 0, 0);
+            } else {
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[i][j], FB, FA, 0, 0, 0, 0);
+            }
+        }
 }
 
 // Interleave NM MFMAs with ND LDS reads, spread over the first NM / DS_SPREAD MFMAs (so that they have
@@ -160,7 +176,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         }
     };
     stamp(0);
-    const float scale_a = *d_sA, scale_b = *d_sB;     // requested now, needed in the epilogue
+    // requested now, needed in the epilogue; BF16 operands carry no scales
+    const float scale_a = FA == kFmtBf16 ? 1.0f : *d_sA, scale_b = FB == kFmtBf16 ? 1.0f : *d_sB;
 
     // ---- global -> LDS: one instruction moves 8 rows x 128 B.  Wave w moves rows [16 NI w, 16 NI (w+1))
     // of the A slab with 2 NI instructions and rows [16 NJ w, ...) of the B slab with 2 NJ.
@@ -186,6 +203,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         }
     };
     constexpr int kLoadsPerStep = 2 * (NI + NJ);
+    constexpr int kMfmaPerHalf = NI * NJ * (FA == kFmtBf16 ? 2 : 1);
 
     // ---- LDS -> registers: lane reads 32 contiguous bytes (two swizzled 16-byte chunks) of its row
     const int fr_row = lane & 31;
@@ -242,7 +260,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         read_frags(curA, offA, 1, a1);
         read_frags(curB, offB, 1, b1);
         mma_block<FA, FB, NI, NJ>(acc, a0, b0);
-        interleave<NI * NJ, kLoadsPerStep, 0, V::kDsSpread, V::kVmSpread, 0>();
+        interleave<kMfmaPerHalf, kLoadsPerStep, 0, V::kDsSpread, V::kVmSpread, 0>();
         // the direct-to-LDS loads of the previous step must have landed; its two touch loads, issued
         // after them, may still be in flight
         if constexpr (kTouch) wait_vmcnt<2>(); else wait_vmcnt<0>();
@@ -252,7 +270,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         read_frags(nxtA, offA, 0, a0);          // past the last slab this reads bytes that are never used
         read_frags(nxtB, offB, 0, b0);
         mma_block<FA, FB, NI, NJ>(acc, a1, b1);
-        interleave<NI * NJ, kLoadsPerStep, kLoadsPerStep, V::kDsSpread, V::kVmSpread, 1>();
+        interleave<kMfmaPerHalf, kLoadsPerStep, kLoadsPerStep, V::kDsSpread, V::kVmSpread, 1>();
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (kTouch) {
             const int kp = kt + 2 + touch_ahead;
@@ -506,6 +524,21 @@ __global__ __launch_bounds__(256) void gemm_tn_generic_kernel(
     }
 }
 
+// BF16 operands, any shape: one output element per lane and trip, binary32 accumulation along t.
+__global__ __launch_bounds__(256) void gemm_bf16_generic_kernel(
+    const uint16_t* __restrict__ A, const uint16_t* __restrict__ B, uint16_t* __restrict__ C,
+    int64_t R, int64_t Cn, int64_t T, int accumulate) {
+    const int64_t n = R * Cn;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n; idx += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t r = idx / Cn, c = idx - r * Cn;
+        float acc = 0.0f;
+        for (int64_t t = 0; t < T; ++t)
+            acc = __builtin_fmaf(__uint_as_float((unsigned)A[r * T + t] << 16), __uint_as_float((unsigned)B[c * T + t] << 16), acc);
+        if (accumulate) acc += __uint_as_float((unsigned)C[idx] << 16);
+        C[idx] = __builtin_bit_cast(uint16_t, (__bf16)acc);
+    }
+}
+
 __global__ void gemm_amax_reset_kernel(unsigned* amax_bits) {
     if (threadIdx.x == 0 && blockIdx.x == 0) *amax_bits = 0u;
 }
@@ -611,9 +644,18 @@ static void launch_one(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C,
         default: break;
     }
 #undef LLMQ_TILE_CASE
-    dim3 grid((unsigned)((C + 31) / 32), (unsigned)((R + 31) / 32));
-    hipLaunchKernelGGL((gemm_tn_generic_kernel<FA, FB>), grid, dim3(256), 0, stream,
-                       A, B, reinterpret_cast<uint16_t*>(c), R, C, T, sA, sB, accumulate, amax);
+    if constexpr (FA == kFmtBf16) {
+        const int64_t n = R * C;
+        int64_t blocks = (n + 255) / 256;
+        if (blocks > 65536) blocks = 65536;
+        hipLaunchKernelGGL(gemm_bf16_generic_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           reinterpret_cast<const uint16_t*>(A), reinterpret_cast<const uint16_t*>(B),
+                           reinterpret_cast<uint16_t*>(c), R, C, T / 2, accumulate);
+    } else {
+        dim3 grid((unsigned)((C + 31) / 32), (unsigned)((R + 31) / 32));
+        hipLaunchKernelGGL((gemm_tn_generic_kernel<FA, FB>), grid, dim3(256), 0, stream,
+                           A, B, reinterpret_cast<uint16_t*>(c), R, C, T, sA, sB, accumulate, amax);
+    }
 }
 
 int launch_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64_t R, int64_t C,
@@ -625,6 +667,14 @@ int launch_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64
     else if (fmtA == 1 && fmtB == 0) launch_one<1, 0>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus);
     else if (fmtA == 0 && fmtB == 1) launch_one<0, 1>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus);
     else launch_one<1, 1>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus);
+    return hipGetLastError() == hipSuccess ? 0 : -6;
+}
+
+// BF16 baseline: same tile kernels with the BF16 MFMA; T counts elements here, rows are 2 T bytes long.
+int launch_gemm_bf16_tn(const void* A, const void* B, int64_t R, int64_t C, int64_t T, void* c_bf16,
+                        int accumulate, hipStream_t stream, int num_cus) {
+    launch_one<kFmtBf16, kFmtBf16>(reinterpret_cast<const uint8_t*>(A), reinterpret_cast<const uint8_t*>(B), R, C, 2 * T,
+                                   nullptr, nullptr, c_bf16, accumulate, nullptr, stream, num_cus);
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 

@@ -14,6 +14,9 @@ int launch_amax(const void* x, size_t n, int fmt, float* d_amax, float* d_scale,
 // workgroup of the first stage) becomes d_amax and, if d_scale is not NULL, the scale for fmt.
 int launch_amax_final(const unsigned* partial, int n_partial, int fmt, float* d_amax, float* d_scale,
                       hipStream_t stream);
+// BF16 x BF16 -> BF16 contraction without scales (T in elements), the baseline of the FP8 GEMM.
+int launch_gemm_bf16_tn(const void* A, const void* B, int64_t R, int64_t C, int64_t T, void* c_bf16,
+                        int accumulate, hipStream_t stream, int num_cus);
 int launch_scale_from_amax(const float* d_amax, int fmt, float* d_scale, hipStream_t stream);
 // zero_word: if not NULL, one 32-bit word the kernel also clears (the absmax accumulator of the GEMM
 // that follows in the same call, which saves a launch).

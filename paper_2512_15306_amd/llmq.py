@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libllmq.so")
 _lib = None
 
-EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "llmq_amax", "llmq_quantize_fp8", "llmq_fp8_gemm_tn",
+EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "llmq_amax", "llmq_quantize_fp8", "llmq_fp8_gemm_tn", "llmq_bf16_gemm_tn",
            "llmq_fp8_linear_workspace_bytes", "llmq_fp8_linear_workspace_offsets",
            "llmq_fp8_linear_fwd", "llmq_fp8_linear_dgrad", "llmq_fp8_linear_wgrad",
            "llmq_scale_from_amax", "llmq_swiglu_workspace_bytes", "llmq_swiglu_fwd", "llmq_swiglu_fwd_fp8",
@@ -58,6 +58,8 @@ def lib() -> ctypes.CDLL:
     L.llmq_quantize_fp8.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp]
     L.llmq_fp8_gemm_tn.restype = i32
     L.llmq_fp8_gemm_tn.argtypes = [vp, i32, vp, i32, i64, i64, i64, vp, vp, vp, i32, vp, vp]
+    L.llmq_bf16_gemm_tn.restype = i32
+    L.llmq_bf16_gemm_tn.argtypes = [vp, vp, i64, i64, i64, vp, i32, vp]
     L.llmq_fp8_linear_workspace_bytes.restype = sz
     L.llmq_fp8_linear_workspace_bytes.argtypes = [i64, i64, i64]
     L.llmq_fp8_linear_workspace_offsets.restype = i32
@@ -154,6 +156,15 @@ def llmq_fp8_gemm_tn(A: torch.Tensor, fmtA: int, B: torch.Tensor, fmtB: int, d_s
                                   _dev(d_scaleA, torch.float32), _dev(d_scaleB, torch.float32),
                                   _dev(c, torch.bfloat16, "c"), int(bool(accumulate)),
                                   _dev(d_amax_c, torch.float32), _stream()), "llmq_fp8_gemm_tn")
+
+
+def llmq_bf16_gemm_tn(A: torch.Tensor, B: torch.Tensor, c: torch.Tensor, accumulate: bool = False) -> None:
+    R, T = A.shape
+    C, T2 = B.shape
+    if T != T2 or tuple(c.shape) != (R, C):
+        raise ValueError("shape mismatch: A %s, B %s, c %s" % (tuple(A.shape), tuple(B.shape), tuple(c.shape)))
+    _check(lib().llmq_bf16_gemm_tn(_dev(A, torch.bfloat16, "A"), _dev(B, torch.bfloat16, "B"), R, C, T,
+                                   _dev(c, torch.bfloat16, "c"), int(bool(accumulate)), _stream()), "llmq_bf16_gemm_tn")
 
 
 def llmq_fp8_linear_workspace_bytes(M: int, N: int, K: int) -> int:
