@@ -160,7 +160,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
     __shared__ __attribute__((aligned(1024))) uint8_t ldsB0[kSlabB];
     __shared__ __attribute__((aligned(1024))) uint8_t ldsA1[kSlabA];
     __shared__ __attribute__((aligned(1024))) uint8_t ldsB1[kSlabB];
-    __shared__ unsigned s_amax[kGemmThreads / kWave];
+    // Four words for the workgroup's output absmax.  The epilogue stages 2048 NJ bytes per wave at the start
+    // of the slabs (8192 NJ bytes in the case of this one), so the end of the last slab is free by then; the
+    // kernel's LDS is exactly its slabs.
+    unsigned* s_amax = reinterpret_cast<unsigned*>(ldsB1 + kSlabB - 16);
     int tr, tc;
     if (!tile_of_block(blockIdx.x, tiles_r, tiles_c, band_rows, tr, tc)) return;   // uniform over the workgroup
 
@@ -333,8 +336,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
 
     // ---- epilogue.  Per 32x32 block a lane holds 4 groups of 4 consecutive columns of row (lane % 32).
     // Storing those 8-byte pieces directly scatters every store over 32 rows; instead each wave
-    // stages its quadrant (32 NI rows x 32 NJ BF16 columns, at most 32 KB) in one of the four slabs,
-    // which nobody reads any more, and writes it out as full row segments, 16 bytes per lane.  The
+    // stages one 32-row block of its quadrant at a time (32 rows x 32 NJ BF16 columns) at the start of one
+    // of the four slabs, which nobody reads any more, and writes it out as full row segments, 16 bytes per lane.  The
     // 16-byte slot index of a staged row is rotated by the row number, so that the 8-byte writes of
     // 32 rows and the 16-byte reads spread over the banks.  The region is private to the wave and LDS
     // executes a wave's accesses in order, so no further barrier is needed.
@@ -381,7 +384,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             if constexpr (V::kEpilogueFence) __builtin_amdgcn_sched_barrier(0);
-            const int row = i * 32 + fr_row;
+            const int row = fr_row;             // the 32 staged rows are reused by every block: LDS runs a wave's accesses in order
             uint8_t* srow = stage + row * kPitch;
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
@@ -402,14 +405,14 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
 #pragma unroll
             for (int k = 0; k < kPiecesPerLane; ++k) {
                 const int p = lane + k * kWave;
-                const int r = i * 32 + p / kSlots, sl = p % kSlots;
+                const int r = p / kSlots, sl = p % kSlots;
                 piece[k] = *reinterpret_cast<const v4u*>(stage + r * kPitch + (((sl + r) % kSlots) << 4));
             }
             if constexpr (V::kEpilogueFence) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int k = 0; k < kPiecesPerLane; ++k) {
                 const int p = lane + k * kWave;
-                const int r = i * 32 + p / kSlots, sl = p % kSlots;
+                const int r = i * 32 + p / kSlots, sl = p % kSlots;      // row inside the wave's quadrant
                 if constexpr (V::kNtStoreC) __builtin_nontemporal_store(piece[k], reinterpret_cast<v4u*>(cbase + (size_t)r * Cn + sl * 8));
                 else *reinterpret_cast<v4u*>(cbase + (size_t)r * Cn + sl * 8) = piece[k];
             }
@@ -573,7 +576,7 @@ static TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus) {
             const int64_t rounds = (tiles + slots - 1) / slots;
             // two resident 2 x 2 workgroups overlap each other's prologue and epilogue, which pays most
             // when the contraction is short
-            const double e = per_cu == 2 ? (T <= 4096 ? 0.92 : 0.82) : eff[ni][nj];
+            const double e = per_cu == 2 ? (T <= 3072 ? 0.90 : 0.80) : eff[ni][nj];
             const double cost = (double)rounds * per_cu * ni * nj / e;
             if (best.ni == 0 || cost < best_cost * 0.97) { best = {ni, nj}; best_cost = cost; }   // larger tile on near ties
         }
