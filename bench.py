@@ -35,7 +35,7 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=20)
     p.add_argument("--warmup", type=int, default=5)
-    p.add_argument("--config", type=int, default=2, help="BASELINE config index (2 = 3B-class block ... 5 = 32B-class)")
+    p.add_argument("--config", type=int, default=2, help="benchmark config index (2 = 3B-class block ... 5 = 32B-class)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--prequantized-w", action="store_true",
                    help="weights quantized once outside the timed region (reused across micro-steps)")
@@ -110,6 +110,22 @@ def run_quant_only(states):
         llmq.llmq_amax(s.W, 0, s.aw, s.sw, s.aws)
         llmq.llmq_quantize_fp8(s.W, s.sw, 0, s.view(2), s.view(3))
         llmq.llmq_amax(s.dY, 1, s.ad, s.sd, s.aws)
+        llmq.llmq_quantize_fp8(s.dY, s.sd, 1, s.view(4), s.view(5))
+
+
+def run_amax_only(states):
+    from paper_2512_15306_amd import llmq
+    for s in states:
+        llmq.llmq_amax(s.X, 0, s.ax, s.sx, s.aws)
+        llmq.llmq_amax(s.W, 0, s.aw, s.sw, s.aws)
+        llmq.llmq_amax(s.dY, 1, s.ad, s.sd, s.aws)
+
+
+def run_quantize_kernel_only(states):
+    from paper_2512_15306_amd import llmq
+    for s in states:
+        llmq.llmq_quantize_fp8(s.X, s.sx, 0, s.view(0), s.view(1))
+        llmq.llmq_quantize_fp8(s.W, s.sw, 0, s.view(2), s.view(3))
         llmq.llmq_quantize_fp8(s.dY, s.sd, 1, s.view(4), s.view(5))
 
 
@@ -306,6 +322,8 @@ def main():
     n_gemm = 3 * len(states)
     gemm_tflops = flops / (ms_gemm * 1e-3) / 1e12
     ms_quant = timed(lambda: run_quant_only(states), reps)
+    ms_amax = timed(lambda: run_amax_only(states), reps)
+    ms_qk = timed(lambda: run_quantize_kernel_only(states), reps)
     ms_fused = timed(lambda: run_step(states, args.prequantized_w, producer_absmax=True), reps)
     qbytes = 6.0 * synth.quantize_elements(cfg)         # absmax reads 2 B, quantize reads 2 B and writes 1 + 1 B
     out = {
@@ -323,6 +341,10 @@ def main():
         "gemm_only_pct_fp8_peak": round(100.0 * gemm_tflops / PEAK_FP8_TFLOPS, 2),
         "quantize_gbps": round(qbytes / (ms_quant * 1e-3) / 1e9, 1),
         "quantize_pct_hbm_peak": round(100.0 * qbytes / (ms_quant * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2),
+        "absmax_only_gbps": round(2.0 * synth.quantize_elements(cfg) / (ms_amax * 1e-3) / 1e9, 1),
+        "absmax_only_pct_hbm_peak": round(100.0 * 2.0 * synth.quantize_elements(cfg) / (ms_amax * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2),
+        "quantize_kernel_only_gbps": round(4.0 * synth.quantize_elements(cfg) / (ms_qk * 1e-3) / 1e9, 1),
+        "quantize_kernel_only_pct_hbm_peak": round(100.0 * 4.0 * synth.quantize_elements(cfg) / (ms_qk * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2),
         "step_tflops_with_producer_fused_absmax": round(flops / (ms_fused * 1e-3) / 1e12, 2),
         "measured_peaks": peaks,
         "gemm_only_pct_measured_random_bits_peak": round(100.0 * gemm_tflops / peaks["mfma_fp8_random_bits_tflops"], 2),
