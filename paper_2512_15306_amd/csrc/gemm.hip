@@ -73,9 +73,11 @@ struct GemmTuning {
     // slab: the workgroups that run side by side on an XCD (4 tile columns x 8 tile rows at a time)
     // share each slab and cover it together.
     static constexpr int kTouchShareA = 4, kTouchShareB = 8;
-    // Fragment reads ride along with the first 1 / kDsSpread of a half step's MFMAs, the direct-to-LDS
-    // loads with the first 1 / kVmSpread.
-    static constexpr int kDsSpread = 2, kVmSpread = 1;
+    // Fragment reads ride along with the first 1 / kDsSpread of a half step's MFMAs (4 x 4 tiles) or
+    // 1 / kDsSpreadSmall (smaller tiles: fewer MFMAs per read, and three reads per MFMA slot from four waves
+    // are more than the LDS delivers; measured +1-4 % on 4 x 3, while 4 x 4 loses 1-4 % on whole rounds with
+    // the reads spread over the whole half), the direct-to-LDS loads with the first 1 / kVmSpread.
+    static constexpr int kDsSpread = 2, kDsSpreadSmall = 1, kVmSpread = 1;
     static constexpr bool kNtStoreC = false;     // streaming hint on the output stores
     // Scheduling fences between the 32-row blocks of the epilogue: without them the compiler hoists every
     // de-scale multiply to the front and parks the products in accumulator registers.
@@ -207,6 +209,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
     };
     constexpr int kLoadsPerStep = 2 * (NI + NJ);
     constexpr int kMfmaPerHalf = NI * NJ * (FA == kFmtBf16 ? 2 : 1);
+    constexpr int kDsSpread = NI * NJ >= 16 ? V::kDsSpread : V::kDsSpreadSmall;
 
     // ---- LDS -> registers: lane reads 32 contiguous bytes (two swizzled 16-byte chunks) of its row
     const int fr_row = lane & 31;
@@ -263,7 +266,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         read_frags(curA, offA, 1, a1);
         read_frags(curB, offB, 1, b1);
         mma_block<FA, FB, NI, NJ>(acc, a0, b0);
-        interleave<kMfmaPerHalf, kLoadsPerStep, 0, V::kDsSpread, V::kVmSpread, 0>();
+        interleave<kMfmaPerHalf, kLoadsPerStep, 0, kDsSpread, V::kVmSpread, 0>();
         // the direct-to-LDS loads of the previous step must have landed; its two touch loads, issued
         // after them, may still be in flight
         if constexpr (kTouch) wait_vmcnt<2>(); else wait_vmcnt<0>();
@@ -273,7 +276,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
         read_frags(nxtA, offA, 0, a0);          // past the last slab this reads bytes that are never used
         read_frags(nxtB, offB, 0, b0);
         mma_block<FA, FB, NI, NJ>(acc, a1, b1);
-        interleave<kMfmaPerHalf, kLoadsPerStep, kLoadsPerStep, V::kDsSpread, V::kVmSpread, 1>();
+        interleave<kMfmaPerHalf, kLoadsPerStep, kLoadsPerStep, kDsSpread, V::kVmSpread, 1>();
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (kTouch) {
             const int kp = kt + 2 + touch_ahead;
