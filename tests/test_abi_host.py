@@ -78,6 +78,48 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.llmq_fp8_linear_wgrad(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, 1, ok_ptr, 0, ws, n(need), 2, None) == -7
 
 
+def test_argument_errors_of_the_producer_and_baseline_entry_points():
+    L = llmq.lib()
+    ok, odd = 0x10000, 0x10008
+    n = ctypes.c_size_t
+    f = ctypes.c_float
+    sw = llmq.llmq_swiglu_workspace_bytes(64, 256)
+    assert sw >= 4 and llmq.llmq_swiglu_workspace_bytes(0, 8) == 0 and llmq.llmq_swiglu_workspace_bytes(8, 1 << 24) == 0
+    assert L.llmq_swiglu_fwd(None, 64, 256, ok, 0, ok, ok, ok, n(sw), None) == -1
+    assert L.llmq_swiglu_fwd(ok, 64, 256, ok, 0, None, ok, ok, n(sw), None) == -1
+    assert L.llmq_swiglu_fwd(ok, 64, 0, ok, 0, ok, ok, ok, n(sw), None) == -2
+    assert L.llmq_swiglu_fwd(ok, 64, 256, ok, 2, ok, ok, ok, n(sw), None) == -4
+    assert L.llmq_swiglu_fwd(odd, 64, 256, ok, 0, ok, ok, ok, n(sw), None) == -3
+    assert L.llmq_swiglu_fwd(ok, 64, 256, ok, 0, ok, ok, odd, n(sw), None) == -3          # scratch: 16-byte aligned
+    assert L.llmq_swiglu_fwd(ok, 64, 256, ok, 0, ok, ok, ok, n(sw - 1), None) == -5
+    assert L.llmq_swiglu_fwd_fp8(ok, 64, 256, None, 0, ok, ok, None, None) == -1
+    assert L.llmq_swiglu_fwd_fp8(ok, 64, 256, ok, 0, None, ok, None, None) == -1
+    assert L.llmq_swiglu_fwd_fp8(ok, 64, 256, ok, 5, ok, ok, None, None) == -4
+    assert L.llmq_swiglu_fwd_fp8(ok, 64, 256, ok, 0, ok, odd, None, None) == -3
+    assert L.llmq_swiglu_bwd(ok, None, 64, 256, ok, 1, ok, ok, ok, n(sw), None) == -1
+    assert L.llmq_swiglu_bwd(ok, ok, -1, 256, ok, 1, ok, ok, ok, n(sw), None) == -2
+    assert L.llmq_swiglu_bwd(ok, ok, 64, 256, ok, 1, ok, ok, ok, n(0), None) == -5
+    rw = llmq.llmq_rmsnorm_workspace_bytes(64)
+    assert rw >= 4 and llmq.llmq_rmsnorm_workspace_bytes(0) == 0
+    assert L.llmq_rmsnorm_fwd(None, None, ok, 64, 256, f(1e-6), None, ok, ok, 0, ok, ok, ok, n(rw), None) == -1
+    assert L.llmq_rmsnorm_fwd(ok, ok, ok, 64, 256, f(1e-6), None, ok, ok, 0, ok, ok, ok, n(rw), None) == -1   # x without res_out
+    assert L.llmq_rmsnorm_fwd(ok, None, ok, 64, 256, f(-1.0), None, ok, ok, 0, ok, ok, ok, n(rw), None) == -2
+    assert L.llmq_rmsnorm_fwd(ok, None, ok, 64, 256, f(float("nan")), None, ok, ok, 0, ok, ok, ok, n(rw), None) == -2
+    assert L.llmq_rmsnorm_fwd(ok, None, ok, 64, 1 << 24, f(1e-6), None, ok, ok, 0, ok, ok, ok, n(rw), None) == -2
+    assert L.llmq_rmsnorm_fwd(ok, None, ok, 64, 256, f(1e-6), None, ok, ok, 3, ok, ok, ok, n(rw), None) == -4
+    assert L.llmq_rmsnorm_fwd(ok, None, ok, 64, 256, f(1e-6), None, odd, ok, 0, ok, ok, ok, n(rw), None) == -3
+    assert L.llmq_rmsnorm_fwd(ok, None, ok, 64, 256, f(1e-6), None, ok, ok, 0, ok, ok, ok, n(rw - 1), None) == -5
+    assert L.llmq_rmsnorm_apply_fp8(ok, ok, None, 64, 256, ok, 0, ok, ok, None, None) == -1
+    assert L.llmq_rmsnorm_apply_fp8(ok, ok, odd, 64, 256, ok, 0, ok, ok, None, None) == -3        # rstd: 16-byte aligned
+    assert L.llmq_rmsnorm_apply_fp8(ok, ok, ok, 64, 256, ok, 9, ok, ok, None, None) == -4
+    assert L.llmq_scale_from_amax(None, 0, ok, None) == -1
+    assert L.llmq_scale_from_amax(ok, 4, ok, None) == -4
+    assert L.llmq_scale_from_amax(ok, 0, ok + 2, None) == -3
+    assert L.llmq_bf16_gemm_tn(ok, None, 16, 16, 16, ok, 0, None) == -1
+    assert L.llmq_bf16_gemm_tn(ok, ok, 16, 16, 0, ok, 0, None) == -2
+    assert L.llmq_bf16_gemm_tn(ok, odd, 16, 16, 16, ok, 0, None) == -3
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     x = torch.zeros(8, dtype=torch.bfloat16)
