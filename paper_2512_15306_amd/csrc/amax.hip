@@ -148,10 +148,13 @@ int launch_amax(const void* x, size_t n, int fmt, float* d_amax, float* d_scale,
     const size_t n_vec = n / 8;
     const int n_tail = (int)(n % 8);
     const size_t chunk = (size_t)kAmaxThreads * kAmaxUnroll;
-    size_t blocks = n_vec / chunk;
+    const size_t chunks = n_vec / chunk;
     size_t max_blocks = (size_t)num_cus * 4;
     if (max_blocks > (size_t)kAmaxMaxPartials) max_blocks = kAmaxMaxPartials;
-    if (blocks > max_blocks) blocks = max_blocks;
+    // every workgroup takes the same number of chunks, give or take one: 1452 chunks are 726 workgroups of
+    // two, not 1024 of which 428 take a second one while the others wait
+    const size_t trips = (chunks + max_blocks - 1) / max_blocks;
+    size_t blocks = trips > 0 ? (chunks + trips - 1) / trips : 1;
     if (blocks < 1) blocks = 1;
     unsigned* partial = reinterpret_cast<unsigned*>(ws);
     hipLaunchKernelGGL(amax_partial_kernel, dim3((unsigned)blocks), dim3(kAmaxThreads), 0, stream,
