@@ -2,7 +2,8 @@
 
 A step is one pass of the whole path over one block's linears (QKV, attention-out, gate/up, down):
 per linear  absmax+scale of X and W, quantize+transpose both, forward GEMM (with fused output absmax),
-absmax+scale of dY, quantize+transpose, dgrad GEMM, wgrad GEMM.  Inputs are resident in HBM.
+absmax+scale of dY, quantize+transpose, dgrad GEMM, wgrad GEMM, through the three linear calls with
+just-in-time scaling.  Inputs are resident in HBM.
 
 Prints ONE JSON line: whole-step TFLOP/s (6*M*K*N summed over the linears / step time), the roofline
 of the dominant kernel (the FP8 MFMA GEMM, timed live with events on the launch stream) and the CPU
@@ -70,21 +71,20 @@ class LinearState:
 
 
 def run_step(states, prequantized_w, producer_absmax=False):
-    """producer_absmax: the absmax passes over X and dY are left out, as when the producing kernel (RMSNorm,
+    """Per linear: absmax + scale + quantize(+transpose) of X and W inside the forward call (just-in-time
+    scaling: first absmax stage, then the quantize kernel finishes the reduction), forward GEMM, the same for
+    dY inside the dgrad call, dgrad GEMM, wgrad GEMM on the copies already there.
+    producer_absmax: the absmax passes over X and dY are left out, as when the producing kernel (RMSNorm,
     SwiGLU, the previous GEMM's epilogue) has already delivered them; the scales of the last full step are
     used.  Reported as a side figure only."""
     from paper_2512_15306_amd import llmq
     for s in states:
         M, K, N = s.M, s.K, s.N
-        if not producer_absmax:
-            llmq.llmq_amax(s.X, llmq.E4M3, s.ax, s.sx, s.aws)
-        if not prequantized_w:
-            llmq.llmq_amax(s.W, llmq.E4M3, s.aw, s.sw, s.aws)
-        llmq.llmq_fp8_linear_fwd(s.X, s.W, M, N, K, s.sx, s.sw, s.Y, s.ay, s.ws,
-                                 llmq.REUSE_W if prequantized_w else 0)
-        if not producer_absmax:
-            llmq.llmq_amax(s.dY, llmq.E5M2, s.ad, s.sd, s.aws)
-        llmq.llmq_fp8_linear_dgrad(s.dY, None, M, N, K, s.sd, s.sw, llmq.E5M2, s.dX, s.adx, s.ws, llmq.REUSE_W)
+        fx = 0 if producer_absmax else llmq.JIT_X
+        fw = llmq.REUSE_W if prequantized_w else llmq.JIT_W
+        llmq.llmq_fp8_linear_fwd(s.X, s.W, M, N, K, s.sx, s.sw, s.Y, s.ay, s.ws, fx | fw)
+        fd = 0 if producer_absmax else llmq.JIT_DY
+        llmq.llmq_fp8_linear_dgrad(s.dY, None, M, N, K, s.sd, s.sw, llmq.E5M2, s.dX, s.adx, s.ws, llmq.REUSE_W | fd)
         llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, s.sd, s.sx, llmq.E5M2, s.dW, False, s.ws,
                                    llmq.REUSE_X | llmq.REUSE_DY)
 

@@ -120,7 +120,8 @@ int llmq_bf16_gemm_tn(const void* A_bf16, const void* B_bf16, int64_t R, int64_t
  * Workspace of the three linear-layer calls below, for one (M, N, K).  It holds the FP8 copies
  *   Xq [M,K], Xq_t [K,M], Wq [N,K], Wq_t [K,N], dYq [M,N], dYq_t [N,M]
  * in this order, each starting at a multiple of 256 bytes; llmq_fp8_linear_workspace_offsets() returns
- * the six byte offsets.  The caller owns the workspace and may read the copies between calls.
+ * the six byte offsets.  Behind them sit 12 KB of scratch for the LLMQ_JIT_* flags.  The caller owns the
+ * workspace and may read the copies between calls.
  */
 size_t llmq_fp8_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t offsets[6]);
@@ -132,6 +133,14 @@ int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t of
 #define LLMQ_REUSE_X  1
 #define LLMQ_REUSE_W  2
 #define LLMQ_REUSE_DY 4
+/* Just-in-time scaling inside the call (Section 3 "Overview": the scale is found right before the conversion,
+ * at the price of one extra kernel for the global reduction): the named operand's d_scale_* is then an OUTPUT.
+ * The call runs the first stage of the absmax reduction over the operand and the quantize kernel finishes it,
+ * so the scale, the FP8 bytes and everything downstream are bit-identical to llmq_amax followed by the call
+ * with the scale given, with one launch less.  Not together with the operand's REUSE flag. */
+#define LLMQ_JIT_X   8
+#define LLMQ_JIT_W  16
+#define LLMQ_JIT_DY 32
 
 /*
  * Forward: Y[M,N] = X[M,K] W[N,K]^T in FP8 (E4M3 x E4M3), BF16 out.
@@ -139,7 +148,7 @@ int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t of
  * runs the contraction on Xq and Wq.  d_amax_y may be NULL.
  */
 int llmq_fp8_linear_fwd(const void* X, const void* W, int64_t M, int64_t N, int64_t K,
-                        const float* d_scale_x, const float* d_scale_w,
+                        float* d_scale_x, float* d_scale_w,
                         void* Y, float* d_amax_y, void* ws, size_t ws_bytes, int flags, void* stream);
 
 /*
@@ -148,7 +157,7 @@ int llmq_fp8_linear_fwd(const void* X, const void* W, int64_t M, int64_t N, int6
  * Wq_t.  W and dY pointers are not read for operands whose REUSE flag is set (and may then be NULL).
  */
 int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, int64_t K,
-                          const float* d_scale_dy, const float* d_scale_w, int fmt_dy,
+                          float* d_scale_dy, float* d_scale_w, int fmt_dy,
                           void* dX, float* d_amax_dx, void* ws, size_t ws_bytes, int flags, void* stream);
 
 /*
@@ -156,7 +165,7 @@ int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, i
  * dYq_t and Xq_t.
  */
 int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, int64_t K,
-                          const float* d_scale_dy, const float* d_scale_x, int fmt_dy,
+                          float* d_scale_dy, float* d_scale_x, int fmt_dy,
                           void* dW, int accumulate, void* ws, size_t ws_bytes, int flags, void* stream);
 
 /*

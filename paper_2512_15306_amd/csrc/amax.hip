@@ -145,6 +145,12 @@ int launch_amax_final(const unsigned* partial, int n_partial, int fmt, float* d_
 
 int launch_amax(const void* x, size_t n, int fmt, float* d_amax, float* d_scale, void* ws,
                 hipStream_t stream, int num_cus) {
+    int blocks = 0;
+    if (launch_amax_partial(x, n, reinterpret_cast<unsigned*>(ws), &blocks, stream, num_cus) != 0) return -6;
+    return launch_amax_final(reinterpret_cast<unsigned*>(ws), blocks, fmt, d_amax, d_scale, stream);
+}
+
+int launch_amax_partial(const void* x, size_t n, unsigned* partial, int* n_partial, hipStream_t stream, int num_cus) {
     const size_t n_vec = n / 8;
     const int n_tail = (int)(n % 8);
     const size_t chunk = (size_t)kAmaxThreads * kAmaxUnroll;
@@ -156,11 +162,11 @@ int launch_amax(const void* x, size_t n, int fmt, float* d_amax, float* d_scale,
     const size_t trips = (chunks + max_blocks - 1) / max_blocks;
     size_t blocks = trips > 0 ? (chunks + trips - 1) / trips : 1;
     if (blocks < 1) blocks = 1;
-    unsigned* partial = reinterpret_cast<unsigned*>(ws);
     hipLaunchKernelGGL(amax_partial_kernel, dim3((unsigned)blocks), dim3(kAmaxThreads), 0, stream,
                        reinterpret_cast<const v4u*>(x), n_vec,
                        reinterpret_cast<const uint16_t*>(x) + n_vec * 8, n_tail, partial);
-    return launch_amax_final(partial, (int)blocks, fmt, d_amax, d_scale, stream);
+    *n_partial = (int)blocks;
+    return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
 }  // namespace llmq

@@ -28,7 +28,7 @@ int num_cus() {
 }
 
 struct WsLayout {
-    size_t xq, xqt, wq, wqt, dyq, dyqt, total;
+    size_t xq, xqt, wq, wqt, dyq, dyqt, part, total;      // part: three absmax scratch areas (X, W, dY)
 };
 
 WsLayout ws_layout(int64_t M, int64_t N, int64_t K) {
@@ -40,6 +40,7 @@ WsLayout ws_layout(int64_t M, int64_t N, int64_t K) {
     l.wqt = off;  off += round256((size_t)N * K);
     l.dyq = off;  off += round256((size_t)M * N);
     l.dyqt = off; off += round256((size_t)M * N);
+    l.part = off; off += 3 * round256((size_t)llmq::kAmaxMaxPartials * sizeof(unsigned));
     l.total = off;
     return l;
 }
@@ -47,7 +48,11 @@ WsLayout ws_layout(int64_t M, int64_t N, int64_t K) {
 int check_linear(int64_t M, int64_t N, int64_t K, const void* ws, size_t ws_bytes, int flags) {
     if (!dim_ok(M) || !dim_ok(N) || !dim_ok(K)) return LLMQ_ERR_SHAPE;
     if (M * K >= kMaxElems || N * K >= kMaxElems || M * N >= kMaxElems) return LLMQ_ERR_SHAPE;
-    if (flags & ~(LLMQ_REUSE_X | LLMQ_REUSE_W | LLMQ_REUSE_DY)) return LLMQ_ERR_FLAGS;
+    if (flags & ~(LLMQ_REUSE_X | LLMQ_REUSE_W | LLMQ_REUSE_DY | LLMQ_JIT_X | LLMQ_JIT_W | LLMQ_JIT_DY)) return LLMQ_ERR_FLAGS;
+    // an operand is either reused or scaled just in time, not both
+    if (((flags & LLMQ_REUSE_X) && (flags & LLMQ_JIT_X)) || ((flags & LLMQ_REUSE_W) && (flags & LLMQ_JIT_W)) ||
+        ((flags & LLMQ_REUSE_DY) && (flags & LLMQ_JIT_DY)))
+        return LLMQ_ERR_FLAGS;
     if (!ws) return LLMQ_ERR_NULL;
     if (!aligned(ws, 256)) return LLMQ_ERR_ALIGN;
     if (ws_bytes < ws_layout(M, N, K).total) return LLMQ_ERR_WORKSPACE;
@@ -57,6 +62,19 @@ int check_linear(int64_t M, int64_t N, int64_t K, const void* ws, size_t ws_byte
 int check_swiglu_shape(int64_t M, int64_t I) {
     if (!dim_ok(M) || !dim_ok(I) || I >= ((int64_t)1 << 24) || M * I >= kMaxElems / 2) return LLMQ_ERR_SHAPE;
     return LLMQ_OK;
+}
+
+// Quantize one operand of a linear call into its two workspace sections.  jit: the scale is not given but
+// found here: the first absmax stage runs over the tensor, the quantize kernel finishes the reduction and
+// stores the scale in d_scale (saving the launch of the second stage).
+int quantize_operand(const void* t, int64_t rows, int64_t cols, float* d_scale, int fmt, uint8_t* q, uint8_t* q_t,
+                     bool jit, unsigned* partial, unsigned* zero, hipStream_t s) {
+    if (!jit) return llmq::launch_quantize(t, rows, cols, d_scale, fmt, q, q_t, zero, s);
+    int n_partial = 0;
+    int st = llmq::launch_amax_partial(t, (size_t)rows * (size_t)cols, partial, &n_partial, s, num_cus());
+    if (st) return st;
+    const llmq::ScaleSource src{nullptr, partial, n_partial, fmt == LLMQ_E4M3 ? 448.0f : 57344.0f, d_scale};
+    return llmq::launch_quantize_from(t, rows, cols, src, fmt, q, q_t, zero, s);
 }
 
 }  // namespace
@@ -138,11 +156,11 @@ int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t of
 }
 
 int llmq_fp8_linear_fwd(const void* X, const void* W, int64_t M, int64_t N, int64_t K,
-                        const float* d_scale_x, const float* d_scale_w, void* Y, float* d_amax_y,
+                        float* d_scale_x, float* d_scale_w, void* Y, float* d_amax_y,
                         void* ws, size_t ws_bytes, int flags, void* stream) {
     int st = check_linear(M, N, K, ws, ws_bytes, flags);
     if (st != LLMQ_OK) return st;
-    if (flags & LLMQ_REUSE_DY) return LLMQ_ERR_FLAGS;
+    if (flags & (LLMQ_REUSE_DY | LLMQ_JIT_DY)) return LLMQ_ERR_FLAGS;
     const bool qx = !(flags & LLMQ_REUSE_X), qw = !(flags & LLMQ_REUSE_W);
     if ((qx && !X) || (qw && !W) || !d_scale_x || !d_scale_w || !Y) return LLMQ_ERR_NULL;
     if ((qx && !aligned(X, 16)) || (qw && !aligned(W, 16)) || !aligned(Y, 16) || !aligned(d_scale_x, 4) ||
@@ -154,18 +172,20 @@ int llmq_fp8_linear_fwd(const void* X, const void* W, int64_t M, int64_t N, int6
     // the first quantize kernel of the call also clears the absmax accumulator of the GEMM
     unsigned* zero = reinterpret_cast<unsigned*>(d_amax_y);
     const bool zeroed = zero && (qx || qw);
-    if (qx && (st = llmq::launch_quantize(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, base + l.xqt, zero, s))) return st;
-    if (qw && (st = llmq::launch_quantize(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, base + l.wqt, qx ? nullptr : zero, s))) return st;
+    unsigned* part = reinterpret_cast<unsigned*>(base + l.part);
+    constexpr size_t kPartWords = 256 * ((llmq::kAmaxMaxPartials * sizeof(unsigned) + 255) / 256) / sizeof(unsigned);
+    if (qx && (st = quantize_operand(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, base + l.xqt, (flags & LLMQ_JIT_X) != 0, part, zero, s))) return st;
+    if (qw && (st = quantize_operand(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, base + l.wqt, (flags & LLMQ_JIT_W) != 0, part + kPartWords, qx ? nullptr : zero, s))) return st;
     return llmq::launch_gemm_tn(base + l.xq, LLMQ_E4M3, base + l.wq, LLMQ_E4M3, M, N, K, d_scale_x, d_scale_w,
                                 Y, 0, d_amax_y, zeroed, s, num_cus());
 }
 
 int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, int64_t K,
-                          const float* d_scale_dy, const float* d_scale_w, int fmt_dy, void* dX,
+                          float* d_scale_dy, float* d_scale_w, int fmt_dy, void* dX,
                           float* d_amax_dx, void* ws, size_t ws_bytes, int flags, void* stream) {
     int st = check_linear(M, N, K, ws, ws_bytes, flags);
     if (st != LLMQ_OK) return st;
-    if (flags & LLMQ_REUSE_X) return LLMQ_ERR_FLAGS;
+    if (flags & (LLMQ_REUSE_X | LLMQ_JIT_X)) return LLMQ_ERR_FLAGS;
     if (!fmt_ok(fmt_dy)) return LLMQ_ERR_FORMAT;
     const bool qd = !(flags & LLMQ_REUSE_DY), qw = !(flags & LLMQ_REUSE_W);
     if ((qd && !dY) || (qw && !W) || !d_scale_dy || !d_scale_w || !dX) return LLMQ_ERR_NULL;
@@ -177,19 +197,21 @@ int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, i
     hipStream_t s = static_cast<hipStream_t>(stream);
     unsigned* zero = reinterpret_cast<unsigned*>(d_amax_dx);
     const bool zeroed = zero && (qd || qw);
-    if (qd && (st = llmq::launch_quantize(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, base + l.dyqt, zero, s))) return st;
-    if (qw && (st = llmq::launch_quantize(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, base + l.wqt, qd ? nullptr : zero, s))) return st;
+    unsigned* part = reinterpret_cast<unsigned*>(base + l.part);
+    constexpr size_t kPartWords = 256 * ((llmq::kAmaxMaxPartials * sizeof(unsigned) + 255) / 256) / sizeof(unsigned);
+    if (qd && (st = quantize_operand(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, base + l.dyqt, (flags & LLMQ_JIT_DY) != 0, part + 2 * kPartWords, zero, s))) return st;
+    if (qw && (st = quantize_operand(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, base + l.wqt, (flags & LLMQ_JIT_W) != 0, part + kPartWords, qd ? nullptr : zero, s))) return st;
     // dX[m,k] = sum_n dYq[m,n] * Wq_t[k,n]
     return llmq::launch_gemm_tn(base + l.dyq, fmt_dy, base + l.wqt, LLMQ_E4M3, M, K, N, d_scale_dy, d_scale_w,
                                 dX, 0, d_amax_dx, zeroed, s, num_cus());
 }
 
 int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, int64_t K,
-                          const float* d_scale_dy, const float* d_scale_x, int fmt_dy, void* dW,
+                          float* d_scale_dy, float* d_scale_x, int fmt_dy, void* dW,
                           int accumulate, void* ws, size_t ws_bytes, int flags, void* stream) {
     int st = check_linear(M, N, K, ws, ws_bytes, flags);
     if (st != LLMQ_OK) return st;
-    if (flags & LLMQ_REUSE_W) return LLMQ_ERR_FLAGS;
+    if (flags & (LLMQ_REUSE_W | LLMQ_JIT_W)) return LLMQ_ERR_FLAGS;
     if (!fmt_ok(fmt_dy)) return LLMQ_ERR_FORMAT;
     const bool qd = !(flags & LLMQ_REUSE_DY), qx = !(flags & LLMQ_REUSE_X);
     if ((qd && !dY) || (qx && !X) || !d_scale_dy || !d_scale_x || !dW) return LLMQ_ERR_NULL;
@@ -199,8 +221,10 @@ int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, i
     const WsLayout l = ws_layout(M, N, K);
     uint8_t* base = static_cast<uint8_t*>(ws);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (qd && (st = llmq::launch_quantize(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, base + l.dyqt, nullptr, s))) return st;
-    if (qx && (st = llmq::launch_quantize(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, base + l.xqt, nullptr, s))) return st;
+    unsigned* part = reinterpret_cast<unsigned*>(base + l.part);
+    constexpr size_t kPartWords = 256 * ((llmq::kAmaxMaxPartials * sizeof(unsigned) + 255) / 256) / sizeof(unsigned);
+    if (qd && (st = quantize_operand(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, base + l.dyqt, (flags & LLMQ_JIT_DY) != 0, part + 2 * kPartWords, nullptr, s))) return st;
+    if (qx && (st = quantize_operand(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, base + l.xqt, (flags & LLMQ_JIT_X) != 0, part, nullptr, s))) return st;
     // dW[n,k] = sum_m dYq_t[n,m] * Xq_t[k,m]
     return llmq::launch_gemm_tn(base + l.dyqt, fmt_dy, base + l.xqt, LLMQ_E4M3, N, K, M, d_scale_dy, d_scale_x,
                                 dW, accumulate, nullptr, false, s, num_cus());

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "llmq_kernels.h"
+
 namespace llmq {
 
 typedef int v2i __attribute__((ext_vector_type(2)));
@@ -62,6 +64,28 @@ __device__ inline unsigned block_max_u32(unsigned m, unsigned* s_part) {
 #pragma unroll
     for (int w = 0; w < THREADS / kWave; ++w) m = m > s_part[w] ? m : s_part[w];
     return m;
+}
+
+// scale = min(fmax / amax, FLT_MAX) from a BF16 magnitude pattern, as the absmax second stage computes it
+__device__ inline float scale_from_mag(unsigned mag16, float fmax) {
+    const float a = __uint_as_float(amax_bits_from_bf16_mag(mag16));
+    float s = fmax / a;                                   // one correctly rounded division
+    if (__builtin_isinf(s)) s = 3.402823466e+38f;
+    return s;
+}
+
+// The scale of a 256-lane workgroup's launch; all lanes of the workgroup must call it.
+__device__ inline float resolve_scale(const ScaleSource& src, bool first_block, unsigned* s_part) {
+    if (src.partial == nullptr) return *src.d_scale;
+    unsigned m = 0;
+    for (int i = threadIdx.x; i < src.n_partial; i += 256) {
+        const unsigned v = src.partial[i];
+        m = m > v ? m : v;
+    }
+    m = block_max_u32<256>(m, s_part);
+    const float s = scale_from_mag(m, src.fmax);
+    if (first_block && threadIdx.x == 0) *src.d_scale_out = s;
+    return s;
 }
 
 // ---- FP8 cast helpers (used by the quantize kernel and by the producers that emit FP8 directly) ----

@@ -22,6 +22,24 @@ int launch_scale_from_amax(const float* d_amax, int fmt, float* d_scale, hipStre
 // that follows in the same call, which saves a launch).
 int launch_quantize(const void* x, int64_t rows, int64_t cols, const float* d_scale, int fmt,
                     uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream);
+// Where a quantizing kernel gets its scale from: a scale on the device, or the per-workgroup results of
+// the first stage of an absmax reduction over the same tensor, in which case every workgroup finishes the
+// reduction itself (at most 1024 words) and the first one also stores the scale: the second-stage launch of
+// the absmax is saved.
+struct ScaleSource {
+    const float* d_scale;        // used when partial == nullptr
+    const unsigned* partial;     // BF16 magnitude patterns, one per workgroup of the first stage
+    int n_partial;
+    float fmax;                  // largest finite value of the target format
+    float* d_scale_out;          // written (by one workgroup) when partial != nullptr
+};
+
+// The same with the scale taken from a ScaleSource (a given scale, or the first-stage results of an absmax).
+int launch_quantize_from(const void* x, int64_t rows, int64_t cols, const ScaleSource& src, int fmt,
+                         uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream);
+// First stage of the absmax only: one BF16 magnitude pattern per workgroup into partial; returns the number
+// of workgroups (<= kAmaxMaxPartials) through n_partial.
+int launch_amax_partial(const void* x, size_t n, unsigned* partial, int* n_partial, hipStream_t stream, int num_cus);
 int launch_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64_t R, int64_t C,
                    int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16,
                    int accumulate, float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus);

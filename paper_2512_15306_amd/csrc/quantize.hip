@@ -32,9 +32,11 @@ struct QuantTuning {
 
 template <int FMT, bool TRANSPOSE, class V = QuantTuning>
 __global__ __launch_bounds__(kQThreads) void quantize_patch_kernel(
-    const uint16_t* __restrict__ x, int64_t rows, int64_t cols, const float* __restrict__ d_scale,
+    const uint16_t* __restrict__ x, int64_t rows, int64_t cols, const ScaleSource scale_src,
     uint8_t* __restrict__ q, uint8_t* __restrict__ qt, unsigned* __restrict__ zero_word) {
+    __shared__ unsigned s_part[kQThreads / kWave];
     if (zero_word && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *zero_word = 0u;
+    const float s = resolve_scale(scale_src, blockIdx.x == 0 && blockIdx.y == 0, s_part);   // before any lane leaves
     constexpr int PC = V::kPatchCols, LR = V::kLanesR, LC = kWave / LR;
     constexpr int NV = PC / 8;                              // 16-byte loads per row of the patch
     constexpr int kWaveRows = kPatchRows * LR, kWaveCols = PC * LC;
@@ -46,7 +48,6 @@ __global__ __launch_bounds__(kQThreads) void quantize_patch_kernel(
     const int64_t r0 = (int64_t)brow * kWaveRows + (lane % LR) * kPatchRows;
     const int64_t c0 = (int64_t)bcol * kBlockCols + wave * kWaveCols + (lane / LR) * PC;
     if (r0 >= rows || c0 >= cols) return;       // rows % 16 == 0 and cols % PC == 0: a patch is all in or all out
-    const float s = *d_scale;
     v4u in[kPatchRows][NV];
     const uint16_t* src = x + r0 * cols + c0;
 #pragma unroll
@@ -101,11 +102,12 @@ __global__ __launch_bounds__(kQThreads) void quantize_patch_kernel(
 // Any shape: one element per lane.  Lanes run along columns for the read and the row-major write.
 template <int FMT>
 __global__ __launch_bounds__(256) void quantize_generic_kernel(
-    const uint16_t* __restrict__ x, int64_t rows, int64_t cols, const float* __restrict__ d_scale,
+    const uint16_t* __restrict__ x, int64_t rows, int64_t cols, const ScaleSource scale_src,
     uint8_t* __restrict__ q, uint8_t* __restrict__ qt, unsigned* __restrict__ zero_word) {
+    __shared__ unsigned s_part[256 / kWave];
     if (zero_word && blockIdx.x == 0 && threadIdx.x == 0) *zero_word = 0u;
     const int64_t n = rows * cols;
-    const float s = *d_scale;
+    const float s = resolve_scale(scale_src, blockIdx.x == 0, s_part);
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
         float p = __uint_as_float((unsigned)x[i] << 16) * s;
         unsigned code = cvt_pair<FMT>(p, p, 0u, false) & 0xFFu;
@@ -118,7 +120,7 @@ __global__ __launch_bounds__(256) void quantize_generic_kernel(
 }
 
 template <class V>
-static void launch_patch(const uint16_t* xb, int64_t rows, int64_t cols, const float* d_scale, int fmt,
+static void launch_patch(const uint16_t* xb, int64_t rows, int64_t cols, const ScaleSource& d_scale, int fmt,
                          uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream) {
     constexpr int kWaveRows = kPatchRows * V::kLanesR;
     constexpr int kBlockCols = V::kPatchCols * (kWave / V::kLanesR) * (kQThreads / kWave);
@@ -136,6 +138,12 @@ static void launch_patch(const uint16_t* xb, int64_t rows, int64_t cols, const f
 
 int launch_quantize(const void* x, int64_t rows, int64_t cols, const float* d_scale, int fmt,
                     uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream) {
+    const ScaleSource src{d_scale, nullptr, 0, fp8_max(fmt), nullptr};
+    return launch_quantize_from(x, rows, cols, src, fmt, q, q_t, zero_word, stream);
+}
+
+int launch_quantize_from(const void* x, int64_t rows, int64_t cols, const ScaleSource& d_scale, int fmt,
+                         uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream) {
     const uint16_t* xb = reinterpret_cast<const uint16_t*>(x);
     if (rows % kPatchRows == 0 && cols % QuantTuning::kPatchCols == 0) {
         launch_patch<QuantTuning>(xb, rows, cols, d_scale, fmt, q, q_t, zero_word, stream);

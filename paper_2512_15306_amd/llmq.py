@@ -16,6 +16,9 @@ E5M2 = 1
 REUSE_X = 1
 REUSE_W = 2
 REUSE_DY = 4
+JIT_X = 8
+JIT_W = 16
+JIT_DY = 32
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libllmq.so")

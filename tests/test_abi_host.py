@@ -68,7 +68,10 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, None, n(need), 0, None) == -1
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need - 1), 0, None) == -5
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws + 16, n(need), 0, None) == -3
-    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 8, None) == -7
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 64, None) == -7
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 8 | 1, None) == -7      # JIT and REUSE of one operand
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 32, None) == -7         # dY is no operand of the forward call
+    assert L.llmq_fp8_linear_wgrad(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, 1, ok_ptr, 0, ws, n(need), 16, None) == -7
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 4, None) == -7
     assert L.llmq_fp8_linear_fwd(None, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 0, None) == -1
     assert L.llmq_fp8_linear_dgrad(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, 5, ok_ptr, None, ws, n(need), 0, None) == -4

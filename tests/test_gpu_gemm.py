@@ -290,6 +290,77 @@ def test_all_tile_shapes_give_the_same_bytes_run_after_run():
         assert np.all(np.abs(got - y) <= GEMM_TOL * S)
 
 
+@pytest.mark.parametrize("shape", [(256, 512, 1024), (272, 400, 528), (33, 17, 5), (4096, 1024, 768)])
+@pytest.mark.parametrize("fmt_dy", [1, 0])
+def test_just_in_time_scaling_inside_the_linear_calls(shape, fmt_dy):
+    """LLMQ_JIT_*: the call finds the scale itself (first absmax stage + the quantize kernel finishing the
+    reduction).  Scales, every workspace copy and every output must be the bytes of the explicit sequence
+    llmq_amax -> call with the scale given; the scales are also checked against the oracle."""
+    M, K, N = shape
+    print("jit linear M=%d K=%d N=%d fmt_dy=%d" % (M, K, N, fmt_dy), flush=True)
+    g = torch.Generator().manual_seed(M + 3 * K + 7 * N)
+    x = torch.randn((M, K), generator=g).to(torch.bfloat16)
+    w = (torch.randn((N, K), generator=g) * 0.02).to(torch.bfloat16)
+    dy = (torch.randn((M, N), generator=g) * 1e-3).to(torch.bfloat16)
+    xd, wd, dyd = x.to(DEV), w.to(DEV), dy.to(DEV)
+    nbytes = llmq.llmq_fp8_linear_workspace_bytes(M, N, K)
+    offs = llmq.llmq_fp8_linear_workspace_offsets(M, N, K)
+    sizes = [M * K, M * K, N * K, N * K, M * N, M * N]
+
+    def run(jit):
+        ws = torch.full((nbytes,), 0x55, dtype=torch.uint8, device=DEV)          # scratch part starts as garbage
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+        dX = torch.empty((M, K), dtype=torch.bfloat16, device=DEV)
+        dW = torch.empty((N, K), dtype=torch.bfloat16, device=DEV)
+        ay = torch.zeros(1, device=DEV)
+        adx = torch.zeros(1, device=DEV)
+        if jit:
+            sx, sw, sd = (torch.full((1,), -1.0, device=DEV) for _ in range(3))
+            llmq.llmq_fp8_linear_fwd(xd, wd, M, N, K, sx, sw, Y, ay, ws, llmq.JIT_X | llmq.JIT_W)
+            llmq.llmq_fp8_linear_dgrad(dyd, None, M, N, K, sd, sw, fmt_dy, dX, adx, ws, llmq.JIT_DY | llmq.REUSE_W)
+            llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, sd, sx, fmt_dy, dW, False, ws, llmq.REUSE_X | llmq.REUSE_DY)
+        else:
+            _, sx = gpu_amax(xd, 0)
+            _, sw = gpu_amax(wd, 0)
+            _, sd = gpu_amax(dyd, fmt_dy)
+            llmq.llmq_fp8_linear_fwd(xd, wd, M, N, K, sx, sw, Y, ay, ws)
+            llmq.llmq_fp8_linear_dgrad(dyd, None, M, N, K, sd, sw, fmt_dy, dX, adx, ws, llmq.REUSE_W)
+            llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, sd, sx, fmt_dy, dW, False, ws, llmq.REUSE_X | llmq.REUSE_DY)
+        copies = [ws[o:o + n].clone() for o, n in zip(offs, sizes)]
+        return (sx, sw, sd), copies, (Y, dX, dW), (ay, adx)
+
+    s0, c0, o0, a0 = run(False)
+    s1, c1, o1, a1 = run(True)
+    assert [f32_bits(t) for t in s0] == [f32_bits(t) for t in s1]
+    want = [oracle.scale(oracle.amax_bf16(synth.bf16_bits(t)), f) for t, f in ((x, 0), (w, 0), (dy, fmt_dy))]
+    assert [f32_bits(t) for t in s1] == [np_f32_bits(v) for v in want]
+    for a, b in zip(c0, c1):
+        assert torch.equal(a, b)
+    for a, b in zip(o0, o1):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    assert [f32_bits(t) for t in a0] == [f32_bits(t) for t in a1]
+    # wgrad may also scale its own operands just in time (no forward or dgrad before it)
+    ws = torch.full((nbytes,), 0xAA, dtype=torch.uint8, device=DEV)
+    sd2, sx2 = torch.full((1,), -1.0, device=DEV), torch.full((1,), -1.0, device=DEV)
+    dW2 = torch.empty((N, K), dtype=torch.bfloat16, device=DEV)
+    llmq.llmq_fp8_linear_wgrad(dyd, xd, M, N, K, sd2, sx2, fmt_dy, dW2, False, ws, llmq.JIT_DY | llmq.JIT_X)
+    assert f32_bits(sd2) == f32_bits(s0[2]) and f32_bits(sx2) == f32_bits(s0[0])
+    assert torch.equal(dW2.view(torch.int16), o0[2].view(torch.int16))
+    # an all-zero operand: scale FLT_MAX, result zero
+    z = torch.zeros_like(xd)
+    sz, sw3 = torch.full((1,), -1.0, device=DEV), torch.full((1,), -1.0, device=DEV)
+    Yz = torch.full((M, N), 3.0, dtype=torch.bfloat16, device=DEV)
+    llmq.llmq_fp8_linear_fwd(z, wd, M, N, K, sz, sw3, Yz, None, ws, llmq.JIT_X | llmq.JIT_W)
+    assert sz.item() == float(np.finfo(np.float32).max) and (Yz == 0).all()
+    # flag combinations that make no sense are refused
+    with pytest.raises(llmq.LlmqError) as e:
+        llmq.llmq_fp8_linear_fwd(xd, wd, M, N, K, sz, sw3, Yz, None, ws, llmq.JIT_X | llmq.REUSE_X)
+    assert e.value.status == -7
+    with pytest.raises(llmq.LlmqError) as e:
+        llmq.llmq_fp8_linear_fwd(xd, wd, M, N, K, sz, sw3, Yz, None, ws, llmq.JIT_DY)
+    assert e.value.status == -7
+
+
 def _block_step(cfg, states):
     for s in states:
         M, K, N = s["M"], s["K"], s["N"]
