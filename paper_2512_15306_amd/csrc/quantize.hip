@@ -9,6 +9,8 @@
 // of each row, transposes the 16x8 byte patch in registers with byte permutes and writes eight
 // 16-byte vectors of the transposed tensor (eight lanes stacked in rows cover a full 128-byte line
 // there).  No LDS, no barrier.
+#include <stdlib.h>
+
 #include "llmq_device.h"
 #include "llmq_kernels.h"
 
@@ -27,24 +29,35 @@ struct QuantTuning {
     static constexpr bool kLoadsFirst = true;    // issue every load of the patch before the first conversion
     static constexpr bool kNtLoad = true;        // streaming hint on the loads
     static constexpr bool kNtStore = false;      // streaming hint on the stores
-    static constexpr bool kBlocksDownRows = true;    // consecutive workgroups walk down rows instead of along columns
+    // Block columns per band of the workgroup walk (see the kernel).  Measured on the benchmark tensors:
+    // walking along the columns (one band) beats walking down the rows (band = 1) by 1-4 %, bands of 2-16 lie
+    // in between.  LLMQ_QUANT_BAND overrides it for tuning.
+    static constexpr int kBandBlocks = 1 << 20;
 };
 
 template <int FMT, bool TRANSPOSE, class V = QuantTuning>
 __global__ __launch_bounds__(kQThreads) void quantize_patch_kernel(
     const uint16_t* __restrict__ x, int64_t rows, int64_t cols, const ScaleSource scale_src,
-    uint8_t* __restrict__ q, uint8_t* __restrict__ qt, unsigned* __restrict__ zero_word) {
+    uint8_t* __restrict__ q, uint8_t* __restrict__ qt, unsigned* __restrict__ zero_word,
+    unsigned grid_rows, unsigned grid_cols, unsigned band) {
     __shared__ unsigned s_part[kQThreads / kWave];
-    if (zero_word && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *zero_word = 0u;
-    const float s = resolve_scale(scale_src, blockIdx.x == 0 && blockIdx.y == 0, s_part);   // before any lane leaves
+    if (zero_word && blockIdx.x == 0 && threadIdx.x == 0) *zero_word = 0u;
+    const float s = resolve_scale(scale_src, blockIdx.x == 0, s_part);   // before any lane leaves
+    // Workgroup id -> block of the tensor: bands of `band` block columns, walked down the rows, `band`
+    // neighbouring blocks of a row one after the other.  Workgroups in flight together then read runs of
+    // band * 512 bytes of a row and write runs of the transposed tensor's rows that keep growing as the walk
+    // moves down (band = 1: plain walk down the rows; band >= grid_cols: along the columns).
+    const unsigned band_first = (blockIdx.x / (band * grid_rows)) * band;
+    const unsigned band_width = grid_cols - band_first < band ? grid_cols - band_first : band;
+    const unsigned in_band = blockIdx.x - band_first * grid_rows;
+    const unsigned brow = in_band / band_width;
+    const unsigned bcol = band_first + in_band % band_width;
     constexpr int PC = V::kPatchCols, LR = V::kLanesR, LC = kWave / LR;
     constexpr int NV = PC / 8;                              // 16-byte loads per row of the patch
     constexpr int kWaveRows = kPatchRows * LR, kWaveCols = PC * LC;
     constexpr int kBlockCols = kWaveCols * (kQThreads / kWave);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const unsigned brow = V::kBlocksDownRows ? blockIdx.x : blockIdx.y;
-    const unsigned bcol = V::kBlocksDownRows ? blockIdx.y : blockIdx.x;
     const int64_t r0 = (int64_t)brow * kWaveRows + (lane % LR) * kPatchRows;
     const int64_t c0 = (int64_t)bcol * kBlockCols + wave * kWaveCols + (lane / LR) * PC;
     if (r0 >= rows || c0 >= cols) return;       // rows % 16 == 0 and cols % PC == 0: a patch is all in or all out
@@ -125,14 +138,16 @@ static void launch_patch(const uint16_t* xb, int64_t rows, int64_t cols, const S
     constexpr int kWaveRows = kPatchRows * V::kLanesR;
     constexpr int kBlockCols = V::kPatchCols * (kWave / V::kLanesR) * (kQThreads / kWave);
     const unsigned gc = (unsigned)((cols + kBlockCols - 1) / kBlockCols), gr = (unsigned)((rows + kWaveRows - 1) / kWaveRows);
-    dim3 grid(V::kBlocksDownRows ? gr : gc, V::kBlocksDownRows ? gc : gr);
+    dim3 grid(gr * gc);
     dim3 block(kQThreads);
+    unsigned band = V::kBandBlocks;
+    if (const char* e = getenv("LLMQ_QUANT_BAND")) { const int v = atoi(e); if (v >= 1) band = (unsigned)v; }
     if (fmt == 0) {
-        if (q_t) hipLaunchKernelGGL((quantize_patch_kernel<0, true, V>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word);
-        else hipLaunchKernelGGL((quantize_patch_kernel<0, false, V>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word);
+        if (q_t) hipLaunchKernelGGL((quantize_patch_kernel<0, true, V>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word, gr, gc, band);
+        else hipLaunchKernelGGL((quantize_patch_kernel<0, false, V>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word, gr, gc, band);
     } else {
-        if (q_t) hipLaunchKernelGGL((quantize_patch_kernel<1, true, V>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word);
-        else hipLaunchKernelGGL((quantize_patch_kernel<1, false, V>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word);
+        if (q_t) hipLaunchKernelGGL((quantize_patch_kernel<1, true, V>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word, gr, gc, band);
+        else hipLaunchKernelGGL((quantize_patch_kernel<1, false, V>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word, gr, gc, band);
     }
 }
 
