@@ -172,12 +172,13 @@ template <int PR, int QFMT, bool TRANSPOSE, bool WRITE_Y>
 __global__ __launch_bounds__(kRnThreads) void rmsnorm_apply_fp8_patch_kernel(
     const uint16_t* __restrict__ res, const uint16_t* __restrict__ w, const float* __restrict__ rstd,
     int64_t M, int64_t C, const float* __restrict__ d_qscale, uint8_t* __restrict__ q,
-    uint8_t* __restrict__ qt, uint16_t* __restrict__ y) {
+    uint8_t* __restrict__ qt, uint16_t* __restrict__ y, unsigned grid_cols) {
     static_assert(!TRANSPOSE || PR == 16, "the register transpose works on 16 x 8 patches");
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const int64_t r0 = (int64_t)blockIdx.x * (PR * kRnLanesR) + (lane % kRnLanesR) * PR;
-    const int64_t c0 = (int64_t)blockIdx.y * kRnBlockCols + wave * (8 * (kWave / kRnLanesR)) + (lane / kRnLanesR) * 8;
+    const unsigned brow = blockIdx.x / grid_cols, bcol = blockIdx.x % grid_cols;     // walk along the columns
+    const int64_t r0 = (int64_t)brow * (PR * kRnLanesR) + (lane % kRnLanesR) * PR;
+    const int64_t c0 = (int64_t)bcol * kRnBlockCols + wave * (8 * (kWave / kRnLanesR)) + (lane / kRnLanesR) * 8;
     if (r0 >= M || c0 >= C) return;
     const uint16_t* src = res + r0 * C + c0;
     v4u in[PR];
@@ -272,13 +273,13 @@ static void launch_apply(const uint16_t* res, const uint16_t* w, const float* rs
     const dim3 block(kRnThreads);
     const unsigned gc = (unsigned)((C + kRnBlockCols - 1) / kRnBlockCols);
     if (q_t && M % 16 == 0 && C % 8 == 0) {
-        const dim3 grid((unsigned)((M + 16 * kRnLanesR - 1) / (16 * kRnLanesR)), gc);
-        if (y) hipLaunchKernelGGL((rmsnorm_apply_fp8_patch_kernel<16, QFMT, true, true>), grid, block, 0, stream, res, w, rstd, M, C, d_qscale, q, q_t, y);
-        else hipLaunchKernelGGL((rmsnorm_apply_fp8_patch_kernel<16, QFMT, true, false>), grid, block, 0, stream, res, w, rstd, M, C, d_qscale, q, q_t, y);
+        const dim3 grid((unsigned)((M + 16 * kRnLanesR - 1) / (16 * kRnLanesR)) * gc);
+        if (y) hipLaunchKernelGGL((rmsnorm_apply_fp8_patch_kernel<16, QFMT, true, true>), grid, block, 0, stream, res, w, rstd, M, C, d_qscale, q, q_t, y, gc);
+        else hipLaunchKernelGGL((rmsnorm_apply_fp8_patch_kernel<16, QFMT, true, false>), grid, block, 0, stream, res, w, rstd, M, C, d_qscale, q, q_t, y, gc);
     } else if (!q_t && M % 4 == 0 && C % 8 == 0) {
-        const dim3 grid((unsigned)((M + 4 * kRnLanesR - 1) / (4 * kRnLanesR)), gc);
-        if (y) hipLaunchKernelGGL((rmsnorm_apply_fp8_patch_kernel<4, QFMT, false, true>), grid, block, 0, stream, res, w, rstd, M, C, d_qscale, q, q_t, y);
-        else hipLaunchKernelGGL((rmsnorm_apply_fp8_patch_kernel<4, QFMT, false, false>), grid, block, 0, stream, res, w, rstd, M, C, d_qscale, q, q_t, y);
+        const dim3 grid((unsigned)((M + 4 * kRnLanesR - 1) / (4 * kRnLanesR)) * gc);
+        if (y) hipLaunchKernelGGL((rmsnorm_apply_fp8_patch_kernel<4, QFMT, false, true>), grid, block, 0, stream, res, w, rstd, M, C, d_qscale, q, q_t, y, gc);
+        else hipLaunchKernelGGL((rmsnorm_apply_fp8_patch_kernel<4, QFMT, false, false>), grid, block, 0, stream, res, w, rstd, M, C, d_qscale, q, q_t, y, gc);
     } else {
         int64_t blocks = (M * C + kRnThreads - 1) / kRnThreads;
         if (blocks > 65536) blocks = 65536;

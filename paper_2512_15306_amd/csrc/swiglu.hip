@@ -94,13 +94,15 @@ template <int PR, bool WRITE_H, bool AMAX, int QFMT, bool TRANSPOSE>
 __global__ __launch_bounds__(kSwThreads) void swiglu_fwd_patch_kernel(
     const uint16_t* __restrict__ gu, int64_t M, int64_t I, uint16_t* __restrict__ h,
     unsigned* __restrict__ partial, const float* __restrict__ d_qscale, uint8_t* __restrict__ q,
-    uint8_t* __restrict__ qt) {
+    uint8_t* __restrict__ qt, unsigned grid_cols) {
     static_assert(!TRANSPOSE || PR == 16, "the register transpose works on 16 x 8 patches");
     __shared__ unsigned s_part[kSwThreads / kWave];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const int64_t r0 = (int64_t)blockIdx.x * (PR * kSwLanesR) + (lane % kSwLanesR) * PR;
-    const int64_t c0 = (int64_t)blockIdx.y * kSwBlockCols + wave * (8 * (kWave / kSwLanesR)) + (lane / kSwLanesR) * 8;
+    // consecutive workgroups walk along the columns (measured a few percent faster than down the rows)
+    const unsigned brow = blockIdx.x / grid_cols, bcol = blockIdx.x % grid_cols;
+    const int64_t r0 = (int64_t)brow * (PR * kSwLanesR) + (lane % kSwLanesR) * PR;
+    const int64_t c0 = (int64_t)bcol * kSwBlockCols + wave * (8 * (kWave / kSwLanesR)) + (lane / kSwLanesR) * 8;
     const bool live = r0 < M && c0 < I;
     unsigned mag = 0;
     if (live) {
@@ -166,20 +168,21 @@ __global__ __launch_bounds__(kSwThreads) void swiglu_fwd_patch_kernel(
     }
     if constexpr (AMAX) {
         mag = block_max_u32<kSwThreads>(mag, s_part);
-        if (threadIdx.x == 0) partial[blockIdx.y * gridDim.x + blockIdx.x] = mag;
+        if (threadIdx.x == 0) partial[blockIdx.x] = mag;
     }
 }
 
 // Backward: dh [M, I], GU [M, 2I] -> dGU [M, 2I], one partial absmax per workgroup.  M % 4 == 0, I % 8 == 0.
 __global__ __launch_bounds__(kSwThreads) void swiglu_bwd_patch_kernel(
     const uint16_t* __restrict__ dh, const uint16_t* __restrict__ gu, int64_t M, int64_t I,
-    uint16_t* __restrict__ dgu, unsigned* __restrict__ partial) {
+    uint16_t* __restrict__ dgu, unsigned* __restrict__ partial, unsigned grid_cols) {
     constexpr int PR = 4;
     __shared__ unsigned s_part[kSwThreads / kWave];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    const int64_t r0 = (int64_t)blockIdx.x * (PR * kSwLanesR) + (lane % kSwLanesR) * PR;
-    const int64_t c0 = (int64_t)blockIdx.y * kSwBlockCols + wave * (8 * (kWave / kSwLanesR)) + (lane / kSwLanesR) * 8;
+    const unsigned brow = blockIdx.x / grid_cols, bcol = blockIdx.x % grid_cols;
+    const int64_t r0 = (int64_t)brow * (PR * kSwLanesR) + (lane % kSwLanesR) * PR;
+    const int64_t c0 = (int64_t)bcol * kSwBlockCols + wave * (8 * (kWave / kSwLanesR)) + (lane / kSwLanesR) * 8;
     unsigned mag = 0;
     if (r0 < M && c0 < I) {
         const uint16_t* src = gu + r0 * (2 * I) + c0;
@@ -214,7 +217,7 @@ __global__ __launch_bounds__(kSwThreads) void swiglu_bwd_patch_kernel(
         mag = fold_max(m0, m1, m2, m3);
     }
     mag = block_max_u32<kSwThreads>(mag, s_part);
-    if (threadIdx.x == 0) partial[blockIdx.y * gridDim.x + blockIdx.x] = mag;
+    if (threadIdx.x == 0) partial[blockIdx.x] = mag;
 }
 
 // Any shape, one element per lane and trip.
@@ -292,9 +295,9 @@ static int64_t patch_blocks(int64_t M, int64_t I, int pr) {
 template <int PR, bool WRITE_H, bool AMAX, int QFMT, bool TRANSPOSE>
 static void launch_fwd_patch(const uint16_t* gu, int64_t M, int64_t I, uint16_t* h, unsigned* partial,
                              const float* d_qscale, uint8_t* q, uint8_t* q_t, hipStream_t stream) {
-    dim3 grid((unsigned)((M + PR * kSwLanesR - 1) / (PR * kSwLanesR)), (unsigned)((I + kSwBlockCols - 1) / kSwBlockCols));
-    hipLaunchKernelGGL((swiglu_fwd_patch_kernel<PR, WRITE_H, AMAX, QFMT, TRANSPOSE>), grid, dim3(kSwThreads), 0, stream,
-                       gu, M, I, h, partial, d_qscale, q, q_t);
+    const unsigned gr = (unsigned)((M + PR * kSwLanesR - 1) / (PR * kSwLanesR)), gc = (unsigned)((I + kSwBlockCols - 1) / kSwBlockCols);
+    hipLaunchKernelGGL((swiglu_fwd_patch_kernel<PR, WRITE_H, AMAX, QFMT, TRANSPOSE>), dim3(gr * gc), dim3(kSwThreads), 0, stream,
+                       gu, M, I, h, partial, d_qscale, q, q_t, gc);
 }
 
 template <int QFMT>
@@ -341,10 +344,10 @@ int launch_swiglu_fwd(const void* gu_, int64_t M, int64_t I, void* h_, unsigned*
 int launch_swiglu_bwd(const void* dh, const void* gu, int64_t M, int64_t I, void* dgu, unsigned* partial,
                       int amax_fmt, float* d_amax, float* d_scale, hipStream_t stream) {
     if (patch_ok(M, I, 4)) {
-        dim3 grid((unsigned)((M + 4 * kSwLanesR - 1) / (4 * kSwLanesR)), (unsigned)((I + kSwBlockCols - 1) / kSwBlockCols));
-        hipLaunchKernelGGL(swiglu_bwd_patch_kernel, grid, dim3(kSwThreads), 0, stream,
+        const unsigned gr = (unsigned)((M + 4 * kSwLanesR - 1) / (4 * kSwLanesR)), gc = (unsigned)((I + kSwBlockCols - 1) / kSwBlockCols);
+        hipLaunchKernelGGL(swiglu_bwd_patch_kernel, dim3(gr * gc), dim3(kSwThreads), 0, stream,
                            reinterpret_cast<const uint16_t*>(dh), reinterpret_cast<const uint16_t*>(gu), M, I,
-                           reinterpret_cast<uint16_t*>(dgu), partial);
+                           reinterpret_cast<uint16_t*>(dgu), partial, gc);
     } else {
         hipLaunchKernelGGL(swiglu_bwd_generic_kernel, dim3((unsigned)generic_blocks(M, I)), dim3(kSwThreads), 0, stream,
                            reinterpret_cast<const uint16_t*>(dh), reinterpret_cast<const uint16_t*>(gu), M, I,
