@@ -107,42 +107,51 @@ __global__ __launch_bounds__(kSwThreads) void swiglu_fwd_patch_kernel(
     unsigned mag = 0;
     if (live) {
         const uint16_t* src = gu + r0 * (2 * I) + c0;
-        v4u g[PR], u[PR];
+        // Rows in groups of at most 8: sixteen 16-byte loads in flight per lane, then the arithmetic and the
+        // row-major stores of those rows; only the FP8 words of a row (two registers) live on to the transpose.
+        constexpr int kGroup = PR < 8 ? PR : 8;
+        float s = 0.0f;
+        if constexpr (QFMT >= 0) s = *d_qscale;
+        unsigned w[PR][2];
+        unsigned m0 = 0, m1 = 0, m2 = 0, m3 = 0;
 #pragma unroll
-        for (int i = 0; i < PR; ++i) {
-            g[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(src + (int64_t)i * 2 * I));
-            u[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(src + (int64_t)i * 2 * I + I));
-        }
-        v4u o[PR];
+        for (int i0 = 0; i0 < PR; i0 += kGroup) {
+            v4u g[kGroup], u[kGroup], o[kGroup];
 #pragma unroll
-        for (int i = 0; i < PR; ++i) o[i] = swiglu8(g[i], u[i]);
-        if constexpr (WRITE_H) {
-            uint16_t* dst = h + r0 * I + c0;
-#pragma unroll
-            for (int i = 0; i < PR; ++i) *reinterpret_cast<v4u*>(dst + (int64_t)i * I) = o[i];
-        }
-        if constexpr (AMAX) {
-            unsigned m0 = 0, m1 = 0, m2 = 0, m3 = 0;
-#pragma unroll
-            for (int i = 0; i < PR; ++i) {
-                m0 = pk_max_mag(m0, o[i][0]);
-                m1 = pk_max_mag(m1, o[i][1]);
-                m2 = pk_max_mag(m2, o[i][2]);
-                m3 = pk_max_mag(m3, o[i][3]);
+            for (int i = 0; i < kGroup; ++i) {
+                g[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(src + (int64_t)(i0 + i) * 2 * I));
+                u[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(src + (int64_t)(i0 + i) * 2 * I + I));
             }
-            mag = fold_max(m0, m1, m2, m3);
+#pragma unroll
+            for (int i = 0; i < kGroup; ++i) o[i] = swiglu8(g[i], u[i]);
+            if constexpr (WRITE_H) {
+                uint16_t* dst = h + (r0 + i0) * I + c0;
+#pragma unroll
+                for (int i = 0; i < kGroup; ++i) *reinterpret_cast<v4u*>(dst + (int64_t)i * I) = o[i];
+            }
+            if constexpr (AMAX) {
+#pragma unroll
+                for (int i = 0; i < kGroup; ++i) {
+                    m0 = pk_max_mag(m0, o[i][0]);
+                    m1 = pk_max_mag(m1, o[i][1]);
+                    m2 = pk_max_mag(m2, o[i][2]);
+                    m3 = pk_max_mag(m3, o[i][3]);
+                }
+            }
+            if constexpr (QFMT >= 0) {
+#pragma unroll
+                for (int i = 0; i < kGroup; ++i) quantize8<QFMT>(o[i], s, w[i0 + i][0], w[i0 + i][1]);
+                uint8_t* dq = q + (r0 + i0) * I + c0;
+#pragma unroll
+                for (int i = 0; i < kGroup; ++i) {
+                    v2u v = {w[i0 + i][0], w[i0 + i][1]};
+                    *reinterpret_cast<v2u*>(dq + (int64_t)i * I) = v;
+                }
+            }
+            if constexpr (PR > kGroup) __builtin_amdgcn_sched_barrier(0);
         }
+        if constexpr (AMAX) mag = fold_max(m0, m1, m2, m3);
         if constexpr (QFMT >= 0) {
-            const float s = *d_qscale;
-            unsigned w[PR][2];
-#pragma unroll
-            for (int i = 0; i < PR; ++i) quantize8<QFMT>(o[i], s, w[i][0], w[i][1]);
-            uint8_t* dq = q + r0 * I + c0;
-#pragma unroll
-            for (int i = 0; i < PR; ++i) {
-                v2u v = {w[i][0], w[i][1]};
-                *reinterpret_cast<v2u*>(dq + (int64_t)i * I) = v;
-            }
             if constexpr (TRANSPOSE) {
                 // column j of the patch -> 16 consecutive bytes of row (c0 + j) of the transposed tensor
                 uint8_t* dt = qt + c0 * M + r0;
