@@ -70,23 +70,24 @@ class LinearState:
         return self.ws[o:o + shape[0] * shape[1]].view(shape)
 
 
-def run_step(states, prequantized_w, producer_absmax=False):
+def run_step(states, prequantized_w, producer_absmax=False, extra_flags=0):
     """Per linear: absmax + scale + quantize(+transpose) of X and W inside the forward call (just-in-time
     scaling: first absmax stage, then the quantize kernel finishes the reduction), forward GEMM, the same for
     dY inside the dgrad call, dgrad GEMM, wgrad GEMM on the copies already there.
     producer_absmax: the absmax passes over X and dY are left out, as when the producing kernel (RMSNorm,
     SwiGLU, the previous GEMM's epilogue) has already delivered them; the scales of the last full step are
-    used.  Reported as a side figure only."""
+    used.  Reported as a side figure only.
+    extra_flags: LLMQ_NO_TRANSPOSE for the side figure without transposed copies."""
     from paper_2512_15306_amd import llmq
     for s in states:
         M, K, N = s.M, s.K, s.N
-        fx = 0 if producer_absmax else llmq.JIT_X
+        fx = extra_flags | (0 if producer_absmax else llmq.JIT_X)
         fw = llmq.REUSE_W if prequantized_w else llmq.JIT_W
         llmq.llmq_fp8_linear_fwd(s.X, s.W, M, N, K, s.sx, s.sw, s.Y, s.ay, s.ws, fx | fw)
-        fd = 0 if producer_absmax else llmq.JIT_DY
+        fd = extra_flags | (0 if producer_absmax else llmq.JIT_DY)
         llmq.llmq_fp8_linear_dgrad(s.dY, None, M, N, K, s.sd, s.sw, llmq.E5M2, s.dX, s.adx, s.ws, llmq.REUSE_W | fd)
         llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, s.sd, s.sx, llmq.E5M2, s.dW, False, s.ws,
-                                   llmq.REUSE_X | llmq.REUSE_DY)
+                                   extra_flags | llmq.REUSE_X | llmq.REUSE_DY)
 
 
 def run_gemms_only(states):
@@ -325,6 +326,10 @@ def main():
     ms_amax = timed(lambda: run_amax_only(states), reps)
     ms_qk = timed(lambda: run_quantize_kernel_only(states), reps)
     ms_fused = timed(lambda: run_step(states, args.prequantized_w, producer_absmax=True), reps)
+    # the same step on row-major FP8 copies only (the backward GEMMs read them T-major): a side figure
+    run_step(states, args.prequantized_w, extra_flags=llmq.NO_TRANSPOSE)       # first use loads those kernels
+    ms_nt = timed(lambda: run_step(states, args.prequantized_w, extra_flags=llmq.NO_TRANSPOSE), reps)
+    ms_nt_fused = timed(lambda: run_step(states, args.prequantized_w, producer_absmax=True, extra_flags=llmq.NO_TRANSPOSE), reps)
     qbytes = 6.0 * synth.quantize_elements(cfg)         # absmax reads 2 B, quantize reads 2 B and writes 1 + 1 B
     out = {
         "metric": "FP8 linear fwd+bwd TFLOP/s and % dense-FP8 MFMA peak; quantize GB/s",
@@ -346,10 +351,12 @@ def main():
         "quantize_kernel_only_gbps": round(4.0 * synth.quantize_elements(cfg) / (ms_qk * 1e-3) / 1e9, 1),
         "quantize_kernel_only_pct_hbm_peak": round(100.0 * 4.0 * synth.quantize_elements(cfg) / (ms_qk * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2),
         "step_tflops_with_producer_fused_absmax": round(flops / (ms_fused * 1e-3) / 1e12, 2),
+        "step_tflops_without_transposed_copies": round(flops / (ms_nt * 1e-3) / 1e12, 2),
+        "step_tflops_without_transposed_copies_with_producer_fused_absmax": round(flops / (ms_nt_fused * 1e-3) / 1e12, 2),
         "measured_peaks": peaks,
         "gemm_only_pct_measured_random_bits_peak": round(100.0 * gemm_tflops / peaks["mfma_fp8_random_bits_tflops"], 2),
         "quantize_pct_measured_copy": round(100.0 * qbytes / (ms_quant * 1e-3) / 1e9 / peaks["hbm_copy_gbps"], 2),
-        "roofline": {"kernel": "gemm_tn_tile_kernel", "bound": "mfma", "achieved": round(gemm_tflops, 2),
+        "roofline": {"kernel": "gemm_tile_kernel", "bound": "mfma", "achieved": round(gemm_tflops, 2),
                      "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_FP8_TFLOPS, 4),
                      "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(cfg.index), "launches_per_step": n_gemm,
                      "avg_launch_ms": round(ms_gemm / n_gemm, 5),

@@ -105,6 +105,26 @@ int llmq_fp8_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB,
                      void* c_bf16, int accumulate, float* d_amax_c, void* stream);
 
 /*
+ * The same contraction with either operand optionally "T-major": stored [T, rows] (the contraction index
+ * runs down the rows, the rows index is contiguous) instead of [rows, T].
+ *   a_t_major != 0: A is [T,R];   b_t_major != 0: B is [T,C];   both 0: identical to llmq_fp8_gemm_tn.
+ * The paper keeps transposed FP8 copies of every quantized tensor because the FP8 GEMM it builds on only
+ * takes contraction-contiguous operands, and names the extra transposes and buffers as the cost of FP8
+ * (Section 3, kernel-fusion paragraph; Section 4 "Impact of FP8").  Here the tile kernel transposes a
+ * T-major operand on its way from LDS to the matrix cores, so the backward GEMMs can read the row-major
+ * copies the forward pass made:
+ *   dX[m,k] = sum_n dYq[m,n] Wq[n,k]   : A = dYq [M,N],            B = Wq [N,K] T-major, T = N
+ *   dW[n,k] = sum_m dYq[m,n] Xq[m,k]   : A = dYq [M,N] T-major,    B = Xq [M,K] T-major, T = M
+ * Every product lands in the same accumulator position as with transposed copies, so the result is
+ * bit-identical to llmq_fp8_gemm_tn on those copies.  Tuned for B in E4M3 with R, C multiples of 128 and T a
+ * multiple of 128; other cases take a slow generic kernel.  Arguments otherwise as above.
+ */
+int llmq_fp8_gemm(const uint8_t* A, int fmtA, int a_t_major, const uint8_t* B, int fmtB, int b_t_major,
+                  int64_t R, int64_t C, int64_t T,
+                  const float* d_scaleA, const float* d_scaleB,
+                  void* c_bf16, int accumulate, float* d_amax_c, void* stream);
+
+/*
  * BF16 baseline of the same contraction, for the FP8-versus-BF16 comparison the paper reports (Section 4,
  * "Impact of FP8", speed-up column of Table 1): no quantization, no scales,
  *   c[r,cc] = bf16( sum_t A[r,t] * B[cc,t] )   (+ c[r,cc] first when accumulate != 0)
@@ -141,10 +161,16 @@ int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t of
 #define LLMQ_JIT_X   8
 #define LLMQ_JIT_W  16
 #define LLMQ_JIT_DY 32
+/* No transposed copies: the call writes only the row-major FP8 copies (Xq, Wq, dYq) and the backward GEMMs
+ * read those T-major (see llmq_fp8_gemm), which saves one byte written per quantized element.  The sections
+ * Xq_t, Wq_t, dYq_t of the workspace are then neither written nor read.  Copies made under this flag can only
+ * be reused (LLMQ_REUSE_*) by calls that carry it too; results are bit-identical either way. */
+#define LLMQ_NO_TRANSPOSE 64
 
 /*
  * Forward: Y[M,N] = X[M,K] W[N,K]^T in FP8 (E4M3 x E4M3), BF16 out.
- * Quantizes X and W (both layouts each, unless LLMQ_REUSE_X / LLMQ_REUSE_W) with the given scales, then
+ * Quantizes X and W (both layouts each, unless LLMQ_REUSE_X / LLMQ_REUSE_W; row-major only under
+ * LLMQ_NO_TRANSPOSE) with the given scales, then
  * runs the contraction on Xq and Wq.  d_amax_y may be NULL.
  */
 int llmq_fp8_linear_fwd(const void* X, const void* W, int64_t M, int64_t N, int64_t K,
@@ -154,7 +180,7 @@ int llmq_fp8_linear_fwd(const void* X, const void* W, int64_t M, int64_t N, int6
 /*
  * Input gradient: dX[M,K] = dY[M,N] W[N,K].  dY is quantized to fmt_dy (E5M2 or E4M3; the paper tried
  * both, Section 5 Scenario 1) unless LLMQ_REUSE_DY; W unless LLMQ_REUSE_W.  Contraction over N on dYq and
- * Wq_t.  W and dY pointers are not read for operands whose REUSE flag is set (and may then be NULL).
+ * Wq_t (on Wq read T-major under LLMQ_NO_TRANSPOSE).  W and dY pointers are not read for operands whose REUSE flag is set (and may then be NULL).
  */
 int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, int64_t K,
                           float* d_scale_dy, float* d_scale_w, int fmt_dy,
@@ -162,7 +188,7 @@ int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, i
 
 /*
  * Weight gradient: dW[N,K] = dY[M,N]^T X[M,K] (accumulate != 0: dW += ..., in BF16).  Contraction over M on
- * dYq_t and Xq_t.
+ * dYq_t and Xq_t (on dYq and Xq read T-major under LLMQ_NO_TRANSPOSE).
  */
 int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, int64_t K,
                           float* d_scale_dy, float* d_scale_x, int fmt_dy,

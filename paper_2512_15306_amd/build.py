@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libllmq.so")
-SOURCES = ["api.hip", "amax.hip", "quantize.hip", "gemm.hip", "swiglu.hip", "rmsnorm.hip", "calibrate.hip"]
+SOURCES = ["api.hip", "amax.hip", "quantize.hip", "gemm.hip", "gemm_tmajor.hip", "swiglu.hip", "rmsnorm.hip", "calibrate.hip"]
 # packed-fp32 VALU ops are disabled on purpose (they have produced silent wrong results on this
 # hardware pool); never add -ffast-math: the scale needs a correctly rounded division.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

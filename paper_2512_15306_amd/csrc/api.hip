@@ -48,7 +48,7 @@ WsLayout ws_layout(int64_t M, int64_t N, int64_t K) {
 int check_linear(int64_t M, int64_t N, int64_t K, const void* ws, size_t ws_bytes, int flags) {
     if (!dim_ok(M) || !dim_ok(N) || !dim_ok(K)) return LLMQ_ERR_SHAPE;
     if (M * K >= kMaxElems || N * K >= kMaxElems || M * N >= kMaxElems) return LLMQ_ERR_SHAPE;
-    if (flags & ~(LLMQ_REUSE_X | LLMQ_REUSE_W | LLMQ_REUSE_DY | LLMQ_JIT_X | LLMQ_JIT_W | LLMQ_JIT_DY)) return LLMQ_ERR_FLAGS;
+    if (flags & ~(LLMQ_REUSE_X | LLMQ_REUSE_W | LLMQ_REUSE_DY | LLMQ_JIT_X | LLMQ_JIT_W | LLMQ_JIT_DY | LLMQ_NO_TRANSPOSE)) return LLMQ_ERR_FLAGS;
     // an operand is either reused or scaled just in time, not both
     if (((flags & LLMQ_REUSE_X) && (flags & LLMQ_JIT_X)) || ((flags & LLMQ_REUSE_W) && (flags & LLMQ_JIT_W)) ||
         ((flags & LLMQ_REUSE_DY) && (flags & LLMQ_JIT_DY)))
@@ -95,7 +95,7 @@ const char* llmq_status_string(int status) {
     }
 }
 
-int llmq_version(void) { return 110; }
+int llmq_version(void) { return 120; }
 
 size_t llmq_amax_workspace_bytes(void) { return (size_t)llmq::kAmaxMaxPartials * sizeof(unsigned); }
 
@@ -130,6 +130,20 @@ int llmq_fp8_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int
         return LLMQ_ERR_ALIGN;
     return llmq::launch_gemm_tn(A, fmtA, B, fmtB, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, d_amax_c, false,
                                 static_cast<hipStream_t>(stream), num_cus());
+}
+
+int llmq_fp8_gemm(const uint8_t* A, int fmtA, int a_t_major, const uint8_t* B, int fmtB, int b_t_major, int64_t R,
+                  int64_t C, int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16, int accumulate,
+                  float* d_amax_c, void* stream) {
+    if (!A || !B || !d_scaleA || !d_scaleB || !c_bf16) return LLMQ_ERR_NULL;
+    if (!dim_ok(R) || !dim_ok(C) || !dim_ok(T)) return LLMQ_ERR_SHAPE;
+    if (R * T >= kMaxElems || C * T >= kMaxElems || R * C >= kMaxElems) return LLMQ_ERR_SHAPE;
+    if (!fmt_ok(fmtA) || !fmt_ok(fmtB)) return LLMQ_ERR_FORMAT;
+    if (!aligned(A, 16) || !aligned(B, 16) || !aligned(c_bf16, 16) || !aligned(d_scaleA, 4) ||
+        !aligned(d_scaleB, 4) || !aligned(d_amax_c, 4))
+        return LLMQ_ERR_ALIGN;
+    return llmq::launch_gemm_fp8(A, fmtA, a_t_major != 0, B, fmtB, b_t_major != 0, R, C, T, d_scaleA, d_scaleB, c_bf16,
+                                 accumulate, d_amax_c, false, static_cast<hipStream_t>(stream), num_cus());
 }
 
 int llmq_bf16_gemm_tn(const void* A_bf16, const void* B_bf16, int64_t R, int64_t C, int64_t T, void* c_bf16,
@@ -174,8 +188,9 @@ int llmq_fp8_linear_fwd(const void* X, const void* W, int64_t M, int64_t N, int6
     const bool zeroed = zero && (qx || qw);
     unsigned* part = reinterpret_cast<unsigned*>(base + l.part);
     constexpr size_t kPartWords = 256 * ((llmq::kAmaxMaxPartials * sizeof(unsigned) + 255) / 256) / sizeof(unsigned);
-    if (qx && (st = quantize_operand(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, base + l.xqt, (flags & LLMQ_JIT_X) != 0, part, zero, s))) return st;
-    if (qw && (st = quantize_operand(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, base + l.wqt, (flags & LLMQ_JIT_W) != 0, part + kPartWords, qx ? nullptr : zero, s))) return st;
+    const bool nt = (flags & LLMQ_NO_TRANSPOSE) != 0;
+    if (qx && (st = quantize_operand(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, nt ? nullptr : base + l.xqt, (flags & LLMQ_JIT_X) != 0, part, zero, s))) return st;
+    if (qw && (st = quantize_operand(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, nt ? nullptr : base + l.wqt, (flags & LLMQ_JIT_W) != 0, part + kPartWords, qx ? nullptr : zero, s))) return st;
     return llmq::launch_gemm_tn(base + l.xq, LLMQ_E4M3, base + l.wq, LLMQ_E4M3, M, N, K, d_scale_x, d_scale_w,
                                 Y, 0, d_amax_y, zeroed, s, num_cus());
 }
@@ -199,11 +214,12 @@ int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, i
     const bool zeroed = zero && (qd || qw);
     unsigned* part = reinterpret_cast<unsigned*>(base + l.part);
     constexpr size_t kPartWords = 256 * ((llmq::kAmaxMaxPartials * sizeof(unsigned) + 255) / 256) / sizeof(unsigned);
-    if (qd && (st = quantize_operand(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, base + l.dyqt, (flags & LLMQ_JIT_DY) != 0, part + 2 * kPartWords, zero, s))) return st;
-    if (qw && (st = quantize_operand(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, base + l.wqt, (flags & LLMQ_JIT_W) != 0, part + kPartWords, qd ? nullptr : zero, s))) return st;
-    // dX[m,k] = sum_n dYq[m,n] * Wq_t[k,n]
-    return llmq::launch_gemm_tn(base + l.dyq, fmt_dy, base + l.wqt, LLMQ_E4M3, M, K, N, d_scale_dy, d_scale_w,
-                                dX, 0, d_amax_dx, zeroed, s, num_cus());
+    const bool nt = (flags & LLMQ_NO_TRANSPOSE) != 0;
+    if (qd && (st = quantize_operand(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, nt ? nullptr : base + l.dyqt, (flags & LLMQ_JIT_DY) != 0, part + 2 * kPartWords, zero, s))) return st;
+    if (qw && (st = quantize_operand(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, nt ? nullptr : base + l.wqt, (flags & LLMQ_JIT_W) != 0, part + kPartWords, qd ? nullptr : zero, s))) return st;
+    // dX[m,k] = sum_n dYq[m,n] * Wq_t[k,n] = sum_n dYq[m,n] * Wq[n,k]
+    return llmq::launch_gemm_fp8(base + l.dyq, fmt_dy, false, nt ? base + l.wq : base + l.wqt, LLMQ_E4M3, nt, M, K, N,
+                                 d_scale_dy, d_scale_w, dX, 0, d_amax_dx, zeroed, s, num_cus());
 }
 
 int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, int64_t K,
@@ -223,11 +239,12 @@ int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, i
     hipStream_t s = static_cast<hipStream_t>(stream);
     unsigned* part = reinterpret_cast<unsigned*>(base + l.part);
     constexpr size_t kPartWords = 256 * ((llmq::kAmaxMaxPartials * sizeof(unsigned) + 255) / 256) / sizeof(unsigned);
-    if (qd && (st = quantize_operand(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, base + l.dyqt, (flags & LLMQ_JIT_DY) != 0, part + 2 * kPartWords, nullptr, s))) return st;
-    if (qx && (st = quantize_operand(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, base + l.xqt, (flags & LLMQ_JIT_X) != 0, part, nullptr, s))) return st;
-    // dW[n,k] = sum_m dYq_t[n,m] * Xq_t[k,m]
-    return llmq::launch_gemm_tn(base + l.dyqt, fmt_dy, base + l.xqt, LLMQ_E4M3, N, K, M, d_scale_dy, d_scale_x,
-                                dW, accumulate, nullptr, false, s, num_cus());
+    const bool nt = (flags & LLMQ_NO_TRANSPOSE) != 0;
+    if (qd && (st = quantize_operand(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, nt ? nullptr : base + l.dyqt, (flags & LLMQ_JIT_DY) != 0, part + 2 * kPartWords, nullptr, s))) return st;
+    if (qx && (st = quantize_operand(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, nt ? nullptr : base + l.xqt, (flags & LLMQ_JIT_X) != 0, part, nullptr, s))) return st;
+    // dW[n,k] = sum_m dYq_t[n,m] * Xq_t[k,m] = sum_m dYq[m,n] * Xq[m,k]
+    return llmq::launch_gemm_fp8(nt ? base + l.dyq : base + l.dyqt, fmt_dy, nt, nt ? base + l.xq : base + l.xqt, LLMQ_E4M3, nt,
+                                 N, K, M, d_scale_dy, d_scale_x, dW, accumulate, nullptr, false, s, num_cus());
 }
 
 int llmq_scale_from_amax(const float* d_amax, int fmt, float* d_scale, void* stream) {

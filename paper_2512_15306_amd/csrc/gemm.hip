@@ -1,479 +1,20 @@
-// FP8 contraction on the gfx950 matrix cores (paper Section 3: the transformer-block matmuls of
-// forward and backward run in FP8, results stay in BF16; the FP8 GEMM is "TN", i.e. both operands
-// have the contraction index contiguous).
-//
-//   C[r,c] = bf16( (sum_t A[r,t] * B[c,t]) / (sA * sB) ),   A [R,T] fp8, B [Cn,T] fp8.
-//
-// Tuned kernel (template on the wave tile NI x NJ in units of 32: workgroup tile BM x BN with
-// BM = 64 NI, BN = 64 NJ, both in {128, 192, 256}; R % BM == 0, Cn % BN == 0, T % 128 == 0)
-//   - one workgroup of 4 wavefronts (2 x 2) per output tile, one workgroup per CU; a wavefront owns
-//     NI x NJ blocks of v_mfma_f32_32x32x64_f8f6f4 with fp32 accumulators (256 registers per lane
-//     at 4 x 4);
-//   - K advances 128 bytes per step; the A and B slabs (BM / BN rows x 128 B) go from global memory
-//     straight into LDS with buffer_load ... lds (16 bytes per lane, no VGPR staging), double buffered;
-//   - LDS rows are 128 B; the 16-byte chunk index is XOR-ed with (row >> 1) & 7, applied on the
-//     global side of the load, so that ds_read_b128 fragment reads of 16 consecutive rows spread
-//     over all 64 banks;
-//   - the order of the contraction index inside one MFMA does not matter as long as A and B use
-//     the same order, so every lane simply reads 32 contiguous bytes of its row;
-//   - every step is software pipelined in two halves: the MFMAs of one 64-byte half run while the
-//     fragments of the next half are read and the slab after next is requested; one barrier per step;
-//   - the MFMA takes the B rows as its first operand, which leaves every lane with 4 consecutive
-//     output columns of one row; the epilogue de-scales in fp32, rounds to BF16 with the hardware
-//     conversion, takes the output absmax on the rounded bits, stages the wave's quadrant in LDS
-//     and stores full row segments, 16 bytes per lane;
-//   - workgroup ids are dealt round-robin to the 8 XCDs by the hardware, so ids are remapped to give
-//     each XCD (own L2) a contiguous range of tiles, walked in bands 8 tile-rows high;
-//   - the host picks NI x NJ per problem so that the tiles fill the 256 CUs in whole rounds.
-// Generic kernel: any shape, one wavefront per 16x16 outputs, guarded loads; slow, for tests and
-// odd sizes.
-#include <stdlib.h>
-
-#include "llmq_device.h"
-#include "llmq_kernels.h"
+// FP8 contraction with both operands contraction-contiguous ("TN"), its BF16 baseline, and the kernels for
+// shapes no tuned tile divides.  The tile kernel itself is in gemm_tile.h.
+#include "gemm_tile.h"
 
 namespace llmq {
 
-typedef __attribute__((address_space(3))) void lds_void;
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+void launch_gemm_generic(const uint8_t* A, int fmtA, bool ta, const uint8_t* B, int fmtB, bool tb, int64_t R, int64_t C,
+                         int64_t T, const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
+                         hipStream_t stream);
 
-constexpr int BK = 128;
-constexpr int kGemmThreads = 256;
-constexpr int kXcds = 8;
-constexpr int kBandRows = 8;
-
-__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
-    // raw buffer, no stride; out-of-range reads return zero instead of faulting
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
-}
-
-// Linear workgroup id -> output tile, XCD-aware.  Returns false for the padding ids.
-__device__ inline bool tile_of_block(int pid, int tiles_r, int tiles_c, int band_rows, int& tr, int& tc) {
-    const int nt = tiles_r * tiles_c;
-    const int per_xcd = (nt + kXcds - 1) / kXcds;
-    const int id = (pid % kXcds) * per_xcd + pid / kXcds;
-    if (id >= nt) return false;
-    const int band = band_rows * tiles_c;
-    const int first = (id / band) * band_rows;
-    const int h = tiles_r - first < band_rows ? tiles_r - first : band_rows;
-    const int in_band = id % band;
-    tr = first + in_band % h;
-    tc = in_band / h;
-    return true;
-}
-
-// MFMA scheduling masks of __builtin_amdgcn_sched_group_barrier
-constexpr int kSchedMfma = 0x008, kSchedVmemRead = 0x020, kSchedDsRead = 0x100;
-
-// Tuning knobs of the tuned kernel.
-struct GemmTuning {
-    // Whether the kernel contains the L2 touch loads at all (their distance is a run-time argument).
-    static constexpr bool kTouch = true;
-    // One workgroup touches 1 / kTouchShareA of the lines of its A slab and 1 / kTouchShareB of its B
-    // slab: the workgroups that run side by side on an XCD (4 tile columns x 8 tile rows at a time)
-    // share each slab and cover it together.
-    static constexpr int kTouchShareA = 4, kTouchShareB = 8;
-    // Fragment reads ride along with the first 1 / kDsSpread of a half step's MFMAs (4 x 4 tiles) or
-    // 1 / kDsSpreadSmall (smaller tiles: fewer MFMAs per read, and three reads per MFMA slot from four waves
-    // are more than the LDS delivers; measured +1-4 % on 4 x 3, while 4 x 4 loses 1-4 % on whole rounds with
-    // the reads spread over the whole half), the direct-to-LDS loads with the first 1 / kVmSpread.
-    static constexpr int kDsSpread = 2, kDsSpreadSmall = 1, kVmSpread = 1;
-    static constexpr bool kNtStoreC = false;     // streaming hint on the output stores
-    // Scheduling fences between the 32-row blocks of the epilogue: without them the compiler hoists every
-    // de-scale multiply to the front and parks the products in accumulator registers.
-    static constexpr bool kEpilogueFence = true;
-    // Development aid: a tuning struct with kProfile = true also provides
-    //   static __device__ void record(int block, int slot, long long value)
-    // and gets cycle stamps of the phases of wave 0 of every workgroup.
-    static constexpr bool kProfile = false;
-    // LDS swizzle of the operand slabs: the 16-byte chunk index of a row is XOR-ed with
-    // (row >> kSwizzleShift) & 7.
-    static constexpr int kSwizzleShift = 1;
-};
-
-template <bool B>
-struct BoolTag { static constexpr bool value = B; };
-
-template <int N>
-__device__ inline void wait_vmcnt() {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
-// Workgroup barrier that orders LDS traffic only: the caller has already waited for the
-// direct-to-LDS loads it needs with wait_vmcnt<>, other global loads may stay in flight.
-__device__ inline void lds_barrier() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-// Operand kinds of the tuned kernel: 0 = E4M3, 1 = E5M2 (one byte per element, any mix), 2 = BF16 (both
-// operands; the baseline the FP8 path is compared with).  The kernel itself moves bytes: T is the length of
-// a row in bytes, and a lane's 32-byte fragment holds 32 FP8 or 16 BF16 contraction elements.
-constexpr int kFmtBf16 = 2;
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-
-template <int FA, int FB, int NI, int NJ>
-__device__ inline void mma_block(v16f (&acc)[NI][NJ], const v8i (&a)[NI], const v8i (&b)[NJ]) {
-    static_assert((FA == kFmtBf16) == (FB == kFmtBf16), "BF16 operands come in pairs");
-#pragma unroll
-    for (int i = 0; i < NI; ++i)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            if constexpr (FA == kFmtBf16) {
-                // two v_mfma_f32_32x32x16_bf16, one per 16-byte half of the fragments
-                const v4i a_lo = {a[i][0], a[i][1], a[i][2], a[i][3]}, a_hi = {a[i][4], a[i][5], a[i][6], a[i][7]};
-                const v4i b_lo = {b[j][0], b[j][1], b[j][2], b[j][3]}, b_hi = {b[j][4], b[j][5], b[j][6], b[j][7]};
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b_lo), __builtin_bit_cast(bf16x8, a_lo), acc[i][j], 0, 0, 0);
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b_hi), __builtin_bit_cast(bf16x8, a_hi), acc[i][j], 0, 0, 0);
-            } else {
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[i][j], FB, FA, 0, 0, 0, 0);
-            }
-        }
-}
-
-// Interleave NM MFMAs with ND LDS reads, spread over the first NM / DS_SPREAD MFMAs (so that they have
-// landed when the MFMAs end), and NV global loads, spread over the first NM / VM_SPREAD.
-template <int NM, int ND, int NV, int DS_SPREAD, int VM_SPREAD, int SYNC, int M = 0>
-__device__ inline void interleave() {
-    if constexpr (M < NM) {
-        constexpr int kDsSpan = (NM + DS_SPREAD - 1) / DS_SPREAD, kVmSpan = (NM + VM_SPREAD - 1) / VM_SPREAD;
-        constexpr int kDsPer = (ND + kDsSpan - 1) / kDsSpan;
-        constexpr int kVmPer = (NV + kVmSpan - 1) / kVmSpan;
-        constexpr int kDsLeft = ND - M * kDsPer, kVmLeft = NV - M * kVmPer;
-        __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, SYNC);
-        if constexpr (kDsLeft > 0) __builtin_amdgcn_sched_group_barrier(kSchedDsRead, kDsLeft < kDsPer ? kDsLeft : kDsPer, SYNC);
-        if constexpr (kVmLeft > 0) __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, kVmLeft < kVmPer ? kVmLeft : kVmPer, SYNC);
-        interleave<NM, ND, NV, DS_SPREAD, VM_SPREAD, SYNC, M + 1>();
-    }
-}
-
-template <int FA, int FB, int NI, int NJ, bool ACCUM, class V = GemmTuning>
-__global__ __launch_bounds__(kGemmThreads, 1) void gemm_tn_tile_kernel(
-    const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ C,
-    int Cn, int T, const float* __restrict__ d_sA, const float* __restrict__ d_sB,
-    unsigned* __restrict__ amax_bits, int tiles_r, int tiles_c, int touch_ahead, int band_rows, int next_stride) {
-    constexpr int BM = 64 * NI, BN = 64 * NJ;
-    constexpr int kSlabA = BM * BK, kSlabB = BN * BK;
-    // One array per stage and operand: distinct LDS objects let the compiler see that the
-    // direct-to-LDS loads of one stage do not alias the fragment reads of the other, so it does
-    // not make the reads wait for the loads in flight.
-    __shared__ __attribute__((aligned(1024))) uint8_t ldsA0[kSlabA];
-    __shared__ __attribute__((aligned(1024))) uint8_t ldsB0[kSlabB];
-    __shared__ __attribute__((aligned(1024))) uint8_t ldsA1[kSlabA];
-    __shared__ __attribute__((aligned(1024))) uint8_t ldsB1[kSlabB];
-    // Four words for the workgroup's output absmax.  The epilogue stages 2048 NJ bytes per wave at the start
-    // of the slabs (8192 NJ bytes in the case of this one), so the end of the last slab is free by then; the
-    // kernel's LDS is exactly its slabs.
-    unsigned* s_amax = reinterpret_cast<unsigned*>(ldsB1 + kSlabB - 16);
-    int tr, tc;
-    if (!tile_of_block(blockIdx.x, tiles_r, tiles_c, band_rows, tr, tc)) return;   // uniform over the workgroup
-
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int wr = wave >> 1, wc = wave & 1;
-    auto stamp = [&](int slot) {
-        if constexpr (V::kProfile) {
-            if (threadIdx.x == 0) {
-                V::record(blockIdx.x, slot, (long long)__builtin_readcyclecounter());
-                V::record(blockIdx.x, slot + 8, (long long)__builtin_amdgcn_s_memrealtime());
-            }
-        }
-    };
-    stamp(0);
-    // requested now, needed in the epilogue; BF16 operands carry no scales
-    const float scale_a = FA == kFmtBf16 ? 1.0f : *d_sA, scale_b = FB == kFmtBf16 ? 1.0f : *d_sB;
-
-    // ---- global -> LDS: one instruction moves 8 rows x 128 B.  Wave w moves rows [16 NI w, 16 NI (w+1))
-    // of the A slab with 2 NI instructions and rows [16 NJ w, ...) of the B slab with 2 NJ.
-    // Instruction j covers rows 8 j + (lane >> 3) of the wave's share; the swizzle of those rows only
-    // depends on the parity of j (the share starts at a multiple of 16 rows).
-    const __amdgpu_buffer_rsrc_t rsA = make_rsrc(A + (size_t)tr * BM * T, (unsigned)((size_t)BM * T));
-    const __amdgpu_buffer_rsrc_t rsB = make_rsrc(B + (size_t)tc * BN * T, (unsigned)((size_t)BN * T));
-    constexpr int kSw = V::kSwizzleShift;
-    const int ld_row = lane >> 3;                                   // row inside the group of 8
-    const int ld_voff0 = ld_row * T + (((lane & 7) ^ ((ld_row >> kSw) & 7)) << 4);
-    const int ld_voff1 = ld_row * T + (((lane & 7) ^ (((8 + ld_row) >> kSw) & 7)) << 4);
-    const int ld_soffA = wave * 16 * NI * T, ld_soffB = wave * 16 * NJ * T;
-    auto issue_loads = [&](uint8_t* slabA, uint8_t* slabB, int k0) {
-        uint8_t* sa = slabA + wave * 16 * NI * BK;
-        uint8_t* sb = slabB + wave * 16 * NJ * BK;
-#pragma unroll
-        for (int j = 0; j < 2 * (NI > NJ ? NI : NJ); ++j) {
-            const int voff = (j & 1) ? ld_voff1 : ld_voff0;
-            if (j < 2 * NI)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_void*)(sa + j * 8 * BK), 16, voff, ld_soffA + k0 + j * 8 * T, 0, 0);
-            if (j < 2 * NJ)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_void*)(sb + j * 8 * BK), 16, voff, ld_soffB + k0 + j * 8 * T, 0, 0);
-        }
-    };
-    constexpr int kLoadsPerStep = 2 * (NI + NJ);
-    constexpr int kMfmaPerHalf = NI * NJ * (FA == kFmtBf16 ? 2 : 1);
-    constexpr int kDsSpread = NI * NJ >= 16 ? V::kDsSpread : V::kDsSpreadSmall;
-
-    // ---- LDS -> registers: lane reads 32 contiguous bytes (two swizzled 16-byte chunks) of its row
-    const int fr_row = lane & 31;
-    const int fr_half = lane >> 5;                                  // which 32 bytes of the 64-byte K half
-    const int swz = (fr_row >> kSw) & 7;                            // same for every row this lane reads
-    const int offA = (wr * 32 * NI + fr_row) * BK, offB = (wc * 32 * NJ + fr_row) * BK;
-    const int ch00 = ((fr_half * 2) ^ swz) << 4, ch01 = ((fr_half * 2 + 1) ^ swz) << 4;
-    const int ch10 = ((4 + fr_half * 2) ^ swz) << 4, ch11 = ((4 + fr_half * 2 + 1) ^ swz) << 4;
-    auto read_frags = [&](const uint8_t* slab, int off, int ks, auto& f) {
-        const int c0 = ks ? ch10 : ch00, c1 = ks ? ch11 : ch01;
-#pragma unroll
-        for (int i = 0; i < (int)(sizeof(f) / sizeof(f[0])); ++i) {
-            const uint8_t* p = slab + off + i * 32 * BK;
-            v4i lo = *reinterpret_cast<const v4i*>(p + c0);
-            v4i hi = *reinterpret_cast<const v4i*>(p + c1);
-            f[i] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        }
-    };
-
-    v16f acc[NI][NJ];
-#pragma unroll
-    for (int i = 0; i < NI; ++i)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-    v8i a0[NI], b0[NJ], a1[NI], b1[NJ];    // fragment sets of the two 64-byte halves of a K step
-    const int nk = T / BK;
-
-    // L2 touch loads: a wave reads the first dword of some rows of a slab that is still touch_ahead
-    // steps ahead of the direct-to-LDS loads (touch_ahead <= 0: nothing is fetched).  All CUs of an
-    // XCD walk K in lock-step, so without this every slab is first requested only ~1.5 steps before
-    // it is needed, less than a miss to HBM takes when the operands are not in the last-level cache.
-    // The workgroup touches rows [g * BM / shareA, (g + 1) * BM / shareA) of the A slab, g = tile
-    // column mod shareA, and likewise of the B slab with the tile row and shareB; each wave takes a quarter.
-    constexpr bool kTouch = V::kTouch;
-    constexpr int kShareA = V::kTouchShareA, kShareB = V::kTouchShareB;
-    constexpr int kOutOfRange = 0x7FFFFF00;
-    constexpr int kRowsA = BM / kShareA / 4, kRowsB = BN / kShareB / 4;     // rows per wave
-    const int touch_voffA = lane < kRowsA ? (((tc % kShareA) * 4 + wave) * kRowsA + lane) * T : kOutOfRange;
-    const int touch_voffB = lane < kRowsB ? (((tr % kShareB) * 4 + wave) * kRowsB + lane) * T : kOutOfRange;
-    int touchA[2] = {0, 0}, touchB[2] = {0, 0};   // results are only kept so that the loads stay tracked
-    int touch_sink = 0;
-
-    // One K step on the stage (curA, curB) while the other stage (nxtA, nxtB) is being filled:
-    //   first half : read the second-half fragments            | MFMAs on the first-half fragments
-    //   barrier    : the next slab has landed, everybody is done reading the current one
-    //   second half: start loading slab kt+2 into the current stage, read the first-half
-    //                fragments of slab kt+1                     | MFMAs on the second-half fragments
-    // Loads that would start beyond the last slab are pointed outside the buffer range instead:
-    // the hardware then fetches nothing (LDS receives zeros), and that stage is never used.
-    auto k_step = [&](uint8_t* curA, uint8_t* curB, uint8_t* nxtA, uint8_t* nxtB, int kt, int parity) {
-        read_frags(curA, offA, 1, a1);
-        read_frags(curB, offB, 1, b1);
-        mma_block<FA, FB, NI, NJ>(acc, a0, b0);
-        interleave<kMfmaPerHalf, kLoadsPerStep, 0, kDsSpread, V::kVmSpread, 0>();
-        // the direct-to-LDS loads of the previous step must have landed; its two touch loads, issued
-        // after them, may still be in flight
-        if constexpr (kTouch) wait_vmcnt<2>(); else wait_vmcnt<0>();
-        lds_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        issue_loads(curA, curB, kt + 2 < nk ? (kt + 2) * BK : kOutOfRange);
-        read_frags(nxtA, offA, 0, a0);          // past the last slab this reads bytes that are never used
-        read_frags(nxtB, offB, 0, b0);
-        mma_block<FA, FB, NI, NJ>(acc, a1, b1);
-        interleave<kMfmaPerHalf, kLoadsPerStep, kLoadsPerStep, kDsSpread, V::kVmSpread, 1>();
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (kTouch) {
-            const int kp = kt + 2 + touch_ahead;
-            const int off = (touch_ahead > 0 && kp < nk) ? kp * BK : kOutOfRange;
-            touch_sink ^= touchA[parity] ^ touchB[parity];          // issued two steps ago: long landed
-            touchA[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, off, 0);
-            touchB[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, off, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-
-    // both stages are requested at once; only the first has to have landed before the first fragments
-    issue_loads(ldsA0, ldsB0, 0);
-    issue_loads(ldsA1, ldsB1, nk > 1 ? BK : kOutOfRange);
-    if constexpr (kTouch) {                       // keep "two touch loads are the newest" true from the start
-        const int off = (touch_ahead > 0 && 2 < nk) ? 2 * BK : kOutOfRange;
-        touchA[1] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, off, 0);
-        touchB[1] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, off, 0);
-    }
-    wait_vmcnt<kLoadsPerStep + (kTouch ? 2 : 0)>();
-    lds_barrier();
-    read_frags(ldsA0, offA, 0, a0);
-    read_frags(ldsB0, offB, 0, b0);
-    stamp(1);
-    int kt = 0;
-    for (; kt + 1 < nk; kt += 2) {
-        k_step(ldsA0, ldsB0, ldsA1, ldsB1, kt, 0);
-        k_step(ldsA1, ldsB1, ldsA0, ldsB0, kt + 1, 1);
-    }
-    if (kt < nk) k_step(ldsA0, ldsB0, ldsA1, ldsB1, kt, 0);
-    // Every wave waits for its own direct-to-LDS loads (the out-of-range ones of the last two steps
-    // still write zeros into the slabs), then all meet: after this barrier nothing lands in LDS any
-    // more and nobody reads the slabs, so the epilogue may reuse them.
-    wait_vmcnt<0>();
-    lds_barrier();
-    if constexpr (kTouch) {
-        touch_sink ^= touchA[0] ^ touchB[0] ^ touchA[1] ^ touchB[1];
-        asm volatile("" ::"v"(touch_sink));
-    }
-    stamp(2);
-    // The workgroup that follows on this XCD (id + next_stride: same XCD, and dispatched about when this
-    // one retires) starts with two slabs of its own operands; one dword per 128-byte line of them is
-    // requested here, so that they reach the L2 while this workgroup is busy with its epilogue.
-    int next_touch[4] = {0, 0, 0, 0};
-    if constexpr (kTouch) {
-        int ntr, ntc;
-        if (next_stride > 0 && T >= 2 * BK && tile_of_block(blockIdx.x + next_stride, tiles_r, tiles_c, band_rows, ntr, ntc)) {
-            const uint8_t* na = A + ((size_t)ntr * BM + wave * (BM / 4) + lane) * T;
-            const uint8_t* nb = B + ((size_t)ntc * BN + wave * (BN / 4) + lane) * T;
-            if (lane < BM / 4) {
-                next_touch[0] = *reinterpret_cast<const int*>(na);
-                next_touch[1] = *reinterpret_cast<const int*>(na + BK);
-            }
-            if (lane < BN / 4) {
-                next_touch[2] = *reinterpret_cast<const int*>(nb);
-                next_touch[3] = *reinterpret_cast<const int*>(nb + BK);
-            }
-        }
-    }
-
-    // ---- epilogue.  Per 32x32 block a lane holds 4 groups of 4 consecutive columns of row (lane % 32).
-    // Storing those 8-byte pieces directly scatters every store over 32 rows; instead each wave
-    // stages one 32-row block of its quadrant at a time (32 rows x 32 NJ BF16 columns) at the start of one
-    // of the four slabs, which nobody reads any more, and writes it out as full row segments, 16 bytes per lane.  The
-    // 16-byte slot index of a staged row is rotated by the row number, so that the 8-byte writes of
-    // 32 rows and the 16-byte reads spread over the banks.  The region is private to the wave and LDS
-    // executes a wave's accesses in order, so no further barrier is needed.
-    // De-scale with one multiply by 1 / (sA sB) unless that product leaves the normal range (degenerate
-    // scales such as FLT_MAX for an all-zero tensor), in which case the two factors are applied in turn
-    // (a second copy of the epilogue, so that the usual path carries no trace of it).
-    const float inv_a = 1.0f / scale_a, inv_b = 1.0f / scale_b;
-    const float inv_ab = inv_a * inv_b;
-    const bool one_mul = inv_ab >= 1.17549435e-38f && inv_ab <= 3.402823466e+38f;
-    const float m1 = one_mul ? inv_ab : inv_a;
-    // The output absmax is taken in fp32 before rounding: rounding to BF16 is monotonic, so the BF16
-    // rounding of the largest |y| is the largest rounded magnitude.
-    float maxabs = 0.0f;
-    auto track4 = [&](const v4f& y) {
-        maxabs = __builtin_fmaxf(__builtin_fmaxf(maxabs, __builtin_fabsf(y[0])), __builtin_fabsf(y[1]));
-        maxabs = __builtin_fmaxf(__builtin_fmaxf(maxabs, __builtin_fabsf(y[2])), __builtin_fabsf(y[3]));
-    };
-    // The body exists twice, for one and for two de-scale multiplies; the choice is uniform over the grid.
-    auto write_out = [&](auto two_mul) {
-    auto descale4 = [&](const v16f& block, int g) -> v4f {
-        v4f y;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            y[e] = block[4 * g + e] * m1;
-            if constexpr (decltype(two_mul)::value) y[e] *= inv_b;
-        }
-        return y;
-    };
-    if constexpr (!ACCUM) {
-        constexpr int kSlots = 4 * NJ;                                       // 16-byte slots per staged row
-        constexpr int kPitch = 16 * kSlots;
-        constexpr bool kPow2 = (kSlots & (kSlots - 1)) == 0;
-        uint8_t* stage = wave == 0 ? ldsA0 : wave == 1 ? ldsB0 : wave == 2 ? ldsA1 : ldsB1;
-        // byte offset inside a staged row of the 8 bytes this lane writes for column group c8 = col / 8;
-        // with a power-of-two slot count it does not depend on the row block (32 rows apart)
-        int slot_off[kSlots];
-        if constexpr (kPow2) {
-#pragma unroll
-            for (int c8 = 0; c8 < kSlots; ++c8) slot_off[c8] = (((c8 + fr_row) & (kSlots - 1)) << 4) | (fr_half << 3);
-        }
-        uint16_t* cbase = C + (size_t)(tr * BM + wr * 32 * NI) * Cn + tc * BN + wc * 32 * NJ;
-        constexpr int kBlockPieces = 32 * kSlots;                            // 16-byte pieces of one block of 32 rows
-        // one block of 32 rows at a time: while its stores are in flight the next block is converted
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            if constexpr (V::kEpilogueFence) __builtin_amdgcn_sched_barrier(0);
-            const int row = fr_row;             // the 32 staged rows are reused by every block: LDS runs a wave's accesses in order
-            uint8_t* srow = stage + row * kPitch;
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const v4f y = descale4(acc[i][j], g);
-                    track4(y);
-                    bf16x4 o = __builtin_convertvector(y, bf16x4);
-                    const int c8 = j * 4 + g;                                // columns 8 c8 + 4 fr_half + 0..3
-                    const int off = kPow2 ? slot_off[c8] : ((((c8 + row) % kSlots) << 4) | (fr_half << 3));
-                    *reinterpret_cast<bf16x4*>(srow + off) = o;
-                }
-            }
-            // all pieces of the block are read back before the first is stored, so that the LDS round
-            // trips overlap instead of each store waiting for its own read
-            constexpr int kPiecesPerLane = kBlockPieces / kWave;
-            v4u piece[kPiecesPerLane];
-#pragma unroll
-            for (int k = 0; k < kPiecesPerLane; ++k) {
-                const int p = lane + k * kWave;
-                const int r = p / kSlots, sl = p % kSlots;
-                piece[k] = *reinterpret_cast<const v4u*>(stage + r * kPitch + (((sl + r) % kSlots) << 4));
-            }
-            if constexpr (V::kEpilogueFence) __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int k = 0; k < kPiecesPerLane; ++k) {
-                const int p = lane + k * kWave;
-                const int r = i * 32 + p / kSlots, sl = p % kSlots;      // row inside the wave's quadrant
-                if constexpr (V::kNtStoreC) __builtin_nontemporal_store(piece[k], reinterpret_cast<v4u*>(cbase + (size_t)r * Cn + sl * 8));
-                else *reinterpret_cast<v4u*>(cbase + (size_t)r * Cn + sl * 8) = piece[k];
-            }
-        }
-        if constexpr (V::kProfile) stamp(4);
-    } else {
-        // BF16 accumulation needs the old value before the single rounding: straight from the registers.
-        const int row_base = tr * BM + wr * 32 * NI + fr_row;
-        const int col_base = tc * BN + wc * 32 * NJ + fr_half * 4;
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            uint16_t* crow = C + (size_t)(row_base + i * 32) * Cn + col_base;
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    uint16_t* dst = crow + j * 32 + g * 8;
-                    v4f y = descale4(acc[i][j], g);
-                    v2u old = *reinterpret_cast<const v2u*>(dst);
-                    y[0] += __uint_as_float(old[0] << 16);
-                    y[1] += __uint_as_float(old[0] & 0xFFFF0000u);
-                    y[2] += __uint_as_float(old[1] << 16);
-                    y[3] += __uint_as_float(old[1] & 0xFFFF0000u);
-                    track4(y);
-                    *reinterpret_cast<bf16x4*>(dst) = __builtin_convertvector(y, bf16x4);
-                }
-            }
-        }
-    }
-    };
-    if (one_mul) write_out(BoolTag<false>{}); else write_out(BoolTag<true>{});
-    if constexpr (kTouch) asm volatile("" ::"v"(next_touch[0] ^ next_touch[1] ^ next_touch[2] ^ next_touch[3]));
-    unsigned mag = (unsigned)__builtin_bit_cast(uint16_t, (__bf16)maxabs);   // non-negative: magnitude bits
-    if (amax_bits) {
-        mag = wave_max_u32(mag);
-        if (lane == 0) s_amax[wave] = mag;
-        __syncthreads();
-        if (threadIdx.x == 0) {
-#pragma unroll
-            for (int w = 1; w < kGemmThreads / kWave; ++w) mag = mag > s_amax[w] ? mag : s_amax[w];
-            // same-address atomics of many workgroups serialise; a stale read never exceeds the true maximum
-            const unsigned bits = amax_bits_from_bf16_mag(mag);
-            if (bits > __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(amax_bits, bits);
-        }
-    }
-    if constexpr (V::kProfile) {
-        stamp(5);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        stamp(3);
-    }
-}
-
-// ---- generic kernel: one wavefront per 16x16 outputs, v_mfma_f32_16x16x128_f8f6f4, guarded loads
+// ---- generic kernel: one wavefront per 16x16 outputs, v_mfma_f32_16x16x128_f8f6f4, guarded loads.
+// ta / tb: the operand is T-major ([T, R] or [T, Cn]); its bytes are then gathered one by one.
 template <int FA, int FB>
-__global__ __launch_bounds__(256) void gemm_tn_generic_kernel(
+__global__ __launch_bounds__(256) void gemm_generic_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ C,
     int64_t R, int64_t Cn, int64_t T, const float* __restrict__ d_sA, const float* __restrict__ d_sB,
-    int accumulate, unsigned* __restrict__ amax_bits) {
+    int accumulate, unsigned* __restrict__ amax_bits, int ta, int tb) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int64_t r0 = ((int64_t)blockIdx.y * 2 + (wave >> 1)) * 16;
@@ -481,9 +22,20 @@ __global__ __launch_bounds__(256) void gemm_tn_generic_kernel(
     const int64_t ar = r0 + (lane & 15), bc = c0 + (lane & 15);
     const bool a_ok = ar < R, b_ok = bc < Cn;
     const bool vec_ok = (T % 16) == 0;
-    auto load32 = [&](const uint8_t* base, bool ok, int64_t row, int64_t k) -> v8i {
+    auto load32 = [&](const uint8_t* base, bool ok, int64_t row, int64_t k, int tmajor, int64_t ld) -> v8i {
         v8i v = {0, 0, 0, 0, 0, 0, 0, 0};
         if (!ok || k >= T) return v;
+        if (tmajor) {
+            for (int w = 0; w < 8; ++w) {
+                unsigned word = 0;
+                for (int e = 0; e < 4; ++e) {
+                    int64_t kk = k + w * 4 + e;
+                    if (kk < T) word |= (unsigned)base[kk * ld + row] << (8 * e);
+                }
+                v[w] = (int)word;
+            }
+            return v;
+        }
         const uint8_t* p = base + row * T + k;
         if (vec_ok && k + 32 <= T) {
             v4i lo = *reinterpret_cast<const v4i*>(p), hi = *reinterpret_cast<const v4i*>(p + 16);
@@ -502,8 +54,8 @@ __global__ __launch_bounds__(256) void gemm_tn_generic_kernel(
     v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
     for (int64_t k0 = 0; k0 < T; k0 += 128) {
         const int64_t k = k0 + (lane >> 4) * 32;
-        v8i a = load32(A, a_ok, ar, k);
-        v8i b = load32(B, b_ok, bc, k);
+        v8i a = load32(A, a_ok, ar, k, ta, R);
+        v8i b = load32(B, b_ok, bc, k, tb, Cn);
         acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b, a, acc, FB, FA, 0, 0, 0, 0);
     }
     // lane holds row r0 + lane % 16, columns c0 + 4 * (lane / 16) + 0..3
@@ -550,15 +102,12 @@ __global__ void gemm_amax_reset_kernel(unsigned* amax_bits) {
 }
 
 // ---- host side: tile choice and launch
-struct TileChoice {
-    int ni, nj;       // 0, 0: no tuned tile divides the problem, use the generic kernel
-};
 
 // Picks the wave tile NI x NJ (workgroup tile 64 NI x 64 NJ) that finishes soonest under a simple
 // model: every CU works through its share of the tiles, a tile costs NI * NJ MFMA blocks per K step
 // divided by the measured efficiency of that shape relative to 4 x 4 (smaller tiles read more LDS
 // and L2 bytes per MFMA; 2 x 2 tiles fit two workgroups per CU, which hide each other's stalls).
-static TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus) {
+TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus) {
     static const float eff[5][5] = {{0, 0, 0, 0, 0}, {0, 0, 0, 0, 0}, {0, 0, 0.90f, 0.74f, 0.77f},
                                     {0, 0, 0.74f, 0.70f, 0.83f}, {0, 0, 0.77f, 0.83f, 1.00f}};
     TileChoice best{0, 0};
@@ -586,70 +135,11 @@ static TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus) {
     return best;
 }
 
-// Distance of the L2 touch loads in K steps; LLMQ_GEMM_TOUCH overrides it for tuning.
-static int touch_ahead() {
-    if (const char* e = getenv("LLMQ_GEMM_TOUCH")) return atoi(e);
-    return 2;
-}
-
-// Height of the bands of tiles, in tile rows; LLMQ_GEMM_BAND overrides it for tuning.
-static int band_rows() {
-    if (const char* e = getenv("LLMQ_GEMM_BAND")) { const int v = atoi(e); if (v >= 1 && v <= 64) return v; }
-    return kBandRows;
-}
-
-// The same for 2 x 2 tiles, where two workgroups share a CU and already cover each other's waits.
-static int touch_ahead_pair() {
-    if (const char* e = getenv("LLMQ_GEMM_TOUCH_PAIR")) return atoi(e);
-    return 0;
-}
-
-// Whether a workgroup requests the first slabs of its successor; LLMQ_GEMM_TOUCH_NEXT=0 / 1 overrides it.
-static bool touch_next(bool by_default) {
-    if (const char* e = getenv("LLMQ_GEMM_TOUCH_NEXT")) return atoi(e) != 0;
-    return by_default;
-}
-
-template <int FA, int FB, int NI, int NJ>
-static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
-                        const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
-                        hipStream_t stream, int num_cus) {
-    const int tiles_r = (int)(R / (64 * NI)), tiles_c = (int)(C / (64 * NJ));
-    const int nt = tiles_r * tiles_c;
-    const int grid = ((nt + kXcds - 1) / kXcds) * kXcds;
-    const int touch = (NI == 2 && NJ == 2) ? touch_ahead_pair() : touch_ahead();
-    // workgroups resident on the chip at once (a multiple of the XCD count): the distance to the
-    // workgroup that takes over a slot
-    // (measured: +3 % on a GEMM of 19 rounds of tiles, whose later workgroups otherwise start on cold
-    // operands; nothing or slightly less on GEMMs of 2-4 rounds, so it is used from 6 rounds on)
-    const int slots = (num_cus / kXcds) * kXcds * ((NI == 2 && NJ == 2) ? 2 : 1);
-    const int next_stride = touch_next(nt >= 6 * slots) ? slots : 0;
-    if (accumulate)
-        hipLaunchKernelGGL((gemm_tn_tile_kernel<FA, FB, NI, NJ, true>), dim3(grid), dim3(kGemmThreads), 0, stream,
-                           A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c,
-                           touch, band_rows(), next_stride);
-    else
-        hipLaunchKernelGGL((gemm_tn_tile_kernel<FA, FB, NI, NJ, false>), dim3(grid), dim3(kGemmThreads), 0, stream,
-                           A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c,
-                           touch, band_rows(), next_stride);
-}
-
 template <int FA, int FB>
 static void launch_one(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
                        const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
                        hipStream_t stream, int num_cus) {
-    const TileChoice tc = choose_tile(R, C, T, num_cus);
-#define LLMQ_TILE_CASE(I, J)                                                                      \
-    case I * 8 + J:                                                                               \
-        launch_tile<FA, FB, I, J>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus);   \
-        return;
-    switch (tc.ni * 8 + tc.nj) {
-        LLMQ_TILE_CASE(4, 4) LLMQ_TILE_CASE(4, 3) LLMQ_TILE_CASE(4, 2)
-        LLMQ_TILE_CASE(3, 4) LLMQ_TILE_CASE(3, 3) LLMQ_TILE_CASE(3, 2)
-        LLMQ_TILE_CASE(2, 4) LLMQ_TILE_CASE(2, 3) LLMQ_TILE_CASE(2, 2)
-        default: break;
-    }
-#undef LLMQ_TILE_CASE
+    if (launch_chosen_tile<FA, FB, false, false>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus)) return;
     if constexpr (FA == kFmtBf16) {
         const int64_t n = R * C;
         int64_t blocks = (n + 255) / 256;
@@ -658,10 +148,23 @@ static void launch_one(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C,
                            reinterpret_cast<const uint16_t*>(A), reinterpret_cast<const uint16_t*>(B),
                            reinterpret_cast<uint16_t*>(c), R, C, T / 2, accumulate);
     } else {
-        dim3 grid((unsigned)((C + 31) / 32), (unsigned)((R + 31) / 32));
-        hipLaunchKernelGGL((gemm_tn_generic_kernel<FA, FB>), grid, dim3(256), 0, stream,
-                           A, B, reinterpret_cast<uint16_t*>(c), R, C, T, sA, sB, accumulate, amax);
+        launch_gemm_generic(A, FA, false, B, FB, false, R, C, T, sA, sB, c, accumulate, amax, stream);
     }
+}
+
+void launch_gemm_generic(const uint8_t* A, int fmtA, bool ta, const uint8_t* B, int fmtB, bool tb, int64_t R, int64_t C,
+                         int64_t T, const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
+                         hipStream_t stream) {
+    dim3 grid((unsigned)((C + 31) / 32), (unsigned)((R + 31) / 32));
+    uint16_t* out = reinterpret_cast<uint16_t*>(c);
+    if (fmtA == 0 && fmtB == 0) hipLaunchKernelGGL((gemm_generic_kernel<0, 0>), grid, dim3(256), 0, stream, A, B, out, R, C, T, sA, sB, accumulate, amax, (int)ta, (int)tb);
+    else if (fmtA == 1 && fmtB == 0) hipLaunchKernelGGL((gemm_generic_kernel<1, 0>), grid, dim3(256), 0, stream, A, B, out, R, C, T, sA, sB, accumulate, amax, (int)ta, (int)tb);
+    else if (fmtA == 0 && fmtB == 1) hipLaunchKernelGGL((gemm_generic_kernel<0, 1>), grid, dim3(256), 0, stream, A, B, out, R, C, T, sA, sB, accumulate, amax, (int)ta, (int)tb);
+    else hipLaunchKernelGGL((gemm_generic_kernel<1, 1>), grid, dim3(256), 0, stream, A, B, out, R, C, T, sA, sB, accumulate, amax, (int)ta, (int)tb);
+}
+
+void launch_gemm_amax_reset(unsigned* amax, hipStream_t stream) {
+    hipLaunchKernelGGL(gemm_amax_reset_kernel, dim3(1), dim3(64), 0, stream, amax);
 }
 
 int launch_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64_t R, int64_t C,

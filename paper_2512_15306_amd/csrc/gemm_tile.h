@@ -1,0 +1,647 @@
+// Tile kernel of the FP8 contraction on the gfx950 matrix cores (paper Section 3: the transformer-block matmuls of
+// forward and backward run in FP8, results stay in BF16; the FP8 GEMM is "TN", i.e. both operands
+// have the contraction index contiguous).
+//
+//   C[r,c] = bf16( (sum_t A[r,t] * B[c,t]) / (sA * sB) ),   A [R,T] fp8, B [Cn,T] fp8.
+//
+// Tuned kernel (template on the wave tile NI x NJ in units of 32: workgroup tile BM x BN with
+// BM = 64 NI, BN = 64 NJ, both in {128, 192, 256}; R % BM == 0, Cn % BN == 0, T % 128 == 0)
+//   - one workgroup of 4 wavefronts (2 x 2) per output tile, one workgroup per CU; a wavefront owns
+//     NI x NJ blocks of v_mfma_f32_32x32x64_f8f6f4 with fp32 accumulators (256 registers per lane
+//     at 4 x 4);
+//   - K advances 128 bytes per step; the A and B slabs (BM / BN rows x 128 B) go from global memory
+//     straight into LDS with buffer_load ... lds (16 bytes per lane, no VGPR staging), double buffered;
+//   - LDS rows are 128 B; the 16-byte chunk index is XOR-ed with (row >> 1) & 7, applied on the
+//     global side of the load, so that ds_read_b128 fragment reads of 16 consecutive rows spread
+//     over all 64 banks;
+//   - the order of the contraction index inside one MFMA does not matter as long as A and B use
+//     the same order, so every lane simply reads 32 contiguous bytes of its row;
+//   - every step is software pipelined in two halves: the MFMAs of one 64-byte half run while the
+//     fragments of the next half are read and the slab after next is requested; one barrier per step;
+//   - the MFMA takes the B rows as its first operand, which leaves every lane with 4 consecutive
+//     output columns of one row; the epilogue de-scales in fp32, rounds to BF16 with the hardware
+//     conversion, takes the output absmax on the rounded bits, stages the wave's quadrant in LDS
+//     and stores full row segments, 16 bytes per lane;
+//   - workgroup ids are dealt round-robin to the 8 XCDs by the hardware, so ids are remapped to give
+//     each XCD (own L2) a contiguous range of tiles, walked in bands 8 tile-rows high;
+//   - the host picks NI x NJ per problem so that the tiles fill the 256 CUs in whole rounds.
+// Generic kernel: any shape, one wavefront per 16x16 outputs, guarded loads; slow, for tests and
+// odd sizes.
+//
+// An operand may also be given "T-major", [T, rows] with the contraction index running down the rows (the
+// untransposed quantized tensor where the backward pass contracts over what is the row index of the
+// forward pass): see SlabShape below.  This header holds the kernel and its launcher; the translation
+// units that include it instantiate the operand layouts they serve.
+#pragma once
+#include <stdlib.h>
+
+#include "llmq_device.h"
+#include "llmq_kernels.h"
+
+namespace llmq {
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(3))) v2i lds_v2i;
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+constexpr int BK = 128;
+constexpr int kGemmThreads = 256;
+constexpr int kXcds = 8;
+constexpr int kBandRows = 8;
+
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+    // raw buffer, no stride; out-of-range reads return zero instead of faulting
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+// Linear workgroup id -> output tile, XCD-aware.  Returns false for the padding ids.
+__device__ inline bool tile_of_block(int pid, int tiles_r, int tiles_c, int band_rows, int& tr, int& tc) {
+    const int nt = tiles_r * tiles_c;
+    const int per_xcd = (nt + kXcds - 1) / kXcds;
+    const int id = (pid % kXcds) * per_xcd + pid / kXcds;
+    if (id >= nt) return false;
+    const int band = band_rows * tiles_c;
+    const int first = (id / band) * band_rows;
+    const int h = tiles_r - first < band_rows ? tiles_r - first : band_rows;
+    const int in_band = id % band;
+    tr = first + in_band % h;
+    tc = in_band / h;
+    return true;
+}
+
+// MFMA scheduling masks of __builtin_amdgcn_sched_group_barrier
+constexpr int kSchedMfma = 0x008, kSchedVmemRead = 0x020, kSchedDsRead = 0x100;
+
+// Tuning knobs of the tuned kernel.
+struct GemmTuning {
+    // Whether the kernel contains the L2 touch loads at all (their distance is a run-time argument).
+    static constexpr bool kTouch = true;
+    // One workgroup touches 1 / kTouchShareA of the lines of its A slab and 1 / kTouchShareB of its B
+    // slab: the workgroups that run side by side on an XCD (4 tile columns x 8 tile rows at a time)
+    // share each slab and cover it together.
+    static constexpr int kTouchShareA = 4, kTouchShareB = 8;
+    // Fragment reads ride along with the first 1 / kDsSpread of a half step's MFMAs (4 x 4 tiles) or
+    // 1 / kDsSpreadSmall (smaller tiles: fewer MFMAs per read, and three reads per MFMA slot from four waves
+    // are more than the LDS delivers; measured +1-4 % on 4 x 3, while 4 x 4 loses 1-4 % on whole rounds with
+    // the reads spread over the whole half), the direct-to-LDS loads with the first 1 / kVmSpread.
+    static constexpr int kDsSpread = 2, kDsSpreadSmall = 1, kVmSpread = 1;
+    static constexpr bool kNtStoreC = false;     // streaming hint on the output stores
+    // Scheduling fences between the 32-row blocks of the epilogue: without them the compiler hoists every
+    // de-scale multiply to the front and parks the products in accumulator registers.
+    static constexpr bool kEpilogueFence = true;
+    // Development aid: a tuning struct with kProfile = true also provides
+    //   static __device__ void record(int block, int slot, long long value)
+    // and gets cycle stamps of the phases of wave 0 of every workgroup.
+    static constexpr bool kProfile = false;
+    // LDS swizzle of the operand slabs: the 16-byte chunk index of a row is XOR-ed with
+    // (row >> kSwizzleShift) & 7.
+    static constexpr int kSwizzleShift = 1;
+};
+
+template <bool B>
+struct BoolTag { static constexpr bool value = B; };
+
+template <int N>
+__device__ inline void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Workgroup barrier that orders LDS traffic only: the caller has already waited for the
+// direct-to-LDS loads it needs with wait_vmcnt<>, other global loads may stay in flight.
+__device__ inline void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Operand kinds of the tuned kernel: 0 = E4M3, 1 = E5M2 (one byte per element, any mix), 2 = BF16 (both
+// operands; the baseline the FP8 path is compared with).  The kernel itself moves bytes: T is the length of
+// a row in bytes, and a lane's 32-byte fragment holds 32 FP8 or 16 BF16 contraction elements.
+constexpr int kFmtBf16 = 2;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <int FA, int FB, int NI, int NJ>
+__device__ inline void mma_block(v16f (&acc)[NI][NJ], const v8i (&a)[NI], const v8i (&b)[NJ]) {
+    static_assert((FA == kFmtBf16) == (FB == kFmtBf16), "BF16 operands come in pairs");
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            if constexpr (FA == kFmtBf16) {
+                // two v_mfma_f32_32x32x16_bf16, one per 16-byte half of the fragments
+                const v4i a_lo = {a[i][0], a[i][1], a[i][2], a[i][3]}, a_hi = {a[i][4], a[i][5], a[i][6], a[i][7]};
+                const v4i b_lo = {b[j][0], b[j][1], b[j][2], b[j][3]}, b_hi = {b[j][4], b[j][5], b[j][6], b[j][7]};
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b_lo), __builtin_bit_cast(bf16x8, a_lo), acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b_hi), __builtin_bit_cast(bf16x8, a_hi), acc[i][j], 0, 0, 0);
+            } else {
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[i][j], FB, FA, 0, 0, 0, 0);
+            }
+        }
+}
+
+// Interleave NM MFMAs with ND LDS reads, spread over the first NM / DS_SPREAD MFMAs (so that they have
+// landed when the MFMAs end), and NV global loads, spread over the first NM / VM_SPREAD.
+template <int NM, int ND, int NV, int DS_SPREAD, int VM_SPREAD, int SYNC, int M = 0>
+__device__ inline void interleave() {
+    if constexpr (M < NM) {
+        constexpr int kDsSpan = (NM + DS_SPREAD - 1) / DS_SPREAD, kVmSpan = (NM + VM_SPREAD - 1) / VM_SPREAD;
+        constexpr int kDsPer = (ND + kDsSpan - 1) / kDsSpan;
+        constexpr int kVmPer = (NV + kVmSpan - 1) / kVmSpan;
+        constexpr int kDsLeft = ND - M * kDsPer, kVmLeft = NV - M * kVmPer;
+        __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, SYNC);
+        if constexpr (kDsLeft > 0) __builtin_amdgcn_sched_group_barrier(kSchedDsRead, kDsLeft < kDsPer ? kDsLeft : kDsPer, SYNC);
+        if constexpr (kVmLeft > 0) __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, kVmLeft < kVmPer ? kVmLeft : kVmPer, SYNC);
+        interleave<NM, ND, NV, DS_SPREAD, VM_SPREAD, SYNC, M + 1>();
+    }
+}
+
+// How one operand slab sits in memory and in LDS, and how its MFMA fragments are read.
+//   TMAJOR = false: the operand is [rows, T], a slab is 64 NX rows of 128 B; LDS keeps the rows, 128 B
+//     each, the 16-byte chunk index XOR-ed with (row >> kSwizzleShift) & 7; a lane reads the 32 contiguous
+//     bytes of its row with two ds_read_b128.
+//   TMAJOR = true: the operand is [T, rows] (the contraction index runs down the rows, `ld` bytes apart),
+//     a slab is 128 rows of 64 NX bytes and LDS keeps it that way.  A lane's 32 contraction bytes then sit
+//     in 32 different LDS rows; four ds_read_b64_tr_b8 fetch them: within 16 lanes, lane s points at 8
+//     bytes of row k0 + s / 2 (the two lanes of a pair at the two halves of 16 consecutive bytes), and the
+//     hardware hands lane i the byte of column i of each of the eight rows, in row order.  So lane i holds
+//     contraction bytes k0 .. k0 + 7 of operand row r0 + i, the same order as in the other layout, and the
+//     two layouts mix freely in one MFMA.  The 16-byte unit index of LDS row k is XOR-ed with k & 7 (with
+//     (k >> 2) & 1 for 192-byte rows, which have no room for three bits), again on the global side of the
+//     load: the eight rows one transposing read touches then lie in eight different groups of four banks.
+template <int NX, bool TMAJOR>
+struct SlabShape {
+    static constexpr int kRows = 64 * NX;                     // operand rows (output rows or columns) of the tile
+    static constexpr int kUnits = kRows / 16;                 // T-major: 16-byte units per LDS row
+    static constexpr int kPeriod = NX == 4 ? 2 : NX == 2 ? 1 : 3;       // T-major: load instructions per pattern
+    static constexpr int kPeriodRows = 64 * kPeriod / kUnits;           // T-major: slab rows per pattern
+    static constexpr int kReadsPerFrag = TMAJOR ? 4 : 2;
+    static constexpr int kLines = TMAJOR ? (kRows + 127) / 128 : 1;     // 128-byte lines per memory row of a slab
+    __device__ static int swizzle_of_row(int k) { return NX == 3 ? (k >> 2) & 1 : k & 7; }
+};
+
+template <int FA, int FB, int NI, int NJ, bool ACCUM, class V = GemmTuning, bool TA = false, bool TB = false>
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
+    const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ C,
+    int Cn, int T, const float* __restrict__ d_sA, const float* __restrict__ d_sB,
+    unsigned* __restrict__ amax_bits, int tiles_r, int tiles_c, int touch_ahead, int band_rows, int next_stride,
+    int ldA, int ldB) {
+    static_assert(!(TA || TB) || (FA != kFmtBf16 && FB != kFmtBf16), "the transposing reads move single bytes");
+    constexpr int BM = 64 * NI, BN = 64 * NJ;
+    typedef SlabShape<NI, TA> SA;
+    typedef SlabShape<NJ, TB> SB;
+    constexpr int kOutOfRange = 0x7FFFFF00;     // a buffer offset beyond every operand: such loads fetch nothing
+    constexpr int kSlabA = BM * BK, kSlabB = BN * BK;
+    // One array per stage and operand: distinct LDS objects let the compiler see that the
+    // direct-to-LDS loads of one stage do not alias the fragment reads of the other, so it does
+    // not make the reads wait for the loads in flight.
+    __shared__ __attribute__((aligned(1024))) uint8_t ldsA0[kSlabA];
+    __shared__ __attribute__((aligned(1024))) uint8_t ldsB0[kSlabB];
+    __shared__ __attribute__((aligned(1024))) uint8_t ldsA1[kSlabA];
+    __shared__ __attribute__((aligned(1024))) uint8_t ldsB1[kSlabB];
+    // Four words for the workgroup's output absmax.  The epilogue stages 2048 NJ bytes per wave at the start
+    // of the slabs (8192 NJ bytes in the case of this one), so the end of the last slab is free by then; the
+    // kernel's LDS is exactly its slabs.
+    unsigned* s_amax = reinterpret_cast<unsigned*>(ldsB1 + kSlabB - 16);
+    int tr, tc;
+    if (!tile_of_block(blockIdx.x, tiles_r, tiles_c, band_rows, tr, tc)) return;   // uniform over the workgroup
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int wr = wave >> 1, wc = wave & 1;
+    auto stamp = [&](int slot) {
+        if constexpr (V::kProfile) {
+            if (threadIdx.x == 0) {
+                V::record(blockIdx.x, slot, (long long)__builtin_readcyclecounter());
+                V::record(blockIdx.x, slot + 8, (long long)__builtin_amdgcn_s_memrealtime());
+            }
+        }
+    };
+    stamp(0);
+    // requested now, needed in the epilogue; BF16 operands carry no scales
+    const float scale_a = FA == kFmtBf16 ? 1.0f : *d_sA, scale_b = FB == kFmtBf16 ? 1.0f : *d_sB;
+
+    // ---- global -> LDS.  Row-wise operand: one instruction moves 8 rows x 128 B; wave w moves rows
+    // [16 NX w, 16 NX (w+1)) of the slab with 2 NX instructions; instruction j covers rows 8 j + (lane >> 3)
+    // of the wave's share, and the swizzle of those rows only depends on the parity of j (the share starts
+    // at a multiple of 16 rows).  T-major operand: an instruction moves 1 KB = 64 units of consecutive LDS
+    // rows (64 NX bytes each); wave w moves slab rows [32 w, 32 w + 32), again 2 NX instructions, whose
+    // lane pattern repeats every kPeriod instructions (kPeriodRows slab rows).
+    const __amdgpu_buffer_rsrc_t rsA = TA ? make_rsrc(A + (size_t)tr * BM, (unsigned)((size_t)T * ldA - (size_t)tr * BM))
+                                          : make_rsrc(A + (size_t)tr * BM * T, (unsigned)((size_t)BM * T));
+    const __amdgpu_buffer_rsrc_t rsB = TB ? make_rsrc(B + (size_t)tc * BN, (unsigned)((size_t)T * ldB - (size_t)tc * BN))
+                                          : make_rsrc(B + (size_t)tc * BN * T, (unsigned)((size_t)BN * T));
+    constexpr int kSw = V::kSwizzleShift;
+    const int ld_row = lane >> 3;                                   // row inside the group of 8
+    const int ld_voff0 = ld_row * T + (((lane & 7) ^ ((ld_row >> kSw) & 7)) << 4);
+    const int ld_voff1 = ld_row * T + (((lane & 7) ^ (((8 + ld_row) >> kSw) & 7)) << 4);
+    auto tmajor_voff = [&](auto shape, int m, int ld) {             // pattern m of a T-major operand
+        typedef decltype(shape) S;
+        const int unit = 64 * m + lane, row = unit / S::kUnits, col = unit % S::kUnits;
+        return row * ld + ((col ^ S::swizzle_of_row(row)) << 4);
+    };
+    int ld_voffA[3], ld_voffB[3];
+#pragma unroll
+    for (int m = 0; m < 3; ++m) {
+        ld_voffA[m] = TA ? (m < SA::kPeriod ? tmajor_voff(SA{}, m, ldA) : 0) : (m & 1) ? ld_voff1 : ld_voff0;
+        ld_voffB[m] = TB ? (m < SB::kPeriod ? tmajor_voff(SB{}, m, ldB) : 0) : (m & 1) ? ld_voff1 : ld_voff0;
+    }
+    const int ld_soffA = TA ? wave * 32 * ldA : wave * 16 * NI * T, ld_soffB = TB ? wave * 32 * ldB : wave * 16 * NJ * T;
+    // k0: first contraction index of the slab, or a negative value for "no slab" (nothing is fetched)
+    auto issue_loads = [&](uint8_t* slabA, uint8_t* slabB, int k0) {
+        uint8_t* sa = slabA + wave * 16 * NI * BK;
+        uint8_t* sb = slabB + wave * 16 * NJ * BK;
+        const int baseA = k0 < 0 ? kOutOfRange : ld_soffA + (TA ? k0 * ldA : k0);
+        const int baseB = k0 < 0 ? kOutOfRange : ld_soffB + (TB ? k0 * ldB : k0);
+#pragma unroll
+        for (int j = 0; j < 2 * (NI > NJ ? NI : NJ); ++j) {
+            if (j < 2 * NI) {
+                const int voff = TA ? ld_voffA[j % SA::kPeriod] : ld_voffA[j & 1];
+                const int soff = TA ? (j / SA::kPeriod) * SA::kPeriodRows * ldA : j * 8 * T;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_void*)(sa + j * 8 * BK), 16, voff, baseA + soff, 0, 0);
+            }
+            if (j < 2 * NJ) {
+                const int voff = TB ? ld_voffB[j % SB::kPeriod] : ld_voffB[j & 1];
+                const int soff = TB ? (j / SB::kPeriod) * SB::kPeriodRows * ldB : j * 8 * T;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_void*)(sb + j * 8 * BK), 16, voff, baseB + soff, 0, 0);
+            }
+        }
+    };
+    constexpr int kLoadsPerStep = 2 * (NI + NJ);
+    constexpr int kReadsPerHalf = SA::kReadsPerFrag * NI + SB::kReadsPerFrag * NJ;      // LDS reads of one fragment set
+    constexpr int kMfmaPerHalf = NI * NJ * (FA == kFmtBf16 ? 2 : 1);
+    // T-major operands take twice as many (half as wide) LDS reads: spread over the whole half step they cost
+    // nothing, bunched into its first half the both-T-major 4 x 4 kernel measured 4-8 % slower
+    constexpr int kDsSpread = (TA || TB) ? 1 : NI * NJ >= 16 ? V::kDsSpread : V::kDsSpreadSmall;
+
+    // ---- LDS -> registers: lane reads 32 contiguous bytes (two swizzled 16-byte chunks) of its row
+    const int fr_row = lane & 31;
+    const int fr_half = lane >> 5;                                  // which 32 bytes of the 64-byte K half
+    const int swz = (fr_row >> kSw) & 7;                            // same for every row this lane reads
+    const int offA = (wr * 32 * NI + fr_row) * BK, offB = (wc * 32 * NJ + fr_row) * BK;
+    const int ch00 = ((fr_half * 2) ^ swz) << 4, ch01 = ((fr_half * 2 + 1) ^ swz) << 4;
+    const int ch10 = ((4 + fr_half * 2) ^ swz) << 4, ch11 = ((4 + fr_half * 2 + 1) ^ swz) << 4;
+    auto read_frags_rows = [&](const uint8_t* slab, int off, int ks, auto& f) {
+        const int c0 = ks ? ch10 : ch00, c1 = ks ? ch11 : ch01;
+#pragma unroll
+        for (int i = 0; i < (int)(sizeof(f) / sizeof(f[0])); ++i) {
+            const uint8_t* p = slab + off + i * 32 * BK;
+            v4i lo = *reinterpret_cast<const v4i*>(p + c0);
+            v4i hi = *reinterpret_cast<const v4i*>(p + c1);
+            f[i] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        }
+    };
+    // T-major: byte offset of this lane's first transposing read of 32-row block i (half 0): LDS row
+    // 32 fr_half + (lane & 15) / 2, unit 2 (2 NX w + i) + ((lane >> 4) & 1) swizzled, half (lane & 1) of the unit.
+    const int tm_row = fr_half * 32 + ((lane & 15) >> 1);
+    int tm_offA[NI], tm_offB[NJ];
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+        tm_offA[i] = tm_row * BM + (((2 * (NI * wr + i) + ((lane >> 4) & 1)) ^ SA::swizzle_of_row(tm_row)) << 4) + ((lane & 1) << 3);
+#pragma unroll
+    for (int i = 0; i < NJ; ++i)
+        tm_offB[i] = tm_row * BN + (((2 * (NJ * wc + i) + ((lane >> 4) & 1)) ^ SB::swizzle_of_row(tm_row)) << 4) + ((lane & 1) << 3);
+    auto read_frags_tmajor = [&](const uint8_t* slab, const auto& offs, int pitch, int ks, auto& f) {
+#pragma unroll
+        for (int i = 0; i < (int)(sizeof(f) / sizeof(f[0])); ++i) {
+            v2i r[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                r[q] = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i*)(slab + offs[i] + (64 * ks + 8 * q) * pitch));
+            f[i] = v8i{r[0][0], r[0][1], r[1][0], r[1][1], r[2][0], r[2][1], r[3][0], r[3][1]};
+        }
+    };
+    auto read_fragsA = [&](uint8_t* slab, int ks, auto& f) {
+        if constexpr (TA) read_frags_tmajor(slab, tm_offA, BM, ks, f); else read_frags_rows(slab, offA, ks, f);
+    };
+    auto read_fragsB = [&](uint8_t* slab, int ks, auto& f) {
+        if constexpr (TB) read_frags_tmajor(slab, tm_offB, BN, ks, f); else read_frags_rows(slab, offB, ks, f);
+    };
+
+    v16f acc[NI][NJ];
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    v8i a0[NI], b0[NJ], a1[NI], b1[NJ];    // fragment sets of the two 64-byte halves of a K step
+    const int nk = T / BK;
+
+    // L2 touch loads: a wave reads the first dword of some rows of a slab that is still touch_ahead
+    // steps ahead of the direct-to-LDS loads (touch_ahead <= 0: nothing is fetched).  All CUs of an
+    // XCD walk K in lock-step, so without this every slab is first requested only ~1.5 steps before
+    // it is needed, less than a miss to HBM takes when the operands are not in the last-level cache.
+    // The workgroup touches rows [g * BM / shareA, (g + 1) * BM / shareA) of the A slab, g = tile
+    // column mod shareA, and likewise of the B slab with the tile row and shareB; each wave takes a quarter.
+    constexpr bool kTouch = V::kTouch;
+    constexpr int kShareA = V::kTouchShareA, kShareB = V::kTouchShareB;
+    // (T-major operand: the slab is 128 memory rows of kLines lines each, shared out the same way.)
+    constexpr int kRowsA = (TA ? BK * SA::kLines : BM) / kShareA / 4, kRowsB = (TB ? BK * SB::kLines : BN) / kShareB / 4;   // lines per wave
+    const int touch_lineA = ((tc % kShareA) * 4 + wave) * kRowsA + lane, touch_lineB = ((tr % kShareB) * 4 + wave) * kRowsB + lane;
+    const int touch_voffA = lane >= kRowsA ? kOutOfRange : TA ? (touch_lineA / SA::kLines) * ldA + (touch_lineA % SA::kLines) * 128 : touch_lineA * T;
+    const int touch_voffB = lane >= kRowsB ? kOutOfRange : TB ? (touch_lineB / SB::kLines) * ldB + (touch_lineB % SB::kLines) * 128 : touch_lineB * T;
+    int touchA[2] = {0, 0}, touchB[2] = {0, 0};   // results are only kept so that the loads stay tracked
+    int touch_sink = 0;
+
+    // One K step on the stage (curA, curB) while the other stage (nxtA, nxtB) is being filled:
+    //   first half : read the second-half fragments            | MFMAs on the first-half fragments
+    //   barrier    : the next slab has landed, everybody is done reading the current one
+    //   second half: start loading slab kt+2 into the current stage, read the first-half
+    //                fragments of slab kt+1                     | MFMAs on the second-half fragments
+    // Loads that would start beyond the last slab are pointed outside the buffer range instead:
+    // the hardware then fetches nothing (LDS receives zeros), and that stage is never used.
+    auto k_step = [&](uint8_t* curA, uint8_t* curB, uint8_t* nxtA, uint8_t* nxtB, int kt, int parity) {
+        read_fragsA(curA, 1, a1);
+        read_fragsB(curB, 1, b1);
+        mma_block<FA, FB, NI, NJ>(acc, a0, b0);
+        interleave<kMfmaPerHalf, kReadsPerHalf, 0, kDsSpread, V::kVmSpread, 0>();
+        // the direct-to-LDS loads of the previous step must have landed; its two touch loads, issued
+        // after them, may still be in flight
+        if constexpr (kTouch) wait_vmcnt<2>(); else wait_vmcnt<0>();
+        lds_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        issue_loads(curA, curB, kt + 2 < nk ? (kt + 2) * BK : -1);
+        read_fragsA(nxtA, 0, a0);               // past the last slab this reads bytes that are never used
+        read_fragsB(nxtB, 0, b0);
+        mma_block<FA, FB, NI, NJ>(acc, a1, b1);
+        interleave<kMfmaPerHalf, kReadsPerHalf, kLoadsPerStep, kDsSpread, V::kVmSpread, 1>();
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (kTouch) {
+            const int kp = kt + 2 + touch_ahead;
+            const bool on = touch_ahead > 0 && kp < nk;
+            touch_sink ^= touchA[parity] ^ touchB[parity];          // issued two steps ago: long landed
+            touchA[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, on ? (TA ? kp * BK * ldA : kp * BK) : kOutOfRange, 0);
+            touchB[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, on ? (TB ? kp * BK * ldB : kp * BK) : kOutOfRange, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // both stages are requested at once; only the first has to have landed before the first fragments
+    issue_loads(ldsA0, ldsB0, 0);
+    issue_loads(ldsA1, ldsB1, nk > 1 ? BK : -1);
+    if constexpr (kTouch) {                       // keep "two touch loads are the newest" true from the start
+        const bool on = touch_ahead > 0 && 2 < nk;
+        touchA[1] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, on ? (TA ? 2 * BK * ldA : 2 * BK) : kOutOfRange, 0);
+        touchB[1] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, on ? (TB ? 2 * BK * ldB : 2 * BK) : kOutOfRange, 0);
+    }
+    wait_vmcnt<kLoadsPerStep + (kTouch ? 2 : 0)>();
+    lds_barrier();
+    read_fragsA(ldsA0, 0, a0);
+    read_fragsB(ldsB0, 0, b0);
+    stamp(1);
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+        k_step(ldsA0, ldsB0, ldsA1, ldsB1, kt, 0);
+        k_step(ldsA1, ldsB1, ldsA0, ldsB0, kt + 1, 1);
+    }
+    if (kt < nk) k_step(ldsA0, ldsB0, ldsA1, ldsB1, kt, 0);
+    // Every wave waits for its own direct-to-LDS loads (the out-of-range ones of the last two steps
+    // still write zeros into the slabs), then all meet: after this barrier nothing lands in LDS any
+    // more and nobody reads the slabs, so the epilogue may reuse them.
+    wait_vmcnt<0>();
+    lds_barrier();
+    if constexpr (kTouch) {
+        touch_sink ^= touchA[0] ^ touchB[0] ^ touchA[1] ^ touchB[1];
+        asm volatile("" ::"v"(touch_sink));
+    }
+    stamp(2);
+    // The workgroup that follows on this XCD (id + next_stride: same XCD, and dispatched about when this
+    // one retires) starts with two slabs of its own operands; one dword per 128-byte line of them is
+    // requested here, so that they reach the L2 while this workgroup is busy with its epilogue.
+    int next_touch[4] = {0, 0, 0, 0};
+    if constexpr (kTouch) {
+        int ntr, ntc;
+        if (next_stride > 0 && T >= 2 * BK && tile_of_block(blockIdx.x + next_stride, tiles_r, tiles_c, band_rows, ntr, ntc)) {
+            if constexpr (TA) {                   // memory rows 0 .. 255, one per thread, kLines lines each
+                const uint8_t* na = A + (size_t)threadIdx.x * ldA + (size_t)ntr * BM;
+                next_touch[0] = *reinterpret_cast<const int*>(na);
+                if (SA::kLines > 1) next_touch[1] = *reinterpret_cast<const int*>(na + 128);
+            } else {
+                const uint8_t* na = A + ((size_t)ntr * BM + wave * (BM / 4) + lane) * T;
+                if (lane < BM / 4) {
+                    next_touch[0] = *reinterpret_cast<const int*>(na);
+                    next_touch[1] = *reinterpret_cast<const int*>(na + BK);
+                }
+            }
+            if constexpr (TB) {
+                const uint8_t* nb = B + (size_t)threadIdx.x * ldB + (size_t)ntc * BN;
+                next_touch[2] = *reinterpret_cast<const int*>(nb);
+                if (SB::kLines > 1) next_touch[3] = *reinterpret_cast<const int*>(nb + 128);
+            } else {
+                const uint8_t* nb = B + ((size_t)ntc * BN + wave * (BN / 4) + lane) * T;
+                if (lane < BN / 4) {
+                    next_touch[2] = *reinterpret_cast<const int*>(nb);
+                    next_touch[3] = *reinterpret_cast<const int*>(nb + BK);
+                }
+            }
+        }
+    }
+
+    // ---- epilogue.  Per 32x32 block a lane holds 4 groups of 4 consecutive columns of row (lane % 32).
+    // Storing those 8-byte pieces directly scatters every store over 32 rows; instead each wave
+    // stages one 32-row block of its quadrant at a time (32 rows x 32 NJ BF16 columns) at the start of one
+    // of the four slabs, which nobody reads any more, and writes it out as full row segments, 16 bytes per lane.  The
+    // 16-byte slot index of a staged row is rotated by the row number, so that the 8-byte writes of
+    // 32 rows and the 16-byte reads spread over the banks.  The region is private to the wave and LDS
+    // executes a wave's accesses in order, so no further barrier is needed.
+    // De-scale with one multiply by 1 / (sA sB) unless that product leaves the normal range (degenerate
+    // scales such as FLT_MAX for an all-zero tensor), in which case the two factors are applied in turn
+    // (a second copy of the epilogue, so that the usual path carries no trace of it).
+    const float inv_a = 1.0f / scale_a, inv_b = 1.0f / scale_b;
+    const float inv_ab = inv_a * inv_b;
+    const bool one_mul = inv_ab >= 1.17549435e-38f && inv_ab <= 3.402823466e+38f;
+    const float m1 = one_mul ? inv_ab : inv_a;
+    // The output absmax is taken in fp32 before rounding: rounding to BF16 is monotonic, so the BF16
+    // rounding of the largest |y| is the largest rounded magnitude.
+    float maxabs = 0.0f;
+    auto track4 = [&](const v4f& y) {
+        maxabs = __builtin_fmaxf(__builtin_fmaxf(maxabs, __builtin_fabsf(y[0])), __builtin_fabsf(y[1]));
+        maxabs = __builtin_fmaxf(__builtin_fmaxf(maxabs, __builtin_fabsf(y[2])), __builtin_fabsf(y[3]));
+    };
+    // The body exists twice, for one and for two de-scale multiplies; the choice is uniform over the grid.
+    auto write_out = [&](auto two_mul) {
+    auto descale4 = [&](const v16f& block, int g) -> v4f {
+        v4f y;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            y[e] = block[4 * g + e] * m1;
+            if constexpr (decltype(two_mul)::value) y[e] *= inv_b;
+        }
+        return y;
+    };
+    if constexpr (!ACCUM) {
+        constexpr int kSlots = 4 * NJ;                                       // 16-byte slots per staged row
+        constexpr int kPitch = 16 * kSlots;
+        constexpr bool kPow2 = (kSlots & (kSlots - 1)) == 0;
+        uint8_t* stage = wave == 0 ? ldsA0 : wave == 1 ? ldsB0 : wave == 2 ? ldsA1 : ldsB1;
+        // byte offset inside a staged row of the 8 bytes this lane writes for column group c8 = col / 8;
+        // with a power-of-two slot count it does not depend on the row block (32 rows apart)
+        int slot_off[kSlots];
+        if constexpr (kPow2) {
+#pragma unroll
+            for (int c8 = 0; c8 < kSlots; ++c8) slot_off[c8] = (((c8 + fr_row) & (kSlots - 1)) << 4) | (fr_half << 3);
+        }
+        uint16_t* cbase = C + (size_t)(tr * BM + wr * 32 * NI) * Cn + tc * BN + wc * 32 * NJ;
+        constexpr int kBlockPieces = 32 * kSlots;                            // 16-byte pieces of one block of 32 rows
+        // one block of 32 rows at a time: while its stores are in flight the next block is converted
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            if constexpr (V::kEpilogueFence) __builtin_amdgcn_sched_barrier(0);
+            const int row = fr_row;             // the 32 staged rows are reused by every block: LDS runs a wave's accesses in order
+            uint8_t* srow = stage + row * kPitch;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const v4f y = descale4(acc[i][j], g);
+                    track4(y);
+                    bf16x4 o = __builtin_convertvector(y, bf16x4);
+                    const int c8 = j * 4 + g;                                // columns 8 c8 + 4 fr_half + 0..3
+                    const int off = kPow2 ? slot_off[c8] : ((((c8 + row) % kSlots) << 4) | (fr_half << 3));
+                    *reinterpret_cast<bf16x4*>(srow + off) = o;
+                }
+            }
+            // all pieces of the block are read back before the first is stored, so that the LDS round
+            // trips overlap instead of each store waiting for its own read
+            constexpr int kPiecesPerLane = kBlockPieces / kWave;
+            v4u piece[kPiecesPerLane];
+#pragma unroll
+            for (int k = 0; k < kPiecesPerLane; ++k) {
+                const int p = lane + k * kWave;
+                const int r = p / kSlots, sl = p % kSlots;
+                piece[k] = *reinterpret_cast<const v4u*>(stage + r * kPitch + (((sl + r) % kSlots) << 4));
+            }
+            if constexpr (V::kEpilogueFence) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < kPiecesPerLane; ++k) {
+                const int p = lane + k * kWave;
+                const int r = i * 32 + p / kSlots, sl = p % kSlots;      // row inside the wave's quadrant
+                if constexpr (V::kNtStoreC) __builtin_nontemporal_store(piece[k], reinterpret_cast<v4u*>(cbase + (size_t)r * Cn + sl * 8));
+                else *reinterpret_cast<v4u*>(cbase + (size_t)r * Cn + sl * 8) = piece[k];
+            }
+        }
+        if constexpr (V::kProfile) stamp(4);
+    } else {
+        // BF16 accumulation needs the old value before the single rounding: straight from the registers.
+        const int row_base = tr * BM + wr * 32 * NI + fr_row;
+        const int col_base = tc * BN + wc * 32 * NJ + fr_half * 4;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            uint16_t* crow = C + (size_t)(row_base + i * 32) * Cn + col_base;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    uint16_t* dst = crow + j * 32 + g * 8;
+                    v4f y = descale4(acc[i][j], g);
+                    v2u old = *reinterpret_cast<const v2u*>(dst);
+                    y[0] += __uint_as_float(old[0] << 16);
+                    y[1] += __uint_as_float(old[0] & 0xFFFF0000u);
+                    y[2] += __uint_as_float(old[1] << 16);
+                    y[3] += __uint_as_float(old[1] & 0xFFFF0000u);
+                    track4(y);
+                    *reinterpret_cast<bf16x4*>(dst) = __builtin_convertvector(y, bf16x4);
+                }
+            }
+        }
+    }
+    };
+    if (one_mul) write_out(BoolTag<false>{}); else write_out(BoolTag<true>{});
+    if constexpr (kTouch) asm volatile("" ::"v"(next_touch[0] ^ next_touch[1] ^ next_touch[2] ^ next_touch[3]));
+    unsigned mag = (unsigned)__builtin_bit_cast(uint16_t, (__bf16)maxabs);   // non-negative: magnitude bits
+    if (amax_bits) {
+        mag = wave_max_u32(mag);
+        if (lane == 0) s_amax[wave] = mag;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int w = 1; w < kGemmThreads / kWave; ++w) mag = mag > s_amax[w] ? mag : s_amax[w];
+            // same-address atomics of many workgroups serialise; a stale read never exceeds the true maximum
+            const unsigned bits = amax_bits_from_bf16_mag(mag);
+            if (bits > __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(amax_bits, bits);
+        }
+    }
+    if constexpr (V::kProfile) {
+        stamp(5);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        stamp(3);
+    }
+}
+
+// ---- host side: tile choice and launch
+struct TileChoice {
+    int ni, nj;       // 0, 0: no tuned tile divides the problem, use the generic kernel
+};
+TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus);
+
+// Distance of the L2 touch loads in K steps; LLMQ_GEMM_TOUCH overrides it for tuning.
+inline int touch_ahead() {
+    if (const char* e = getenv("LLMQ_GEMM_TOUCH")) return atoi(e);
+    return 2;
+}
+
+// Height of the bands of tiles, in tile rows; LLMQ_GEMM_BAND overrides it for tuning.
+inline int band_rows() {
+    if (const char* e = getenv("LLMQ_GEMM_BAND")) { const int v = atoi(e); if (v >= 1 && v <= 64) return v; }
+    return kBandRows;
+}
+
+// The same for 2 x 2 tiles, where two workgroups share a CU and already cover each other's waits.
+inline int touch_ahead_pair() {
+    if (const char* e = getenv("LLMQ_GEMM_TOUCH_PAIR")) return atoi(e);
+    return 0;
+}
+
+// Whether a workgroup requests the first slabs of its successor; LLMQ_GEMM_TOUCH_NEXT=0 / 1 overrides it.
+inline bool touch_next(bool by_default) {
+    if (const char* e = getenv("LLMQ_GEMM_TOUCH_NEXT")) return atoi(e) != 0;
+    return by_default;
+}
+
+template <int FA, int FB, int NI, int NJ, bool TA = false, bool TB = false>
+static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
+                        const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
+                        hipStream_t stream, int num_cus) {
+    const int tiles_r = (int)(R / (64 * NI)), tiles_c = (int)(C / (64 * NJ));
+    const int nt = tiles_r * tiles_c;
+    const int grid = ((nt + kXcds - 1) / kXcds) * kXcds;
+    const int touch = (NI == 2 && NJ == 2) ? touch_ahead_pair() : touch_ahead();
+    // workgroups resident on the chip at once (a multiple of the XCD count): the distance to the
+    // workgroup that takes over a slot
+    // (measured: +3 % on a GEMM of 19 rounds of tiles, whose later workgroups otherwise start on cold
+    // operands; nothing or slightly less on GEMMs of 2-4 rounds, so it is used from 6 rounds on)
+    const int slots = (num_cus / kXcds) * kXcds * ((NI == 2 && NJ == 2) ? 2 : 1);
+    const int next_stride = touch_next(nt >= 6 * slots) ? slots : 0;
+    if (accumulate)
+        hipLaunchKernelGGL((gemm_tile_kernel<FA, FB, NI, NJ, true, GemmTuning, TA, TB>), dim3(grid), dim3(kGemmThreads), 0, stream,
+                           A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c,
+                           touch, band_rows(), next_stride, (int)R, (int)C);
+    else
+        hipLaunchKernelGGL((gemm_tile_kernel<FA, FB, NI, NJ, false, GemmTuning, TA, TB>), dim3(grid), dim3(kGemmThreads), 0, stream,
+                           A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c,
+                           touch, band_rows(), next_stride, (int)R, (int)C);
+}
+
+
+// Dispatch on the tile chosen for the problem; false if none divides it.
+template <int FA, int FB, bool TA, bool TB>
+static bool launch_chosen_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
+                               const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
+                               hipStream_t stream, int num_cus) {
+    const TileChoice tc = choose_tile(R, C, T, num_cus);
+#define LLMQ_TILE_CASE(I, J)                                                                              \
+    case I * 8 + J:                                                                                       \
+        launch_tile<FA, FB, I, J, TA, TB>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus);   \
+        return true;
+    switch (tc.ni * 8 + tc.nj) {
+        LLMQ_TILE_CASE(4, 4) LLMQ_TILE_CASE(4, 3) LLMQ_TILE_CASE(4, 2)
+        LLMQ_TILE_CASE(3, 4) LLMQ_TILE_CASE(3, 3) LLMQ_TILE_CASE(3, 2)
+        LLMQ_TILE_CASE(2, 4) LLMQ_TILE_CASE(2, 3) LLMQ_TILE_CASE(2, 2)
+        default: break;
+    }
+#undef LLMQ_TILE_CASE
+    return false;
+}
+
+}  // namespace llmq

@@ -44,6 +44,12 @@ int launch_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64
                    int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16,
                    int accumulate, float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus);
 
+// The same contraction with either operand optionally T-major: ta: A is [T, R], tb: B is [T, C] (the
+// contraction index runs down the rows), so the backward GEMMs can read the untransposed quantized tensors.
+int launch_gemm_fp8(const uint8_t* A, int fmtA, bool ta, const uint8_t* B, int fmtB, bool tb, int64_t R, int64_t C,
+                    int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16, int accumulate,
+                    float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus);
+
 // SwiGLU with its extra outputs.  h, d_amax (with partial, the per-workgroup scratch), q and q_t are
 // optional; q_fmt is only read when q is given.  swiglu_blocks() is the number of scratch words.
 int64_t swiglu_blocks(int64_t M, int64_t I);

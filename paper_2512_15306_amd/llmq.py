@@ -19,12 +19,13 @@ REUSE_DY = 4
 JIT_X = 8
 JIT_W = 16
 JIT_DY = 32
+NO_TRANSPOSE = 64
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libllmq.so")
 _lib = None
 
-EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "llmq_amax", "llmq_quantize_fp8", "llmq_fp8_gemm_tn", "llmq_bf16_gemm_tn",
+EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "llmq_amax", "llmq_quantize_fp8", "llmq_fp8_gemm_tn", "llmq_fp8_gemm", "llmq_bf16_gemm_tn",
            "llmq_fp8_linear_workspace_bytes", "llmq_fp8_linear_workspace_offsets",
            "llmq_fp8_linear_fwd", "llmq_fp8_linear_dgrad", "llmq_fp8_linear_wgrad",
            "llmq_scale_from_amax", "llmq_swiglu_workspace_bytes", "llmq_swiglu_fwd", "llmq_swiglu_fwd_fp8",
@@ -61,6 +62,8 @@ def lib() -> ctypes.CDLL:
     L.llmq_quantize_fp8.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp]
     L.llmq_fp8_gemm_tn.restype = i32
     L.llmq_fp8_gemm_tn.argtypes = [vp, i32, vp, i32, i64, i64, i64, vp, vp, vp, i32, vp, vp]
+    L.llmq_fp8_gemm.restype = i32
+    L.llmq_fp8_gemm.argtypes = [vp, i32, i32, vp, i32, i32, i64, i64, i64, vp, vp, vp, i32, vp, vp]
     L.llmq_bf16_gemm_tn.restype = i32
     L.llmq_bf16_gemm_tn.argtypes = [vp, vp, i64, i64, i64, vp, i32, vp]
     L.llmq_fp8_linear_workspace_bytes.restype = sz
@@ -159,6 +162,20 @@ def llmq_fp8_gemm_tn(A: torch.Tensor, fmtA: int, B: torch.Tensor, fmtB: int, d_s
                                   _dev(d_scaleA, torch.float32), _dev(d_scaleB, torch.float32),
                                   _dev(c, torch.bfloat16, "c"), int(bool(accumulate)),
                                   _dev(d_amax_c, torch.float32), _stream()), "llmq_fp8_gemm_tn")
+
+
+def llmq_fp8_gemm(A: torch.Tensor, fmtA: int, a_t_major: bool, B: torch.Tensor, fmtB: int, b_t_major: bool,
+                  d_scaleA: torch.Tensor, d_scaleB: torch.Tensor, c: torch.Tensor, accumulate: bool = False,
+                  d_amax_c: Optional[torch.Tensor] = None) -> None:
+    """A is [R, T], or [T, R] when a_t_major; B is [C, T], or [T, C] when b_t_major."""
+    T, R = A.shape if a_t_major else A.shape[::-1]
+    T2, C = B.shape if b_t_major else B.shape[::-1]
+    if T != T2 or tuple(c.shape) != (R, C):
+        raise ValueError("shape mismatch: A %s, B %s, c %s" % (tuple(A.shape), tuple(B.shape), tuple(c.shape)))
+    _check(lib().llmq_fp8_gemm(_dev(A, torch.uint8, "A"), fmtA, int(bool(a_t_major)), _dev(B, torch.uint8, "B"), fmtB,
+                               int(bool(b_t_major)), R, C, T, _dev(d_scaleA, torch.float32),
+                               _dev(d_scaleB, torch.float32), _dev(c, torch.bfloat16, "c"), int(bool(accumulate)),
+                               _dev(d_amax_c, torch.float32), _stream()), "llmq_fp8_gemm")
 
 
 def llmq_bf16_gemm_tn(A: torch.Tensor, B: torch.Tensor, c: torch.Tensor, accumulate: bool = False) -> None:

@@ -63,12 +63,17 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.llmq_fp8_gemm_tn(ok_ptr, 0, ok_ptr, 0, 16, 0, 16, ok_ptr, ok_ptr, ok_ptr, 0, None, None) == -2
     assert L.llmq_fp8_gemm_tn(ok_ptr, 3, ok_ptr, 0, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, 0, None, None) == -4
     assert L.llmq_fp8_gemm_tn(ok_ptr, 0, ok_ptr, 0, 16, 16, 16, ok_ptr, ok_ptr, odd_ptr, 0, None, None) == -3
+    L.llmq_fp8_gemm.restype = ctypes.c_int
+    assert L.llmq_fp8_gemm(ok_ptr, 0, 1, None, 0, 1, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, 0, None, None) == -1
+    assert L.llmq_fp8_gemm(ok_ptr, 0, 1, ok_ptr, 0, 1, 16, 0, 16, ok_ptr, ok_ptr, ok_ptr, 0, None, None) == -2
+    assert L.llmq_fp8_gemm(ok_ptr, 0, 1, ok_ptr, 5, 0, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, 0, None, None) == -4
+    assert L.llmq_fp8_gemm(odd_ptr, 0, 0, ok_ptr, 0, 1, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, 0, None, None) == -3
     ws = 0x100000
     need = llmq.llmq_fp8_linear_workspace_bytes(16, 16, 16)
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, None, n(need), 0, None) == -1
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need - 1), 0, None) == -5
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws + 16, n(need), 0, None) == -3
-    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 64, None) == -7
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 128, None) == -7
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 8 | 1, None) == -7      # JIT and REUSE of one operand
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 32, None) == -7         # dY is no operand of the forward call
     assert L.llmq_fp8_linear_wgrad(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, 1, ok_ptr, 0, ws, n(need), 16, None) == -7
