@@ -138,12 +138,15 @@ int llmq_bf16_gemm_tn(const void* A_bf16, const void* B_bf16, int64_t R, int64_t
 
 /*
  * Workspace of the three linear-layer calls below, for one (M, N, K).  It holds the FP8 copies
- *   Xq [M,K], Xq_t [K,M], Wq [N,K], Wq_t [K,N], dYq [M,N], dYq_t [N,M]
- * in this order, each starting at a multiple of 256 bytes; llmq_fp8_linear_workspace_offsets() returns
- * the six byte offsets.  Behind them sit 12 KB of scratch for the LLMQ_JIT_* flags.  The caller owns the
- * workspace and may read the copies between calls.
+ *   Xq [M,K], Wq [N,K], dYq [M,N], then 12 KB of scratch for the LLMQ_JIT_* flags, then
+ *   Xq_t [K,M], Wq_t [K,N], dYq_t [N,M],
+ * each starting at a multiple of 256 bytes.  llmq_fp8_linear_workspace_offsets() returns the byte offsets of
+ * the copies in the order Xq, Xq_t, Wq, Wq_t, dYq, dYq_t.  Calls that carry LLMQ_NO_TRANSPOSE touch nothing
+ * behind the scratch and accept a workspace of llmq_fp8_linear_workspace_bytes_no_transpose() bytes (half the
+ * FP8 copies).  The caller owns the workspace and may read the copies between calls.
  */
 size_t llmq_fp8_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
+size_t llmq_fp8_linear_workspace_bytes_no_transpose(int64_t M, int64_t N, int64_t K);
 int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t offsets[6]);
 
 /* `flags` of the linear calls: the named operand's FP8 copies are already in the workspace (written by
@@ -162,9 +165,10 @@ int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t of
 #define LLMQ_JIT_W  16
 #define LLMQ_JIT_DY 32
 /* No transposed copies: the call writes only the row-major FP8 copies (Xq, Wq, dYq) and the backward GEMMs
- * read those T-major (see llmq_fp8_gemm), which saves one byte written per quantized element.  The sections
- * Xq_t, Wq_t, dYq_t of the workspace are then neither written nor read.  Copies made under this flag can only
- * be reused (LLMQ_REUSE_*) by calls that carry it too; results are bit-identical either way. */
+ * read those T-major (see llmq_fp8_gemm), which saves one byte written per quantized element and half the
+ * workspace: the sections Xq_t, Wq_t, dYq_t are neither written nor read and need not exist.  Copies made
+ * under this flag can only be reused (LLMQ_REUSE_*) by calls that carry it too, copies made without it by
+ * any call; results are bit-identical either way. */
 #define LLMQ_NO_TRANSPOSE 64
 
 /*

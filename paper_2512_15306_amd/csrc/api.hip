@@ -28,19 +28,23 @@ int num_cus() {
 }
 
 struct WsLayout {
-    size_t xq, xqt, wq, wqt, dyq, dyqt, part, total;      // part: three absmax scratch areas (X, W, dY)
+    size_t xq, xqt, wq, wqt, dyq, dyqt, part;     // part: three absmax scratch areas (X, W, dY)
+    size_t compact, total;                        // bytes needed without / with the transposed copies
 };
 
+// Row-major copies and the scratch first, the transposed copies behind them: a workspace that ends after the
+// scratch serves every call that carries LLMQ_NO_TRANSPOSE.
 WsLayout ws_layout(int64_t M, int64_t N, int64_t K) {
     WsLayout l;
     size_t off = 0;
     l.xq = off;   off += round256((size_t)M * K);
-    l.xqt = off;  off += round256((size_t)M * K);
     l.wq = off;   off += round256((size_t)N * K);
-    l.wqt = off;  off += round256((size_t)N * K);
     l.dyq = off;  off += round256((size_t)M * N);
-    l.dyqt = off; off += round256((size_t)M * N);
     l.part = off; off += 3 * round256((size_t)llmq::kAmaxMaxPartials * sizeof(unsigned));
+    l.compact = off;
+    l.xqt = off;  off += round256((size_t)M * K);
+    l.wqt = off;  off += round256((size_t)N * K);
+    l.dyqt = off; off += round256((size_t)M * N);
     l.total = off;
     return l;
 }
@@ -55,7 +59,8 @@ int check_linear(int64_t M, int64_t N, int64_t K, const void* ws, size_t ws_byte
         return LLMQ_ERR_FLAGS;
     if (!ws) return LLMQ_ERR_NULL;
     if (!aligned(ws, 256)) return LLMQ_ERR_ALIGN;
-    if (ws_bytes < ws_layout(M, N, K).total) return LLMQ_ERR_WORKSPACE;
+    const WsLayout l = ws_layout(M, N, K);
+    if (ws_bytes < ((flags & LLMQ_NO_TRANSPOSE) ? l.compact : l.total)) return LLMQ_ERR_WORKSPACE;
     return LLMQ_OK;
 }
 
@@ -159,6 +164,11 @@ int llmq_bf16_gemm_tn(const void* A_bf16, const void* B_bf16, int64_t R, int64_t
 size_t llmq_fp8_linear_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     if (!dim_ok(M) || !dim_ok(N) || !dim_ok(K)) return 0;
     return ws_layout(M, N, K).total;
+}
+
+size_t llmq_fp8_linear_workspace_bytes_no_transpose(int64_t M, int64_t N, int64_t K) {
+    if (!dim_ok(M) || !dim_ok(N) || !dim_ok(K)) return 0;
+    return ws_layout(M, N, K).compact;
 }
 
 int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t offsets[6]) {

@@ -29,14 +29,21 @@ def test_workspace_layout():
     M, N, K = 256, 1024, 512
     offs = llmq.llmq_fp8_linear_workspace_offsets(M, N, K)
     sizes = [M * K, M * K, N * K, N * K, M * N, M * N]
-    assert offs[0] == 0
-    for i in range(5):
-        assert offs[i + 1] >= offs[i] + sizes[i] and offs[i + 1] % 256 == 0
-    assert llmq.llmq_fp8_linear_workspace_bytes(M, N, K) >= offs[5] + sizes[5]
+    total = llmq.llmq_fp8_linear_workspace_bytes(M, N, K)
+    compact = llmq.llmq_fp8_linear_workspace_bytes_no_transpose(M, N, K)
+    assert offs[0] == 0 and all(o % 256 == 0 for o in offs)
+    spans = sorted((o, o + n) for o, n in zip(offs, sizes))
+    for (a0, a1), (b0, b1) in zip(spans, spans[1:]):
+        assert a1 <= b0                                         # no two copies overlap
+    assert spans[-1][1] <= total
+    # row-major copies and the scratch (12 KB) come first: a workspace without transposed copies is a prefix
+    assert max(offs[i] + sizes[i] for i in (0, 2, 4)) + 12288 <= compact <= min(offs[i] for i in (1, 3, 5))
+    assert compact < total and total - compact >= sum(sizes[1::2])
     # ragged sizes are padded to 256-byte boundaries
     offs = llmq.llmq_fp8_linear_workspace_offsets(3, 5, 7)
     assert all(o % 256 == 0 for o in offs) and len(set(offs)) == 6
     assert llmq.llmq_fp8_linear_workspace_bytes(0, 1, 1) == 0
+    assert llmq.llmq_fp8_linear_workspace_bytes_no_transpose(1, 0, 1) == 0
 
 
 def test_argument_errors_are_reported_before_any_launch():
@@ -74,6 +81,9 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need - 1), 0, None) == -5
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws + 16, n(need), 0, None) == -3
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 128, None) == -7
+    small = llmq.llmq_fp8_linear_workspace_bytes_no_transpose(16, 16, 16)
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(small), 0, None) == -5
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(small - 1), 64, None) == -5
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 8 | 1, None) == -7      # JIT and REUSE of one operand
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 32, None) == -7         # dY is no operand of the forward call
     assert L.llmq_fp8_linear_wgrad(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, 1, ok_ptr, 0, ws, n(need), 16, None) == -7

@@ -125,9 +125,12 @@ def test_linear_calls_without_transposed_copies(shape, fmt_dy):
     xd, wd, dyd = x.to(DEV), w.to(DEV), dy.to(DEV)
     nbytes = llmq.llmq_fp8_linear_workspace_bytes(M, N, K)
     offs = llmq.llmq_fp8_linear_workspace_offsets(M, N, K)
+    compact = llmq.llmq_fp8_linear_workspace_bytes_no_transpose(M, N, K)
+    assert compact <= min(offs[1], offs[3], offs[5])
     outs = {}
     for flag in (0, llmq.NO_TRANSPOSE):
-        ws = torch.full((nbytes,), 0x55, dtype=torch.uint8, device=DEV)
+        full = torch.full((nbytes,), 0x55, dtype=torch.uint8, device=DEV)
+        ws = full[:compact] if flag else full       # the bytes behind a compact workspace must stay untouched
         gsx = torch.zeros(1, dtype=torch.float32, device=DEV)
         gsw, gsd = torch.zeros_like(gsx), torch.zeros_like(gsx)
         Y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
@@ -138,11 +141,12 @@ def test_linear_calls_without_transposed_copies(shape, fmt_dy):
         llmq.llmq_fp8_linear_fwd(xd, wd, M, N, K, gsx, gsw, Y, amax_y, ws, flag | llmq.JIT_X | llmq.JIT_W)
         llmq.llmq_fp8_linear_dgrad(dyd, None, M, N, K, gsd, gsw, fmt_dy, dX, amax_dx, ws, flag | llmq.REUSE_W | llmq.JIT_DY)
         llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, gsd, gsx, fmt_dy, dW, True, ws, flag | llmq.REUSE_X | llmq.REUSE_DY)
-        outs[flag] = (Y, dX, dW, amax_y.item(), amax_dx.item(), ws.cpu().numpy())
+        outs[flag] = (Y, dX, dW, amax_y.item(), amax_dx.item(), full.cpu().numpy())
     for a, b in zip(outs[0][:3], outs[llmq.NO_TRANSPOSE][:3]):
         assert torch.equal(a.view(torch.int16), b.view(torch.int16))
     assert outs[0][3:5] == outs[llmq.NO_TRANSPOSE][3:5]
     wsh = outs[llmq.NO_TRANSPOSE][5]
+    assert (wsh[compact:] == 0x55).all()
     for i, want in enumerate((xq, xqt, wq, wqt, dq, dqt)):
         got = wsh[offs[i]:offs[i] + want.size]
         if i % 2 == 0:
