@@ -130,6 +130,14 @@ def run_quantize_kernel_only(states):
         llmq.llmq_quantize_fp8(s.dY, s.sd, 1, s.view(4), s.view(5))
 
 
+def run_quantize_row_major_only(states):
+    from paper_2512_15306_amd import llmq
+    for s in states:
+        llmq.llmq_quantize_fp8(s.X, s.sx, 0, s.view(0), None)
+        llmq.llmq_quantize_fp8(s.W, s.sw, 0, s.view(2), None)
+        llmq.llmq_quantize_fp8(s.dY, s.sd, 1, s.view(4), None)
+
+
 def timed(fn, reps):
     """Average milliseconds per call of fn over reps calls, by events on the current stream."""
     import torch
@@ -326,6 +334,7 @@ def main():
     ms_amax = timed(lambda: run_amax_only(states), reps)
     ms_qk = timed(lambda: run_quantize_kernel_only(states), reps)
     ms_fused = timed(lambda: run_step(states, args.prequantized_w, producer_absmax=True), reps)
+    ms_qrow = timed(lambda: run_quantize_row_major_only(states), reps)
     # the same step on row-major FP8 copies only (the backward GEMMs read them T-major): a side figure
     run_step(states, args.prequantized_w, extra_flags=llmq.NO_TRANSPOSE)       # first use loads those kernels
     ms_nt = timed(lambda: run_step(states, args.prequantized_w, extra_flags=llmq.NO_TRANSPOSE), reps)
@@ -350,6 +359,8 @@ def main():
         "absmax_only_pct_hbm_peak": round(100.0 * 2.0 * synth.quantize_elements(cfg) / (ms_amax * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2),
         "quantize_kernel_only_gbps": round(4.0 * synth.quantize_elements(cfg) / (ms_qk * 1e-3) / 1e9, 1),
         "quantize_kernel_only_pct_hbm_peak": round(100.0 * 4.0 * synth.quantize_elements(cfg) / (ms_qk * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2),
+        "quantize_row_major_only_gbps": round(3.0 * synth.quantize_elements(cfg) / (ms_qrow * 1e-3) / 1e9, 1),
+        "quantize_row_major_only_pct_hbm_peak": round(100.0 * 3.0 * synth.quantize_elements(cfg) / (ms_qrow * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2),
         "step_tflops_with_producer_fused_absmax": round(flops / (ms_fused * 1e-3) / 1e12, 2),
         "step_tflops_without_transposed_copies": round(flops / (ms_nt * 1e-3) / 1e12, 2),
         "step_tflops_without_transposed_copies_with_producer_fused_absmax": round(flops / (ms_nt_fused * 1e-3) / 1e12, 2),

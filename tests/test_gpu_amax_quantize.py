@@ -103,6 +103,8 @@ def test_quantize_every_bf16_value_under_many_scales(fmt):
         bad = np.argwhere(got != wq)
         assert bad.size == 0, (sc, hex(xb[tuple(bad[0])]), hex(got[tuple(bad[0])]), hex(wq[tuple(bad[0])]))
         assert np.array_equal(qt.cpu().numpy(), wqt)
+        q_only, _ = gpu_quantize(xd, s, fmt, transpose=False)       # the kernel without a transposed copy
+        assert np.array_equal(q_only.cpu().numpy(), wq)
 
 
 def test_config_tensors_quantize_bit_exact_at_full_size():
@@ -119,4 +121,6 @@ def test_config_tensors_quantize_bit_exact_at_full_size():
         assert np.array_equal(q.cpu().numpy(), wq)
         assert np.array_equal(qt.cpu().numpy(), wqt)
         assert (wq & 0x7F).max() == {0: 0x7E, 1: 0x7B}[fmt]
-        del t, q, qt
+        q_only, _ = gpu_quantize(t, s, fmt, transpose=False)
+        assert torch.equal(q_only, q)
+        del t, q, qt, q_only
