@@ -213,3 +213,43 @@ def test_full_size_backward_without_transposed_copies(cfg_i, li):
         err = np.abs(got - y)
         assert np.all(err <= GEMM_TOL * S), (name, err.max())
         assert np.isfinite(got).all() and np.abs(got).max() > 0
+
+
+@pytest.mark.parametrize("ta,tb", LAYOUTS)
+def test_request_of_the_next_tiles_slabs_with_t_major_operands(ta, tb, monkeypatch):
+    """272 tiles of 256 x 256 on 256 CUs with the successor's first slabs requested by every workgroup (forced
+    through the tuning override; by default only long GEMMs do it): the loads must not change any byte."""
+    R, C, T = 17 * 256, 16 * 256, 512
+    A = _rand_codes((R, T), 1, 71)
+    B = _rand_codes((C, T), 0, 72)
+    monkeypatch.setenv("LLMQ_GEMM_TILE", "4x4")
+    monkeypatch.setenv("LLMQ_GEMM_TOUCH_NEXT", "1")
+    c, am = _run(A, 1, ta, B, 0, tb, 2.5, 0.5, want_amax=True)
+    monkeypatch.setenv("LLMQ_GEMM_TOUCH_NEXT", "0")
+    c0, _ = _run(A, 1, ta, B, 0, tb, 2.5, 0.5)
+    assert torch.equal(c.view(torch.int16), c0.view(torch.int16))
+    assert torch.equal(_run_tn(A, 1, B, 0, 2.5, 0.5).view(torch.int16), c.view(torch.int16))
+    assert am.item() == c.float().abs().max().item()
+    rr, cc = _sample_positions(R, C, 1024, 5)
+    y, S = oracle.gemm_tn_sampled(A, 1, B, 0, 2.5, 0.5, rr, cc)
+    got = c[torch.from_numpy(rr).to(DEV), torch.from_numpy(cc).to(DEV)].cpu().to(torch.float64).numpy()
+    assert np.all(np.abs(got - y) <= GEMM_TOL * S)
+
+
+def test_degenerate_scales_and_all_zero_operands_with_t_major_operands():
+    """An all-zero operand quantized with the FLT_MAX scale, and a scale product that leaves the normal range
+    (second copy of the epilogue), in the T-major instantiations."""
+    R, C, T = 256, 256, 256
+    A = _rand_codes((R, T), 0, 81)
+    Z = np.zeros((C, T), np.uint8)
+    for ta, tb in LAYOUTS:
+        c, am = _run(A, 0, ta, Z, 0, tb, 3.0, 3.4028234e38, want_amax=True)
+        assert (c.view(torch.int16) & 0x7FFF).max().item() == 0 and am.item() == 0.0
+        B = _rand_codes((C, T), 0, 82)
+        big = 2.0 ** 65                  # 1 / (sA sB) = 2^-130 is below the normal range: two multiplies
+        c, _ = _run(A, 0, ta, B, 0, tb, big, big)
+        want = _run_tn(A, 0, B, 0, big, big)
+        assert torch.equal(want.view(torch.int16), c.view(torch.int16))
+        assert c.float().abs().max().item() > 0
+        y, S = oracle.gemm_tn(A, 0, B, 0, big, big)
+        assert_gemm_close(c, y, S, "tiny")
