@@ -253,3 +253,55 @@ def test_degenerate_scales_and_all_zero_operands_with_t_major_operands():
         assert c.float().abs().max().item() > 0
         y, S = oracle.gemm_tn(A, 0, B, 0, big, big)
         assert_gemm_close(c, y, S, "tiny")
+
+
+def test_step_without_transposed_copies_replays_from_a_graph():
+    """The benchmark's side-figure step on config 2 (just-in-time scaling, row-major FP8 copies only, backward
+    GEMMs on T-major operands, compact workspaces): the same bytes run after run, from a captured HIP graph
+    replayed with eager work in between, and the same outputs as the step with transposed copies."""
+    cfg = synth.CONFIGS[2]
+    states = []
+    for li, lin in enumerate(cfg.linears):
+        M, K, N = cfg.M, lin.K, lin.N
+        states.append(dict(M=M, K=K, N=N, X=synth.make_x(cfg, li, device=DEV), W=synth.make_w(cfg, li, device=DEV),
+                           dY=synth.make_dy(cfg, li, device=DEV),
+                           ws=torch.zeros(llmq.llmq_fp8_linear_workspace_bytes(M, N, K), dtype=torch.uint8, device=DEV),
+                           f=torch.zeros(8, dtype=torch.float32, device=DEV),
+                           Y=torch.empty((M, N), dtype=torch.bfloat16, device=DEV),
+                           dX=torch.empty((M, K), dtype=torch.bfloat16, device=DEV),
+                           dW=torch.empty((N, K), dtype=torch.bfloat16, device=DEV)))
+
+    def step(flag):
+        for s in states:
+            M, K, N, f = s["M"], s["K"], s["N"], s["f"]
+            ws = s["ws"][:llmq.llmq_fp8_linear_workspace_bytes_no_transpose(M, N, K)] if flag else s["ws"]
+            llmq.llmq_fp8_linear_fwd(s["X"], s["W"], M, N, K, f[1:2], f[3:4], s["Y"], f[6:7], ws, flag | llmq.JIT_X | llmq.JIT_W)
+            llmq.llmq_fp8_linear_dgrad(s["dY"], None, M, N, K, f[5:6], f[3:4], 1, s["dX"], f[7:8], ws, flag | llmq.REUSE_W | llmq.JIT_DY)
+            llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, f[5:6], f[1:2], 1, s["dW"], False, ws, flag | llmq.REUSE_X | llmq.REUSE_DY)
+
+    def snapshot(keys=("Y", "dX", "dW", "f")):
+        torch.cuda.synchronize()
+        return [s[k].clone() for s in states for k in keys]
+
+    def scrub():
+        for s in states:
+            for k in ("Y", "dX", "dW", "f"):
+                s[k].zero_()
+
+    def same(a, b):
+        return all(torch.equal(x.view(torch.uint8), y.view(torch.uint8)) for x, y in zip(a, b))
+
+    step(0)
+    with_copies = snapshot()
+    scrub()
+    step(llmq.NO_TRANSPOSE)
+    ref = snapshot()
+    assert same(with_copies, ref)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step(llmq.NO_TRANSPOSE)
+    for rep in range(3):
+        scrub()
+        torch.cuda.synchronize()
+        g.replay()
+        assert same(ref, snapshot()), "graph replay %d differs" % rep
