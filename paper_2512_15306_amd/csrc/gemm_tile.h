@@ -165,9 +165,9 @@ __device__ inline void interleave() {
 //     bytes of row k0 + s / 2 (the two lanes of a pair at the two halves of 16 consecutive bytes), and the
 //     hardware hands lane i the byte of column i of each of the eight rows, in row order.  So lane i holds
 //     contraction bytes k0 .. k0 + 7 of operand row r0 + i, the same order as in the other layout, and the
-//     two layouts mix freely in one MFMA.  The 16-byte unit index of LDS row k is XOR-ed with k & 7 (with
-//     (k >> 2) & 1 for 192-byte rows, which have no room for three bits), again on the global side of the
-//     load: the eight rows one transposing read touches then lie in eight different groups of four banks.
+//     two layouts mix freely in one MFMA.  The 16-byte unit index of an LDS row is XOR-ed with a mask that
+//     depends on the row (swizzle_of_row), again on the global side of the load, so that the rows one
+//     transposing read touches lie in different banks.
 template <int NX, bool TMAJOR>
 struct SlabShape {
     static constexpr int kRows = 64 * NX;                     // operand rows (output rows or columns) of the tile
@@ -176,7 +176,10 @@ struct SlabShape {
     static constexpr int kPeriodRows = 64 * kPeriod / kUnits;           // T-major: slab rows per pattern
     static constexpr int kReadsPerFrag = TMAJOR ? 4 : 2;
     static constexpr int kLines = TMAJOR ? (kRows + 127) / 128 : 1;     // 128-byte lines per memory row of a slab
-    __device__ static int swizzle_of_row(int k) { return NX == 3 ? (k >> 2) & 1 : k & 7; }
+    // XOR mask of the 16-byte unit index of LDS row k.  One transposing read of 32 lanes touches 8 consecutive
+    // rows x 2 neighbouring units (x 2 halves); the mask moves in steps of two units so that these 16 units fall
+    // into 16 different groups of four banks: rows are 64 / 48 / 32 banks long for NX = 4 / 3 / 2.
+    __device__ static int swizzle_of_row(int k) { return (NX == 4 ? k & 7 : NX == 2 ? (k >> 1) & 3 : (k >> 2) & 1) << 1; }
 };
 
 template <int FA, int FB, int NI, int NJ, bool ACCUM, class V = GemmTuning, bool TA = false, bool TB = false>
