@@ -23,7 +23,7 @@
 //     conversion, takes the output absmax on the rounded bits, stages the wave's quadrant in LDS
 //     and stores full row segments, 16 bytes per lane;
 //   - workgroup ids are dealt round-robin to the 8 XCDs by the hardware, so ids are remapped to give
-//     each XCD (own L2) a contiguous range of tiles, walked in bands 8 tile-rows high;
+//     each XCD (own L2) a contiguous range of tiles, walked in bands 4 tile-rows high;
 //   - the host picks NI x NJ per problem so that the tiles fill the 256 CUs in whole rounds.
 // Generic kernel: any shape, one wavefront per 16x16 outputs, guarded loads; slow, for tests and
 // odd sizes.
@@ -47,7 +47,7 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 constexpr int BK = 128;
 constexpr int kGemmThreads = 256;
 constexpr int kXcds = 8;
-constexpr int kBandRows = 8;
+constexpr int kBandRows = 4;
 
 __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
     // raw buffer, no stride; out-of-range reads return zero instead of faulting
@@ -76,10 +76,6 @@ constexpr int kSchedMfma = 0x008, kSchedVmemRead = 0x020, kSchedDsRead = 0x100;
 struct GemmTuning {
     // Whether the kernel contains the L2 touch loads at all (their distance is a run-time argument).
     static constexpr bool kTouch = true;
-    // One workgroup touches 1 / kTouchShareA of the lines of its A slab and 1 / kTouchShareB of its B
-    // slab: the workgroups that run side by side on an XCD (4 tile columns x 8 tile rows at a time)
-    // share each slab and cover it together.
-    static constexpr int kTouchShareA = 4, kTouchShareB = 8;
     // Fragment reads ride along with the first 1 / kDsSpread of a half step's MFMAs (4 x 4 tiles) or
     // 1 / kDsSpreadSmall (smaller tiles: fewer MFMAs per read, and three reads per MFMA slot from four waves
     // are more than the LDS delivers; measured +1-4 % on 4 x 3, while 4 x 4 loses 1-4 % on whole rounds with
@@ -187,7 +183,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ C,
     int Cn, int T, const float* __restrict__ d_sA, const float* __restrict__ d_sB,
     unsigned* __restrict__ amax_bits, int tiles_r, int tiles_c, int touch_ahead, int band_rows, int next_stride,
-    int ldA, int ldB) {
+    int ldA, int ldB, int share_a, int share_b) {
     static_assert(!(TA || TB) || (FA != kFmtBf16 && FB != kFmtBf16), "the transposing reads move single bytes");
     constexpr int BM = 64 * NI, BN = 64 * NJ;
     typedef SlabShape<NI, TA> SA;
@@ -335,15 +331,19 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     // steps ahead of the direct-to-LDS loads (touch_ahead <= 0: nothing is fetched).  All CUs of an
     // XCD walk K in lock-step, so without this every slab is first requested only ~1.5 steps before
     // it is needed, less than a miss to HBM takes when the operands are not in the last-level cache.
-    // The workgroup touches rows [g * BM / shareA, (g + 1) * BM / shareA) of the A slab, g = tile
-    // column mod shareA, and likewise of the B slab with the tile row and shareB; each wave takes a quarter.
+    // The workgroups that run side by side on an XCD (band_rows tile rows x the tile columns that fit) share
+    // each slab: a workgroup touches the lines [g * n / share, (g + 1) * n / share) of the n lines of its A slab,
+    // g = tile column mod share_a, and likewise of its B slab with the tile row and share_b (the host picks the
+    // shares); each wave takes a quarter of that.
     constexpr bool kTouch = V::kTouch;
-    constexpr int kShareA = V::kTouchShareA, kShareB = V::kTouchShareB;
     // (T-major operand: the slab is 128 memory rows of kLines lines each, shared out the same way.)
-    constexpr int kRowsA = (TA ? BK * SA::kLines : BM) / kShareA / 4, kRowsB = (TB ? BK * SB::kLines : BN) / kShareB / 4;   // lines per wave
-    const int touch_lineA = ((tc % kShareA) * 4 + wave) * kRowsA + lane, touch_lineB = ((tr % kShareB) * 4 + wave) * kRowsB + lane;
-    const int touch_voffA = lane >= kRowsA ? kOutOfRange : TA ? (touch_lineA / SA::kLines) * ldA + (touch_lineA % SA::kLines) * 128 : touch_lineA * T;
-    const int touch_voffB = lane >= kRowsB ? kOutOfRange : TB ? (touch_lineB / SB::kLines) * ldB + (touch_lineB % SB::kLines) * 128 : touch_lineB * T;
+    constexpr int kLinesOfA = TA ? BK * SA::kLines : BM, kLinesOfB = TB ? BK * SB::kLines : BN;
+    const int per_wave_a = (kLinesOfA + share_a * 4 - 1) / (share_a * 4), per_wave_b = (kLinesOfB + share_b * 4 - 1) / (share_b * 4);
+    const int touch_lineA = ((tc % share_a) * 4 + wave) * per_wave_a + lane, touch_lineB = ((tr % share_b) * 4 + wave) * per_wave_b + lane;
+    const int touch_voffA = (lane >= per_wave_a || touch_lineA >= kLinesOfA) ? kOutOfRange
+                            : TA ? (touch_lineA / SA::kLines) * ldA + (touch_lineA % SA::kLines) * 128 : touch_lineA * T;
+    const int touch_voffB = (lane >= per_wave_b || touch_lineB >= kLinesOfB) ? kOutOfRange
+                            : TB ? (touch_lineB / SB::kLines) * ldB + (touch_lineB % SB::kLines) * 128 : touch_lineB * T;
     int touchA[2] = {0, 0}, touchB[2] = {0, 0};   // results are only kept so that the loads stay tracked
     int touch_sink = 0;
 
@@ -615,15 +615,24 @@ static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C
     // (measured: +3 % on a GEMM of 19 rounds of tiles, whose later workgroups otherwise start on cold
     // operands; nothing or slightly less on GEMMs of 2-4 rounds, so it is used from 6 rounds on)
     const int slots = (num_cus / kXcds) * kXcds * ((NI == 2 && NJ == 2) ? 2 : 1);
+    // Touch shares (LLMQ_GEMM_SHARE_A / _B override them): the band_rows tile rows that run side by side on an
+    // XCD cover a B slab together, each a different part.  Of the tile columns side by side (the XCD's workgroups
+    // / band_rows: 8 at band height 4) four cover an A slab together, so every A line is requested by two
+    // workgroups: they are not in lock step, and a line that only a straggler would request comes late.
+    const int band = band_rows();
+    int share_b = band < tiles_r ? band : tiles_r;
+    int share_a = 4 < tiles_c ? 4 : tiles_c;
+    if (const char* e = getenv("LLMQ_GEMM_SHARE_A")) { const int v = atoi(e); if (v >= 1 && v <= 64) share_a = v; }
+    if (const char* e = getenv("LLMQ_GEMM_SHARE_B")) { const int v = atoi(e); if (v >= 1 && v <= 64) share_b = v; }
     const int next_stride = touch_next(nt >= 6 * slots) ? slots : 0;
     if (accumulate)
         hipLaunchKernelGGL((gemm_tile_kernel<FA, FB, NI, NJ, true, GemmTuning, TA, TB>), dim3(grid), dim3(kGemmThreads), 0, stream,
                            A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c,
-                           touch, band_rows(), next_stride, (int)R, (int)C);
+                           touch, band, next_stride, (int)R, (int)C, share_a, share_b);
     else
         hipLaunchKernelGGL((gemm_tile_kernel<FA, FB, NI, NJ, false, GemmTuning, TA, TB>), dim3(grid), dim3(kGemmThreads), 0, stream,
                            A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c,
-                           touch, band_rows(), next_stride, (int)R, (int)C);
+                           touch, band, next_stride, (int)R, (int)C, share_a, share_b);
 }
 
 
