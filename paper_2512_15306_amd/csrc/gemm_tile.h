@@ -578,10 +578,12 @@ struct TileChoice {
 };
 TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus);
 
-// Distance of the L2 touch loads in K steps; LLMQ_GEMM_TOUCH overrides it for tuning.
+// Distance of the L2 touch loads in K steps beyond the slab the direct-to-LDS loads are fetching (measured with
+// bands 4 high on the block configurations: 1 is 0.5-0.8 % faster than 2, 3 and 4 lose 1.5 % and 4 %);
+// LLMQ_GEMM_TOUCH overrides it for tuning.
 inline int touch_ahead() {
     if (const char* e = getenv("LLMQ_GEMM_TOUCH")) return atoi(e);
-    return 2;
+    return 1;
 }
 
 // Height of the bands of tiles, in tile rows; LLMQ_GEMM_BAND overrides it for tuning.
