@@ -28,7 +28,7 @@ PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E, published
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by a plain 1 GiB copy
 # (profiles/bench_config<N>_gemm_quantize_amax.md); None where not measured.  They include hits in the
 # memory-side last-level cache: the 8 XCDs have private L2s and each re-reads the operands of its tiles.
-MEASURED_GEMM_TRAFFIC_BYTES = {2: 222.8e6, 3: 1022.3e6, 5: 3964.9e6}
+MEASURED_GEMM_TRAFFIC_BYTES = {2: 222.8e6, 3: 986.6e6, 5: 3792.3e6}
 
 
 def parse():
