@@ -290,6 +290,36 @@ def test_all_tile_shapes_give_the_same_bytes_run_after_run():
         assert np.all(np.abs(got - y) <= GEMM_TOL * S)
 
 
+def test_tile_walk_and_touch_settings_do_not_change_any_byte(monkeypatch):
+    """Band height of the tile walk, shares and distance of the L2 touch loads (tuning overrides) only move
+    loads whose results are dropped and change which workgroup computes which tile: outputs and the fused absmax
+    stay the same for every setting, on row-wise and T-major operands, with a ragged last band (9 tile rows)."""
+    R, C, T = 9 * 256, 5 * 256, 896
+    A = _rand_codes((R, T), 1, 31)
+    B = _rand_codes((C, T), 0, 32)
+    Ad, Bd = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    At, Bt = Ad.t().contiguous(), Bd.t().contiguous()
+    dsa, dsb = _scales(1.3, 0.9)
+    monkeypatch.setenv("LLMQ_GEMM_TILE", "4x4")
+
+    def run(ta, tb):
+        c = torch.full((R, C), float("nan"), dtype=torch.bfloat16, device=DEV)
+        am = torch.full((1,), -1.0, dtype=torch.float32, device=DEV)
+        llmq.llmq_fp8_gemm(At if ta else Ad, 1, ta, Bt if tb else Bd, 0, tb, dsa, dsb, c, False, am)
+        return c, am
+
+    ref, ref_am = run(False, False)
+    y, S = oracle.gemm_tn(A, 1, B, 0, 1.3, 0.9)
+    assert_gemm_close(ref, y, S, "default walk")
+    for band, sa, sb, touch in [(1, 1, 1, 0), (2, 64, 64, 1), (8, 4, 8, 2), (64, 2, 3, 5), (3, 5, 7, 9)]:
+        for k, v in (("LLMQ_GEMM_BAND", band), ("LLMQ_GEMM_SHARE_A", sa), ("LLMQ_GEMM_SHARE_B", sb), ("LLMQ_GEMM_TOUCH", touch)):
+            monkeypatch.setenv(k, str(v))
+        for ta, tb in ((False, False), (False, True), (True, True)):
+            c, am = run(ta, tb)
+            assert torch.equal(c.view(torch.int16), ref.view(torch.int16)), (band, sa, sb, touch, ta, tb)
+            assert f32_bits(am) == f32_bits(ref_am)
+
+
 @pytest.mark.parametrize("shape", [(256, 512, 1024), (272, 400, 528), (33, 17, 5), (4096, 1024, 768)])
 @pytest.mark.parametrize("fmt_dy", [1, 0])
 def test_just_in_time_scaling_inside_the_linear_calls(shape, fmt_dy):
