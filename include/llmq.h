@@ -115,11 +115,11 @@ int llmq_fp8_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB,
  * copies the forward pass made:
  *   dX[m,k] = sum_n dYq[m,n] Wq[n,k]   : A = dYq [M,N],            B = Wq [N,K] T-major, T = N
  *   dW[n,k] = sum_m dYq[m,n] Xq[m,k]   : A = dYq [M,N] T-major,    B = Xq [M,K] T-major, T = M
- * Tuned for B in E4M3 with R, C multiples of 128 and T a multiple of 128; other cases take a slow generic
- * kernel.  In the tuned kernel (and likewise in the generic one) every product lands in the same accumulator
+ * Tuned for B in E4M3 with R, C multiples of 128, T a multiple of 128 and T-major operands below 2 GiB; other
+ * cases take a slow generic kernel.  In the tuned kernel (and likewise in the generic one) every product lands in the same accumulator
  * position as with transposed copies, so the result is bit-identical to llmq_fp8_gemm_tn on those copies
- * whenever both calls run the same kind of kernel, which is the case for everything the linear calls below
- * launch.  Arguments otherwise as above.
+ * whenever both calls run the same kind of kernel, which is the case for what the linear calls below launch
+ * on operands below 2 GiB.  Arguments otherwise as above.
  */
 int llmq_fp8_gemm(const uint8_t* A, int fmtA, int a_t_major, const uint8_t* B, int fmtB, int b_t_major,
                   int64_t R, int64_t C, int64_t T,
