@@ -328,9 +328,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     const int nk = T / BK;
 
     // L2 touch loads: a wave reads the first dword of some rows of a slab that is still touch_ahead
-    // steps ahead of the direct-to-LDS loads (touch_ahead <= 0: nothing is fetched).  All CUs of an
-    // XCD walk K in lock-step, so without this every slab is first requested only ~1.5 steps before
-    // it is needed, less than a miss to HBM takes when the operands are not in the last-level cache.
+    // steps ahead of the direct-to-LDS loads (touch_ahead <= 0: nothing is fetched).  The CUs of an XCD
+    // start their tiles together and walk K at about the same pace, so without this every slab is first
+    // requested only ~1.5 steps before it is needed, less than a miss to HBM takes when the operands are
+    // not in the last-level cache.
     // The workgroups that run side by side on an XCD (band_rows tile rows x the tile columns that fit) share
     // each slab: a workgroup touches the lines [g * n / share, (g + 1) * n / share) of the n lines of its A slab,
     // g = tile column mod share_a, and likewise of its B slab with the tile row and share_b (the host picks the
