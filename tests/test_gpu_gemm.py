@@ -213,7 +213,7 @@ def _sample_positions(R, C, n, seed, tile=256):
 
 @pytest.mark.parametrize("cfg_i,li", [(c, l) for c in (2, 3, 4, 5) for l in range(4)])
 def test_full_size_linears_on_sampled_outputs(cfg_i, li):
-    """BASELINE shapes in the launch configuration bench.py times; the oracle computes >= 4096 random
+    """The benchmark configurations' shapes in the launch configuration bench.py times; the oracle computes >= 4096 random
     outputs plus tile-boundary rows and columns of each of the three GEMMs with full-length dot
     products; quantized operands are compared in full."""
     cfg = synth.CONFIGS[cfg_i]
