@@ -55,15 +55,16 @@ const char* llmq_status_string(int status);
 int llmq_version(void);
 
 /*
- * Absmax and scale of a BF16 tensor (Section 3 "Overview": "determine the largest absolute value in
- * each tensor, and then rescale so that this is mapped to the largest representable value").
+ * Absmax and scale of a BF16 tensor (Section 3 "Overview": tensor-level absmax scaling, the scale maps the
+ * tensor's largest magnitude onto the largest finite value of the FP8 format).
  *   x_bf16   [n] BF16, device, 16-byte aligned; n >= 1.
  *   fmt      target FP8 format, selects FMAX (448 or 57344) for the scale.
  *   d_amax   [1] float, device, written: max_i |x_i| exactly; the canonical quiet NaN 0x7FC00000 if the
  *            tensor holds a NaN; +Inf if it holds an Inf and no NaN.
  *   d_scale  [1] float, device, written if not NULL: min(FMAX / amax, FLT_MAX) with one IEEE binary32
- *            division, so FLT_MAX for an all-zero tensor (every code is then +-0) and for an absmax so
- *            small that the quotient overflows; 0 when amax is +Inf; NaN when amax is NaN.
+ *            division (FLT_MAX for an absmax so small that the quotient overflows); 1 for an all-zero
+ *            tensor, where the rule defines no scale and every code is +-0 whatever the scale; 0 when amax
+ *            is +Inf; NaN when amax is NaN.
  *   ws       device scratch of at least llmq_amax_workspace_bytes() bytes, 4-byte aligned; contents on
  *            entry do not matter, it holds per-block partial results between the two launches (a
  *            streaming reduction, then a one-block kernel that reduces the partial results and writes
@@ -75,7 +76,8 @@ int llmq_amax(const void* x_bf16, size_t n, int fmt, float* d_amax, float* d_sca
               void* ws, size_t ws_bytes, void* stream);
 
 /*
- * Fused scale + FP8 cast + transposed copy (Section 3: "a fused transpose+quantize kernel").
+ * Fused scale + FP8 cast + transposed copy (Section 3, kernel-fusion paragraph: quantization and the
+ * transposition the backward GEMMs need are one kernel).
  *   q[i,j]   = cast( fl32( fl32(x[i,j]) * d_scale[0] ) ),  q_t[j,i] = q[i,j]
  * cast = round-to-nearest-even onto the FP8 grid, saturating at +-FMAX (a finite product never yields
  * an Inf or NaN code).  The result for NaN inputs is unspecified.
@@ -202,7 +204,7 @@ int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, i
 
 /*
  * Scale from an absmax that a fused producer left on the device (the d_amax_* outputs of the calls above):
- *   d_scale[0] = min(FMAX(fmt) / d_amax[0], FLT_MAX), the same rule and rounding as llmq_amax.
+ *   d_scale[0] = min(FMAX(fmt) / d_amax[0], FLT_MAX), 1 if d_amax[0] == 0: the same rule and rounding as llmq_amax.
  */
 int llmq_scale_from_amax(const float* d_amax, int fmt, float* d_scale, void* stream);
 

@@ -19,8 +19,9 @@
  *
  * Readings where the paper is silent (listed in the design notes as well):
  *   scale  s = min(fl32(FMAX / amax), FLT_MAX): one IEEE binary32 division, whose
- *          overflow (tiny amax, and amax == 0 where the quotient is +Inf) is
- *          clamped to the largest finite binary32;
+ *          overflow (a tiny amax) is clamped to the largest finite binary32;
+ *          s = 1 for amax == 0, where "map the absmax onto FMAX" defines no
+ *          scale and every scale gives the same codes (all +-0);
  *   value  p = fl32(fl32(x) * s), one binary32 multiplication, not fused;
  *   cast   round-to-nearest-even onto the FP8 grid, saturating to +-FMAX
  *          (never produces an Inf or NaN code from a finite p); NaN -> S.1111111;
@@ -166,8 +167,10 @@ float oracle_amax_bf16(const uint16_t* x, size_t n) {
 float oracle_scale(float amax, int fmt) {
     volatile float num = (float)oracle_fp8_max(fmt);
     volatile float den = amax;
-    volatile float s = num / den;          /* one binary32 division */
-    if (isinf(s)) s = FLT_MAX;
+    volatile float s;
+    if (amax == 0.0f) return 1.0f;         /* all-zero tensor: the rule defines no scale, every code is +-0 */
+    s = num / den;                         /* one binary32 division */
+    if (isinf(s)) s = FLT_MAX;             /* a tiny absmax: the quotient overflows */
     return s;
 }
 

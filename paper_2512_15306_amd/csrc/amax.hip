@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kAmaxThreads) void amax_partial_kernel(
     if (threadIdx.x == 0) partial[blockIdx.x] = m;
 }
 
-// amax = max over the partial results (NaN made canonical), scale = min(FMAX / amax, FLT_MAX)
+// amax = max over the partial results (NaN made canonical), scale = scale_of_amax(amax, FMAX)
 __global__ __launch_bounds__(kAmaxThreads) void amax_final_kernel(
     const unsigned* __restrict__ partial, int n_partial, float* __restrict__ d_amax,
     float* __restrict__ d_scale, float fmax) {
@@ -68,11 +68,7 @@ __global__ __launch_bounds__(kAmaxThreads) void amax_final_kernel(
     if (threadIdx.x == 0) {
         const float a = __uint_as_float(amax_bits_from_bf16_mag(m));
         *d_amax = a;
-        if (d_scale) {
-            float s = fmax / a;                                   // one correctly rounded division
-            if (__builtin_isinf(s)) s = 3.402823466e+38f;         // all-zero tensor or a tiny absmax
-            *d_scale = s;
-        }
+        if (d_scale) *d_scale = scale_of_amax(a, fmax);
     }
 }
 
@@ -113,18 +109,12 @@ __global__ __launch_bounds__(kAmaxWideThreads) void amax_final_wide_kernel(
     if (threadIdx.x == 0) {
         const float a = __uint_as_float(amax_bits_from_bf16_mag(m));
         *d_amax = a;
-        if (d_scale) {
-            float s = fmax / a;
-            if (__builtin_isinf(s)) s = 3.402823466e+38f;
-            *d_scale = s;
-        }
+        if (d_scale) *d_scale = scale_of_amax(a, fmax);
     }
 }
 
 __global__ void scale_from_amax_kernel(const float* __restrict__ d_amax, float* __restrict__ d_scale, float fmax) {
-    float s = fmax / *d_amax;
-    if (__builtin_isinf(s)) s = 3.402823466e+38f;
-    *d_scale = s;
+    *d_scale = scale_of_amax(*d_amax, fmax);
 }
 
 int launch_scale_from_amax(const float* d_amax, int fmt, float* d_scale, hipStream_t stream) {

@@ -66,12 +66,20 @@ __device__ inline unsigned block_max_u32(unsigned m, unsigned* s_part) {
     return m;
 }
 
-// scale = min(fmax / amax, FLT_MAX) from a BF16 magnitude pattern, as the absmax second stage computes it
-__device__ inline float scale_from_mag(unsigned mag16, float fmax) {
-    const float a = __uint_as_float(amax_bits_from_bf16_mag(mag16));
-    float s = fmax / a;                                   // one correctly rounded division
-    if (__builtin_isinf(s)) s = 3.402823466e+38f;
+// The scale of a tensor whose absmax is a (paper Section 3 "Overview": the absmax is mapped onto the largest
+// finite FP8 value): fmax / a with one correctly rounded binary32 division, FLT_MAX when that quotient
+// overflows (a tiny absmax), and 1 for an all-zero tensor, where the rule defines nothing and every scale
+// gives the same codes (+-0): the neutral scale keeps the de-scaling exact and stays usable as a kept statistic.
+// a = +Inf gives 0, a = NaN gives NaN.
+__device__ inline float scale_of_amax(float a, float fmax) {
+    float s = fmax / a;
+    if (__builtin_isinf(s)) s = a == 0.0f ? 1.0f : 3.402823466e+38f;
     return s;
+}
+
+// The same from a BF16 magnitude pattern, as the absmax second stage computes it
+__device__ inline float scale_from_mag(unsigned mag16, float fmax) {
+    return scale_of_amax(__uint_as_float(amax_bits_from_bf16_mag(mag16)), fmax);
 }
 
 // The scale of a 256-lane workgroup's launch; all lanes of the workgroup must call it.

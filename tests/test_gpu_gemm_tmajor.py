@@ -237,7 +237,7 @@ def test_request_of_the_next_tiles_slabs_with_t_major_operands(ta, tb, monkeypat
 
 
 def test_degenerate_scales_and_all_zero_operands_with_t_major_operands():
-    """An all-zero operand quantized with the FLT_MAX scale, and a scale product that leaves the normal range
+    """An all-zero operand with the largest finite scale (a tiny absmax gives it), and a scale product that leaves the normal range
     (second copy of the epilogue), in the T-major instantiations."""
     R, C, T = 256, 256, 256
     A = _rand_codes((R, T), 0, 81)

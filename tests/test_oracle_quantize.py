@@ -46,8 +46,8 @@ def test_amax_matches_library_max():
 
 @pytest.mark.parametrize("fmt,tdtype,fmax,maxcode", FMTS)
 def test_scale_rule(fmt, tdtype, fmax, maxcode):
-    # all-zero tensor: FMAX / 0 = +Inf, clamped like every overflowing quotient
-    assert float(oracle.scale(0.0, fmt)) == float(np.finfo(np.float32).max)
+    # all-zero tensor: the rule defines no scale; the neutral one is taken (-0.0 is zero too)
+    assert float(oracle.scale(0.0, fmt)) == 1.0 and float(oracle.scale(np.float32(-0.0), fmt)) == 1.0
     # powers of two: FMAX * 2^j maps with an exact power-of-two scale
     for j in range(-20, 20):
         assert float(oracle.scale(fmax * 2.0 ** j, fmt)) == 2.0 ** (-j)
@@ -119,7 +119,10 @@ def test_quantize_all_zero_and_given_scale(fmt, tdtype, fmax, maxcode):
     z[2, 3] = 0x8000
     s = oracle.scale(oracle.amax_bf16(z), fmt)
     q, qt = oracle.quantize(z, s, fmt)
-    assert float(s) == float(np.finfo(np.float32).max) and q[2, 3] == 0x80 and np.count_nonzero(q) == 1
+    assert float(s) == 1.0 and q[2, 3] == 0x80 and np.count_nonzero(q) == 1
+    # every finite positive scale gives these same codes: the choice at absmax 0 cannot change a byte
+    for other in (np.float32(np.finfo(np.float32).max), np.float32(2.0 ** -100)):
+        assert np.array_equal(oracle.quantize(z, other, fmt)[0], q)
     # a scale that is too large saturates instead of overflowing to Inf/NaN codes
     x = _rand_bf16((16, 16), 12, 1.0)
     q, _ = oracle.quantize(_bits(x), np.float32(1e6), fmt)
