@@ -29,6 +29,8 @@ PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E, published
 # (profiles/bench_config<N>_gemm_quantize_amax.md); None where not measured.  They include hits in the
 # memory-side last-level cache: the 8 XCDs have private L2s and each re-reads the operands of its tiles.
 MEASURED_GEMM_TRAFFIC_BYTES = {2: 222.8e6, 3: 986.6e6, 5: 3792.3e6}
+HEADLINE_CONFIG = 5           # the largest single-GPU configuration (32B-class block)
+SIDE_CONFIGS = (3, 4)         # 7B- and 14B-class blocks: reported in the same line
 
 
 def parse():
@@ -36,7 +38,9 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=20)
     p.add_argument("--warmup", type=int, default=5)
-    p.add_argument("--config", type=int, default=2, help="benchmark config index (2 = 3B-class block ... 5 = 32B-class)")
+    p.add_argument("--config", type=int, default=0,
+                   help="benchmark config index (2 = 3B-class block ... 5 = 32B-class); default: config 5 as the "
+                        "headline with configs 3 and 4 (the other shapes the target is quoted on) as side entries")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--prequantized-w", action="store_true",
                    help="weights quantized once outside the timed region (reused across micro-steps)")
@@ -294,6 +298,81 @@ def cpu_baseline(cfg):
                       "quantize+transpose and fp64 fwd/dgrad/wgrad" % (cfg.index, lin.name, lin.K, lin.N, Ms, cfg.M)}
 
 
+def measure_config(cfg, args, dev, full):
+    """One configuration: the timed step (args.warmup untimed, args.steps timed), then the GEMM launches alone
+    (the roofline of the dominant kernel) and the absmax / quantize legs on the same operands.  full: also
+    the side figures (no transposed copies, producer-fused absmax).  Returns a dict of raw figures."""
+    import torch
+    from paper_2512_15306_amd import llmq, synth
+    states = [LinearState(cfg, li, dev) for li in range(len(cfg.linears))]
+    if args.prequantized_w:
+        for s in states:
+            llmq.llmq_amax(s.W, llmq.E4M3, s.aw, s.sw, s.aws)
+            llmq.llmq_quantize_fp8(s.W, s.sw, llmq.E4M3, s.view(2), s.view(3))
+    for _ in range(args.warmup):
+        run_step(states, args.prequantized_w)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ms_step = timed(lambda: run_step(states, args.prequantized_w), args.steps)
+    wall = (time.perf_counter() - t0) * 1e3 / args.steps
+    flops = float(synth.linear_flops(cfg))
+    # dominant kernel: the FP8 GEMM (three launches per linear), timed alone on the same operands
+    reps = max(3, min(args.steps, 20))
+    r = {"cfg": cfg, "flops": flops, "ms_step": ms_step, "wall": wall, "reps": reps, "n_gemm": 3 * len(states),
+         "elements": float(synth.quantize_elements(cfg))}
+    r["ms_gemm"] = timed(lambda: run_gemms_only(states), reps)
+    r["ms_quant"] = timed(lambda: run_quant_only(states), reps)
+    r["ms_amax"] = timed(lambda: run_amax_only(states), reps)
+    r["ms_qk"] = timed(lambda: run_quantize_kernel_only(states), reps)
+    if full:
+        r["ms_fused"] = timed(lambda: run_step(states, args.prequantized_w, producer_absmax=True), reps)
+        r["ms_qrow"] = timed(lambda: run_quantize_row_major_only(states), reps)
+        # the same step on row-major FP8 copies only (the backward GEMMs read them T-major): a side figure
+        run_step(states, args.prequantized_w, extra_flags=llmq.NO_TRANSPOSE)       # first use loads those kernels
+        r["ms_nt"] = timed(lambda: run_step(states, args.prequantized_w, extra_flags=llmq.NO_TRANSPOSE), reps)
+        r["ms_nt_gemm"] = timed(lambda: run_gemms_only(states, llmq.NO_TRANSPOSE), reps)
+        r["ms_nt_fused"] = timed(lambda: run_step(states, args.prequantized_w, producer_absmax=True, extra_flags=llmq.NO_TRANSPOSE), reps)
+    del states
+    torch.cuda.empty_cache()
+    return r
+
+
+def workload_name(cfg, prequantized_w):
+    return ("config %d: %s, M=%d tokens, linears %s; absmax + quantize(+transpose) of X, W, dY "
+            "(e4m3, e4m3, e5m2) and fwd+dgrad+wgrad per linear%s" % (
+                cfg.index, cfg.name, cfg.M, ", ".join("%s %dx%d" % (l.name, l.K, l.N) for l in cfg.linears),
+                "; W pre-quantized" if prequantized_w else ""))
+
+
+def roofline_of(r):
+    gemm_tflops = r["flops"] / (r["ms_gemm"] * 1e-3) / 1e12
+    return {"kernel": "gemm_tile_kernel", "bound": "mfma", "achieved": round(gemm_tflops, 2),
+            "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_FP8_TFLOPS, 4),
+            "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(r["cfg"].index), "launches_per_step": r["n_gemm"],
+            "avg_launch_ms": round(r["ms_gemm"] / r["n_gemm"], 5), "flops_per_launch": r["flops"] / r["n_gemm"]}
+
+
+def rate_fields(r):
+    """Whole-step and per-leg rates of one configuration (the fields the headline and the side entries share)."""
+    flops, n = r["flops"], r["elements"]
+    value = flops / (r["ms_step"] * 1e-3) / 1e12
+    gemm_tflops = flops / (r["ms_gemm"] * 1e-3) / 1e12
+    gbps = lambda bpe, ms: bpe * n / (ms * 1e-3) / 1e9
+    return {
+        "ms_per_step": round(r["ms_step"], 4),
+        "step_tflops": round(value, 2), "pct_fp8_peak": round(100.0 * value / PEAK_FP8_TFLOPS, 2),
+        "gemm_only_tflops": round(gemm_tflops, 2),
+        "gemm_only_pct_fp8_peak": round(100.0 * gemm_tflops / PEAK_FP8_TFLOPS, 2),
+        # absmax reads 2 B, quantize reads 2 B and writes 1 + 1 B per element
+        "quantize_gbps": round(gbps(6.0, r["ms_quant"]), 1),
+        "quantize_pct_hbm_peak": round(100.0 * gbps(6.0, r["ms_quant"]) / PEAK_HBM_GBPS, 2),
+        "absmax_only_gbps": round(gbps(2.0, r["ms_amax"]), 1),
+        "absmax_only_pct_hbm_peak": round(100.0 * gbps(2.0, r["ms_amax"]) / PEAK_HBM_GBPS, 2),
+        "quantize_kernel_only_gbps": round(gbps(4.0, r["ms_qk"]), 1),
+        "quantize_kernel_only_pct_hbm_peak": round(100.0 * gbps(4.0, r["ms_qk"]) / PEAK_HBM_GBPS, 2),
+    }
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -308,75 +387,43 @@ def main():
     llmq.lib()
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    cfg = synth.CONFIGS[args.config]
-    states = [LinearState(cfg, li, dev) for li in range(len(cfg.linears))]
+    cfg = synth.CONFIGS[args.config or HEADLINE_CONFIG]
     peaks = measure_peaks(dev)
-    if args.prequantized_w:
-        for s in states:
-            llmq.llmq_amax(s.W, llmq.E4M3, s.aw, s.sw, s.aws)
-            llmq.llmq_quantize_fp8(s.W, s.sw, llmq.E4M3, s.view(2), s.view(3))
-    for _ in range(args.warmup):
-        run_step(states, args.prequantized_w)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ms_step = timed(lambda: run_step(states, args.prequantized_w), args.steps)
-    wall = (time.perf_counter() - t0) * 1e3 / args.steps
-    ms_step = max(ms_step, 0.0)
-    flops = float(synth.linear_flops(cfg))
-    value = flops / (ms_step * 1e-3) / 1e12
-
-    # dominant kernel: the FP8 GEMM (three launches per linear), timed alone on the same operands
-    reps = max(3, min(args.steps, 20))
-    ms_gemm = timed(lambda: run_gemms_only(states), reps)
-    n_gemm = 3 * len(states)
-    gemm_tflops = flops / (ms_gemm * 1e-3) / 1e12
-    ms_quant = timed(lambda: run_quant_only(states), reps)
-    ms_amax = timed(lambda: run_amax_only(states), reps)
-    ms_qk = timed(lambda: run_quantize_kernel_only(states), reps)
-    ms_fused = timed(lambda: run_step(states, args.prequantized_w, producer_absmax=True), reps)
-    ms_qrow = timed(lambda: run_quantize_row_major_only(states), reps)
-    # the same step on row-major FP8 copies only (the backward GEMMs read them T-major): a side figure
-    run_step(states, args.prequantized_w, extra_flags=llmq.NO_TRANSPOSE)       # first use loads those kernels
-    ms_nt = timed(lambda: run_step(states, args.prequantized_w, extra_flags=llmq.NO_TRANSPOSE), reps)
-    ms_nt_gemm = timed(lambda: run_gemms_only(states, llmq.NO_TRANSPOSE), reps)
-    ms_nt_fused = timed(lambda: run_step(states, args.prequantized_w, producer_absmax=True, extra_flags=llmq.NO_TRANSPOSE), reps)
-    qbytes = 6.0 * synth.quantize_elements(cfg)         # absmax reads 2 B, quantize reads 2 B and writes 1 + 1 B
+    r = measure_config(cfg, args, dev, full=True)
+    flops, ms_step, ms_gemm, reps = r["flops"], r["ms_step"], r["ms_gemm"], r["reps"]
+    n = r["elements"]
+    rates = rate_fields(r)
+    gemm_tflops = rates["gemm_only_tflops"]
     out = {
         "metric": "FP8 linear fwd+bwd TFLOP/s and % dense-FP8 MFMA peak; quantize GB/s",
-        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_step, 4), "wall_ms_per_step": round(wall, 4), "higher_is_better": True,
+        "value": rates["step_tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": rates["ms_per_step"], "wall_ms_per_step": round(r["wall"], 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "fp8", "data": "synthetic",
-        "config": {"workload": "config %d: %s, M=%d tokens, linears %s; absmax + quantize(+transpose) of X, W, dY "
-                               "(e4m3, e4m3, e5m2) and fwd+dgrad+wgrad per linear%s" % (
-                                   cfg.index, cfg.name, cfg.M,
-                                   ", ".join("%s %dx%d" % (l.name, l.K, l.N) for l in cfg.linears),
-                                   "; W pre-quantized" if args.prequantized_w else "")},
-        "pct_fp8_peak": round(100.0 * value / PEAK_FP8_TFLOPS, 2),
-        "gemm_only_tflops": round(gemm_tflops, 2),
-        "gemm_only_pct_fp8_peak": round(100.0 * gemm_tflops / PEAK_FP8_TFLOPS, 2),
-        "quantize_gbps": round(qbytes / (ms_quant * 1e-3) / 1e9, 1),
-        "quantize_pct_hbm_peak": round(100.0 * qbytes / (ms_quant * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2),
-        "absmax_only_gbps": round(2.0 * synth.quantize_elements(cfg) / (ms_amax * 1e-3) / 1e9, 1),
-        "absmax_only_pct_hbm_peak": round(100.0 * 2.0 * synth.quantize_elements(cfg) / (ms_amax * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2),
-        "quantize_kernel_only_gbps": round(4.0 * synth.quantize_elements(cfg) / (ms_qk * 1e-3) / 1e9, 1),
-        "quantize_kernel_only_pct_hbm_peak": round(100.0 * 4.0 * synth.quantize_elements(cfg) / (ms_qk * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2),
-        "quantize_row_major_only_gbps": round(3.0 * synth.quantize_elements(cfg) / (ms_qrow * 1e-3) / 1e9, 1),
-        "quantize_row_major_only_pct_hbm_peak": round(100.0 * 3.0 * synth.quantize_elements(cfg) / (ms_qrow * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2),
-        "step_tflops_with_producer_fused_absmax": round(flops / (ms_fused * 1e-3) / 1e12, 2),
-        "step_tflops_without_transposed_copies": round(flops / (ms_nt * 1e-3) / 1e12, 2),
-        "gemm_only_tflops_without_transposed_copies": round(flops / (ms_nt_gemm * 1e-3) / 1e12, 2),
-        "step_tflops_without_transposed_copies_with_producer_fused_absmax": round(flops / (ms_nt_fused * 1e-3) / 1e12, 2),
+        "config": {"workload": workload_name(cfg, args.prequantized_w)},
+    }
+    out.update({k: v for k, v in rates.items() if k not in ("ms_per_step", "step_tflops")})
+    out.update({
+        "quantize_row_major_only_gbps": round(3.0 * n / (r["ms_qrow"] * 1e-3) / 1e9, 1),
+        "quantize_row_major_only_pct_hbm_peak": round(100.0 * 3.0 * n / (r["ms_qrow"] * 1e-3) / 1e9 / PEAK_HBM_GBPS, 2),
+        "step_tflops_with_producer_fused_absmax": round(flops / (r["ms_fused"] * 1e-3) / 1e12, 2),
+        "step_tflops_without_transposed_copies": round(flops / (r["ms_nt"] * 1e-3) / 1e12, 2),
+        "gemm_only_tflops_without_transposed_copies": round(flops / (r["ms_nt_gemm"] * 1e-3) / 1e12, 2),
+        "step_tflops_without_transposed_copies_with_producer_fused_absmax": round(flops / (r["ms_nt_fused"] * 1e-3) / 1e12, 2),
         "measured_peaks": peaks,
         "gemm_only_pct_measured_random_bits_peak": round(100.0 * gemm_tflops / peaks["mfma_fp8_random_bits_tflops"], 2),
-        "quantize_pct_measured_copy": round(100.0 * qbytes / (ms_quant * 1e-3) / 1e9 / peaks["hbm_copy_gbps"], 2),
-        "roofline": {"kernel": "gemm_tile_kernel", "bound": "mfma", "achieved": round(gemm_tflops, 2),
-                     "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_FP8_TFLOPS, 4),
-                     "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(cfg.index), "launches_per_step": n_gemm,
-                     "avg_launch_ms": round(ms_gemm / n_gemm, 5),
-                     "flops_per_launch": flops / n_gemm},
-    }
-    del states
-    torch.cuda.empty_cache()
+        "quantize_pct_measured_copy": round(100.0 * rates["quantize_gbps"] / peaks["hbm_copy_gbps"], 2),
+        "roofline": roofline_of(r),
+    })
+    if not args.config:
+        # the other shapes the target is quoted on, each timed the same way (same warm-up and step counts)
+        sides = {}
+        for ci in SIDE_CONFIGS:
+            rs = measure_config(synth.CONFIGS[ci], args, dev, full=False)
+            e = {"workload": workload_name(synth.CONFIGS[ci], args.prequantized_w)}
+            e.update(rate_fields(rs))
+            e["roofline"] = roofline_of(rs)
+            sides["config %d" % ci] = e
+        out["side_configs"] = sides
     ms_bf16 = measure_bf16_baseline(cfg, dev, reps)
     torch.cuda.empty_cache()
     bf16_tflops = flops / (ms_bf16 * 1e-3) / 1e12

@@ -113,7 +113,7 @@ TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus) {
     TileChoice best{0, 0};
     if (T % BK != 0 || T >= (1ll << 23)) return best;
     // Override for tests and tuning: LLMQ_GEMM_TILE=IxJ forces that wave tile where it divides the problem.
-    if (const char* force = getenv("LLMQ_GEMM_TILE")) {
+    if (const char* force = tuning_env("LLMQ_GEMM_TILE")) {
         const int ni = force[0] - '0', nj = force[0] && force[1] ? force[2] - '0' : 0;
         if (ni >= 2 && ni <= 4 && nj >= 2 && nj <= 4 && R % (64 * ni) == 0 && C % (64 * nj) == 0) return TileChoice{ni, nj};
     }

@@ -457,11 +457,13 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     const bool one_mul = inv_ab >= 1.17549435e-38f && inv_ab <= 3.402823466e+38f;
     const float m1 = one_mul ? inv_ab : inv_a;
     // The output absmax is taken in fp32 before rounding: rounding to BF16 is monotonic, so the BF16
-    // rounding of the largest |y| is the largest rounded magnitude.
+    // rounding of the largest |y| is the largest rounded magnitude.  The maximum is the IEEE 754-2019 one
+    // (v_maximum3_f32, two elements per instruction): a NaN output makes the absmax NaN, as it does for the
+    // absmax kernel run over the stored tensor.
     float maxabs = 0.0f;
     auto track4 = [&](const v4f& y) {
-        maxabs = __builtin_fmaxf(__builtin_fmaxf(maxabs, __builtin_fabsf(y[0])), __builtin_fabsf(y[1]));
-        maxabs = __builtin_fmaxf(__builtin_fmaxf(maxabs, __builtin_fabsf(y[2])), __builtin_fabsf(y[3]));
+        maxabs = __builtin_elementwise_maximum(__builtin_elementwise_maximum(maxabs, __builtin_fabsf(y[0])), __builtin_fabsf(y[1]));
+        maxabs = __builtin_elementwise_maximum(__builtin_elementwise_maximum(maxabs, __builtin_fabsf(y[2])), __builtin_fabsf(y[3]));
     };
     // The body exists twice, for one and for two de-scale multiplies; the choice is uniform over the grid.
     auto write_out = [&](auto two_mul) {
@@ -583,25 +585,25 @@ TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus);
 // bands 4 high on the block configurations: 1 is 0.5-0.8 % faster than 2, 3 and 4 lose 1.5 % and 4 %);
 // LLMQ_GEMM_TOUCH overrides it for tuning.
 inline int touch_ahead() {
-    if (const char* e = getenv("LLMQ_GEMM_TOUCH")) return atoi(e);
+    if (const char* e = tuning_env("LLMQ_GEMM_TOUCH")) return atoi(e);
     return 1;
 }
 
 // Height of the bands of tiles, in tile rows; LLMQ_GEMM_BAND overrides it for tuning.
 inline int band_rows() {
-    if (const char* e = getenv("LLMQ_GEMM_BAND")) { const int v = atoi(e); if (v >= 1 && v <= 64) return v; }
+    if (const char* e = tuning_env("LLMQ_GEMM_BAND")) { const int v = atoi(e); if (v >= 1 && v <= 64) return v; }
     return kBandRows;
 }
 
 // The same for 2 x 2 tiles, where two workgroups share a CU and already cover each other's waits.
 inline int touch_ahead_pair() {
-    if (const char* e = getenv("LLMQ_GEMM_TOUCH_PAIR")) return atoi(e);
+    if (const char* e = tuning_env("LLMQ_GEMM_TOUCH_PAIR")) return atoi(e);
     return 0;
 }
 
 // Whether a workgroup requests the first slabs of its successor; LLMQ_GEMM_TOUCH_NEXT=0 / 1 overrides it.
 inline bool touch_next(bool by_default) {
-    if (const char* e = getenv("LLMQ_GEMM_TOUCH_NEXT")) return atoi(e) != 0;
+    if (const char* e = tuning_env("LLMQ_GEMM_TOUCH_NEXT")) return atoi(e) != 0;
     return by_default;
 }
 
@@ -625,8 +627,8 @@ static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C
     const int band = band_rows();
     int share_b = band < tiles_r ? band : tiles_r;
     int share_a = 4 < tiles_c ? 4 : tiles_c;
-    if (const char* e = getenv("LLMQ_GEMM_SHARE_A")) { const int v = atoi(e); if (v >= 1 && v <= 64) share_a = v; }
-    if (const char* e = getenv("LLMQ_GEMM_SHARE_B")) { const int v = atoi(e); if (v >= 1 && v <= 64) share_b = v; }
+    if (const char* e = tuning_env("LLMQ_GEMM_SHARE_A")) { const int v = atoi(e); if (v >= 1 && v <= 64) share_a = v; }
+    if (const char* e = tuning_env("LLMQ_GEMM_SHARE_B")) { const int v = atoi(e); if (v >= 1 && v <= 64) share_b = v; }
     const int next_stride = touch_next(nt >= 6 * slots) ? slots : 0;
     if (accumulate)
         hipLaunchKernelGGL((gemm_tile_kernel<FA, FB, NI, NJ, true, GemmTuning, TA, TB>), dim3(grid), dim3(kGemmThreads), 0, stream,

@@ -3,8 +3,17 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 namespace llmq {
+
+// Tuning overrides come from the environment, for tests and tuning runs only: they are looked at when the
+// process started with LLMQ_TUNING=1 (read once) and ignored otherwise, so the product path never calls
+// getenv at launch.
+inline const char* tuning_env(const char* name) {
+    static const bool enabled = [] { const char* e = getenv("LLMQ_TUNING"); return e && e[0] == '1'; }();
+    return enabled ? getenv(name) : nullptr;
+}
 
 // Each returns 0 or LLMQ_ERR_DEVICE (-6).  Arguments are validated by the callers in api.hip.
 constexpr int kAmaxMaxPartials = 1024;      // the absmax workspace holds one 32-bit word per block

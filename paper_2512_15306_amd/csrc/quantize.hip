@@ -1,6 +1,6 @@
-// Fused scale + FP8 cast + transposed copy (paper Section 3: "a fused transpose+quantize kernel";
-// the FP8 GEMM wants both operands contraction-contiguous, so every quantized tensor is also
-// needed transposed in the backward pass).
+// Fused scale + FP8 cast + transposed copy (paper Section 3, kernel-fusion paragraph: quantization and
+// transposition are one kernel; the FP8 GEMM wants both operands contraction-contiguous, so every
+// quantized tensor is also needed transposed in the backward pass).
 //
 // HBM-bound: per element 2 bytes read, 1 byte written row-major and 1 byte written transposed.
 // Tuned kernel: one lane owns a 16-row x 8-column patch.  It reads the patch with sixteen 16-byte
@@ -172,7 +172,8 @@ static void launch_patch(const uint16_t* xb, int64_t rows, int64_t cols, const S
     dim3 grid(gr * gc);
     dim3 block(kQThreads);
     unsigned band = V::kBandBlocks;
-    if (const char* e = getenv("LLMQ_QUANT_BAND")) { const int v = atoi(e); if (v >= 1) band = (unsigned)v; }
+    if (const char* e = tuning_env("LLMQ_QUANT_BAND")) { const int v = atoi(e); if (v >= 1) band = (unsigned)v; }
+    if (band > gc) band = gc;      // band * gr then stays within the grid size, which fits 32 bits
     if (fmt == 0) {
         if (q_t) hipLaunchKernelGGL((quantize_patch_kernel<0, true, V>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word, gr, gc, band);
         else hipLaunchKernelGGL((quantize_patch_kernel<0, false, V>), grid, block, 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word, gr, gc, band);

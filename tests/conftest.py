@@ -3,6 +3,10 @@ import sys
 
 import pytest
 
+# The library looks at its tuning overrides (LLMQ_GEMM_TILE and the like, which several tests set) only in
+# processes started with LLMQ_TUNING=1; it reads that switch once, at its first launch.
+os.environ.setdefault("LLMQ_TUNING", "1")
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)

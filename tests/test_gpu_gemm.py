@@ -63,6 +63,27 @@ def test_gemm_tn_within_tolerance(R, C, T, fa, fb):
     assert torch.equal(c2.view(torch.int16), c.view(torch.int16))
 
 
+@pytest.mark.parametrize("R,C,T", [(256, 256, 256), (512, 768, 384), (48, 40, 1000)])
+def test_fused_absmax_reports_a_nan_output(R, C, T):
+    """One NaN code in A makes one output row NaN; the fused absmax of the tuned kernel (first two shapes) and
+    of the generic one (last) must then be the canonical NaN that llmq_amax reports for the stored tensor,
+    and an Inf output (E5M2 Inf code) must give +Inf."""
+    A = _rand_codes((R, T), 0, 91)
+    B = _rand_codes((C, T), 0, 92)
+    A[R // 2 + 1, T // 3] = 0x7F                          # E4M3 NaN
+    c, am = _run_gemm(A, 0, B, 0, 1.5, 0.8, want_amax=True)
+    a2, _ = gpu_amax(c.reshape(-1), 0, want_scale=False)
+    assert torch.isnan(c[R // 2 + 1]).all() and not torch.isnan(c[R // 2]).any()
+    assert f32_bits(am) == f32_bits(a2) == 0x7FC00000
+    A5 = _rand_codes((R, T), 1, 93)
+    A5[R - 1, 0] = 0x7C                                   # E5M2 +Inf
+    B[:, 0] = 0x38                                        # E4M3 1.0: the Inf row stays Inf, no 0 * Inf
+    c, am = _run_gemm(A5, 1, B, 0, 1.5, 0.8, want_amax=True)
+    a2, _ = gpu_amax(c.reshape(-1), 0, want_scale=False)
+    assert torch.isinf(c[R - 1]).all()
+    assert f32_bits(am) == f32_bits(a2) == 0x7F800000
+
+
 @pytest.mark.parametrize("tile", ["4x4", "4x3", "4x2", "3x4", "3x3", "3x2", "2x4", "2x3", "2x2"])
 def test_every_tuned_tile_shape(tile, monkeypatch):
     """Each wave-tile instantiation of the tuned kernel, forced through the tuning override, on a
@@ -211,35 +232,49 @@ def _sample_positions(R, C, n, seed, tile=256):
     return np.concatenate([rr] + er), np.concatenate([cc] + ec)
 
 
-@pytest.mark.parametrize("cfg_i,li", [(c, l) for c in (2, 3, 4, 5) for l in range(4)])
-def test_full_size_linears_on_sampled_outputs(cfg_i, li):
-    """The benchmark configurations' shapes in the launch configuration bench.py times; the oracle computes >= 4096 random
-    outputs plus tile-boundary rows and columns of each of the three GEMMs with full-length dot
-    products; quantized operands are compared in full."""
+# Every linear of configs 2-5 with explicit scales (llmq_amax first) and with just-in-time scaling inside the
+# calls, which is the launch sequence bench.py times; E5M2 gradients as in the benchmark configurations, plus
+# one linear per config with E4M3 gradients (Section 5, Scenario 1 of the paper tried both).
+FULL_SIZE_CASES = [(c, l, jit, 1) for c in (2, 3, 4, 5) for l in range(4) for jit in (False, True)] + \
+                  [(2, 1, True, 0), (3, 2, True, 0), (4, 0, True, 0), (5, 3, True, 0), (3, 3, False, 0)]
+
+
+@pytest.mark.parametrize("cfg_i,li,jit,fmt_dy", FULL_SIZE_CASES)
+def test_full_size_linears_on_sampled_outputs(cfg_i, li, jit, fmt_dy):
+    """The benchmark configurations' shapes; with jit the three calls run exactly as bench.py's step runs them
+    (LLMQ_JIT_X | LLMQ_JIT_W, LLMQ_JIT_DY | LLMQ_REUSE_W, LLMQ_REUSE_X | LLMQ_REUSE_DY: the scales are outputs of
+    the calls), without it the scales come from llmq_amax.  Either way the scales must be the oracle's bit
+    for bit, the six quantized copies are compared in full, and the oracle computes >= 4096 random outputs
+    plus tile-boundary rows and columns of each of the three GEMMs with full-length dot products."""
     cfg = synth.CONFIGS[cfg_i]
     lin = cfg.linears[li]
     M, K, N = cfg.M, lin.K, lin.N
-    print("full-size config %d %s M=%d K=%d N=%d" % (cfg_i, lin.name, M, K, N), flush=True)
+    print("full-size config %d %s M=%d K=%d N=%d jit=%d fmt_dy=%d" % (cfg_i, lin.name, M, K, N, jit, fmt_dy), flush=True)
     xd = synth.make_x(cfg, li, device=DEV)
     wd = synth.make_w(cfg, li, device=DEV)
     dyd = synth.make_dy(cfg, li, device=DEV)
-    _, sx = gpu_amax(xd, 0)
-    _, sw = gpu_amax(wd, 0)
-    _, sd = gpu_amax(dyd, 1)
     ws = torch.empty(llmq.llmq_fp8_linear_workspace_bytes(M, N, K), dtype=torch.uint8, device=DEV)
     offs = llmq.llmq_fp8_linear_workspace_offsets(M, N, K)
     Y = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
     dX = torch.empty((M, K), dtype=torch.bfloat16, device=DEV)
     dW = torch.empty((N, K), dtype=torch.bfloat16, device=DEV)
     amax_y = torch.zeros(1, dtype=torch.float32, device=DEV)
-    llmq.llmq_fp8_linear_fwd(xd, wd, M, N, K, sx, sw, Y, amax_y, ws)
-    llmq.llmq_fp8_linear_dgrad(dyd, None, M, N, K, sd, sw, 1, dX, None, ws, llmq.REUSE_W)
-    llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, sd, sx, 1, dW, False, ws, llmq.REUSE_X | llmq.REUSE_DY)
+    if jit:
+        sx, sw, sd = (torch.full((1,), -1.0, dtype=torch.float32, device=DEV) for _ in range(3))
+        llmq.llmq_fp8_linear_fwd(xd, wd, M, N, K, sx, sw, Y, amax_y, ws, llmq.JIT_X | llmq.JIT_W)
+        llmq.llmq_fp8_linear_dgrad(dyd, None, M, N, K, sd, sw, fmt_dy, dX, None, ws, llmq.JIT_DY | llmq.REUSE_W)
+    else:
+        _, sx = gpu_amax(xd, 0)
+        _, sw = gpu_amax(wd, 0)
+        _, sd = gpu_amax(dyd, fmt_dy)
+        llmq.llmq_fp8_linear_fwd(xd, wd, M, N, K, sx, sw, Y, amax_y, ws)
+        llmq.llmq_fp8_linear_dgrad(dyd, None, M, N, K, sd, sw, fmt_dy, dX, None, ws, llmq.REUSE_W)
+    llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, sd, sx, fmt_dy, dW, False, ws, llmq.REUSE_X | llmq.REUSE_DY)
     torch.cuda.synchronize()
     print("  gpu done; oracle quantize", flush=True)
     ox = oracle_quantized(xd, 0)
     ow = oracle_quantized(wd, 0)
-    od = oracle_quantized(dyd, 1)
+    od = oracle_quantized(dyd, fmt_dy)
     assert [f32_bits(t) for t in (sx, sw, sd)] == [np_f32_bits(o[1]) for o in (ox, ow, od)]
     wsh = ws.cpu().numpy()
     for off, want in zip(offs, (ox[2], ox[3], ow[2], ow[3], od[2], od[3])):
@@ -248,8 +283,8 @@ def test_full_size_linears_on_sampled_outputs(cfg_i, li):
     assert amax_y.item() == Y.float().abs().max().item()
     for name, out, (A, fa, sa), (B, fb, sb) in [
             ("fwd", Y, (ox[2], 0, ox[1]), (ow[2], 0, ow[1])),
-            ("dgrad", dX, (od[2], 1, od[1]), (ow[3], 0, ow[1])),
-            ("wgrad", dW, (od[3], 1, od[1]), (ox[3], 0, ox[1]))]:
+            ("dgrad", dX, (od[2], fmt_dy, od[1]), (ow[3], 0, ow[1])),
+            ("wgrad", dW, (od[3], fmt_dy, od[1]), (ox[3], 0, ox[1]))]:
         print("  oracle samples %s" % name, flush=True)
         rr, cc = _sample_positions(out.shape[0], out.shape[1], 4096, 17 + li)
         y, S = oracle.gemm_tn_sampled(A, fa, B, fb, sa, sb, rr, cc)
@@ -376,12 +411,12 @@ def test_just_in_time_scaling_inside_the_linear_calls(shape, fmt_dy):
     llmq.llmq_fp8_linear_wgrad(dyd, xd, M, N, K, sd2, sx2, fmt_dy, dW2, False, ws, llmq.JIT_DY | llmq.JIT_X)
     assert f32_bits(sd2) == f32_bits(s0[2]) and f32_bits(sx2) == f32_bits(s0[0])
     assert torch.equal(dW2.view(torch.int16), o0[2].view(torch.int16))
-    # an all-zero operand: scale FLT_MAX, result zero
+    # an all-zero operand: scale 1, result zero
     z = torch.zeros_like(xd)
     sz, sw3 = torch.full((1,), -1.0, device=DEV), torch.full((1,), -1.0, device=DEV)
     Yz = torch.full((M, N), 3.0, dtype=torch.bfloat16, device=DEV)
     llmq.llmq_fp8_linear_fwd(z, wd, M, N, K, sz, sw3, Yz, None, ws, llmq.JIT_X | llmq.JIT_W)
-    assert sz.item() == float(np.finfo(np.float32).max) and (Yz == 0).all()
+    assert sz.item() == 1.0 and (Yz == 0).all()
     # flag combinations that make no sense are refused
     with pytest.raises(llmq.LlmqError) as e:
         llmq.llmq_fp8_linear_fwd(xd, wd, M, N, K, sz, sw3, Yz, None, ws, llmq.JIT_X | llmq.REUSE_X)
