@@ -76,6 +76,20 @@ int llmq_amax(const void* x_bf16, size_t n, int fmt, float* d_amax, float* d_sca
               void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * llmq_amax for callers that cannot allocate device memory and have no workspace to hand over: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit-identical outputs, but the per-block partial results go to a 4 KB array inside the library's device
+ * image (one copy per GPU, held until the process ends) instead of `ws`.  The call allocates and frees
+ * nothing.  n: 1 <= n < 2^40 elements as for llmq_amax, LLMQ_ERR_SHAPE beyond; the array's size does not
+ * depend on n.  It uses the copy of the device that is current when the call is made, which must be the
+ * stream's device; LLMQ_ERR_DEVICE if the runtime cannot resolve the array.  Every call on a GPU shares that
+ * GPU's array: calls that may overlap on one device (different streams, or graphs replayed side by side) race
+ * on it and need llmq_amax with separate workspaces instead.  Nothing in the array has to be cleared between
+ * calls: every word the second stage reads has been written by the first stage of the same call.
+ */
+int llmq_amax_static(const void* x_bf16, size_t n, int fmt, float* d_amax, float* d_scale, void* stream);
+
+/*
  * Fused scale + FP8 cast + transposed copy (Section 3, kernel-fusion paragraph: quantization and the
  * transposition the backward GEMMs need are one kernel).
  *   q[i,j]   = cast( fl32( fl32(x[i,j]) * d_scale[0] ) ),  q_t[j,i] = q[i,j]

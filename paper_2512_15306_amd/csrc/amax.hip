@@ -9,10 +9,38 @@
 // blocks on one address serialise at roughly 12 ns each on this chip, and an accumulator that
 // atomics could target would need a reset launch of its own, which costs as much as the second
 // kernel does.
+#include <mutex>
+
 #include "llmq_device.h"
 #include "llmq_kernels.h"
 
 namespace llmq {
+
+// Scratch of the entry point that allocates nothing and takes no workspace (llmq_amax_static): the per-block
+// partial results live in this file-scope array, 4 KB on every GPU the library runs on, held until the
+// process ends.  In host code the array's name is only a handle for the runtime: the device address of the
+// current GPU's copy comes from hipGetSymbolAddress, once per device, and that address is what kernels and
+// launches get.
+static __device__ __align__(256) unsigned amax_static_scratch[kAmaxMaxPartials];
+constexpr int kMaxDevices = 64;
+static unsigned* g_static_scratch_ptr[kMaxDevices];      // per device; guarded by g_static_scratch_mutex
+static std::mutex g_static_scratch_mutex;
+
+// Device address of the current GPU's copy of the static scratch, or nullptr if the runtime refuses.
+static unsigned* static_scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (g_static_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(amax_static_scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_static_scratch_ptr[dev] = static_cast<unsigned*>(p);
+    }
+    return g_static_scratch_ptr[dev];
+}
 
 constexpr int kAmaxThreads = 256;
 constexpr int kAmaxUnroll = 8;          // 16-byte loads in flight per lane
@@ -138,6 +166,15 @@ int launch_amax(const void* x, size_t n, int fmt, float* d_amax, float* d_scale,
     int blocks = 0;
     if (launch_amax_partial(x, n, reinterpret_cast<unsigned*>(ws), &blocks, stream, num_cus) != 0) return -6;
     return launch_amax_final(reinterpret_cast<unsigned*>(ws), blocks, fmt, d_amax, d_scale, stream);
+}
+
+// Every block of the first stage writes its word before the second stage reads it, so nothing in the
+// scratch has to start at zero; what the last call left there is simply overwritten.
+int launch_amax_static(const void* x, size_t n, int fmt, float* d_amax, float* d_scale, hipStream_t stream,
+                       int num_cus) {
+    unsigned* scratch = static_scratch_of_current_device();
+    if (scratch == nullptr) return -6;
+    return launch_amax(x, n, fmt, d_amax, d_scale, scratch, stream, num_cus);
 }
 
 int launch_amax_partial(const void* x, size_t n, unsigned* partial, int* n_partial, hipStream_t stream, int num_cus) {

@@ -114,6 +114,14 @@ int llmq_amax(const void* x_bf16, size_t n, int fmt, float* d_amax, float* d_sca
     return llmq::launch_amax(x_bf16, n, fmt, d_amax, d_scale, ws, static_cast<hipStream_t>(stream), num_cus());
 }
 
+int llmq_amax_static(const void* x_bf16, size_t n, int fmt, float* d_amax, float* d_scale, void* stream) {
+    if (!x_bf16 || !d_amax) return LLMQ_ERR_NULL;
+    if (n < 1 || n >= (size_t)kMaxElems) return LLMQ_ERR_SHAPE;      // the largest tensor llmq_amax takes
+    if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
+    if (!aligned(x_bf16, 16) || !aligned(d_amax, 4) || !aligned(d_scale, 4)) return LLMQ_ERR_ALIGN;
+    return llmq::launch_amax_static(x_bf16, n, fmt, d_amax, d_scale, static_cast<hipStream_t>(stream), num_cus());
+}
+
 int llmq_quantize_fp8(const void* x_bf16, int64_t rows, int64_t cols, const float* d_scale, int fmt,
                       uint8_t* q, uint8_t* q_t, void* stream) {
     if (!x_bf16 || !d_scale || !q) return LLMQ_ERR_NULL;

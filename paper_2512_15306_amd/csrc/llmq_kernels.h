@@ -19,6 +19,9 @@ inline const char* tuning_env(const char* name) {
 constexpr int kAmaxMaxPartials = 1024;      // the absmax workspace holds one 32-bit word per block
 int launch_amax(const void* x, size_t n, int fmt, float* d_amax, float* d_scale, void* ws,
                 hipStream_t stream, int num_cus);
+// The same with the partial results in the library's own file-scope device array (no workspace, no allocation).
+int launch_amax_static(const void* x, size_t n, int fmt, float* d_amax, float* d_scale, hipStream_t stream,
+                       int num_cus);
 // Second stage of every absmax reduction: the maximum of n_partial BF16 magnitude patterns (one per
 // workgroup of the first stage) becomes d_amax and, if d_scale is not NULL, the scale for fmt.
 int launch_amax_final(const unsigned* partial, int n_partial, int fmt, float* d_amax, float* d_scale,

@@ -25,7 +25,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libllmq.so")
 _lib = None
 
-EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "llmq_amax", "llmq_quantize_fp8", "llmq_fp8_gemm_tn", "llmq_fp8_gemm", "llmq_bf16_gemm_tn",
+EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "llmq_amax", "llmq_amax_static", "llmq_quantize_fp8", "llmq_fp8_gemm_tn", "llmq_fp8_gemm", "llmq_bf16_gemm_tn",
            "llmq_fp8_linear_workspace_bytes", "llmq_fp8_linear_workspace_bytes_no_transpose", "llmq_fp8_linear_workspace_offsets",
            "llmq_fp8_linear_fwd", "llmq_fp8_linear_dgrad", "llmq_fp8_linear_wgrad",
            "llmq_scale_from_amax", "llmq_swiglu_workspace_bytes", "llmq_swiglu_fwd", "llmq_swiglu_fwd_fp8",
@@ -58,6 +58,8 @@ def lib() -> ctypes.CDLL:
     L.llmq_amax_workspace_bytes.argtypes = []
     L.llmq_amax.restype = i32
     L.llmq_amax.argtypes = [vp, sz, i32, vp, vp, vp, sz, vp]
+    L.llmq_amax_static.restype = i32
+    L.llmq_amax_static.argtypes = [vp, sz, i32, vp, vp, vp]
     L.llmq_quantize_fp8.restype = i32
     L.llmq_quantize_fp8.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp]
     L.llmq_fp8_gemm_tn.restype = i32
@@ -141,6 +143,11 @@ def llmq_amax(x: torch.Tensor, fmt: int, d_amax: torch.Tensor, d_scale: Optional
     _check(lib().llmq_amax(_dev(x, torch.bfloat16, "x"), x.numel(), fmt, _dev(d_amax, torch.float32, "d_amax"),
                            _dev(d_scale, torch.float32, "d_scale"), _dev(ws, torch.uint8, "ws"), ws.numel(),
                            _stream()), "llmq_amax")
+
+
+def llmq_amax_static(x: torch.Tensor, fmt: int, d_amax: torch.Tensor, d_scale: Optional[torch.Tensor]) -> None:
+    _check(lib().llmq_amax_static(_dev(x, torch.bfloat16, "x"), x.numel(), fmt, _dev(d_amax, torch.float32, "d_amax"),
+                                  _dev(d_scale, torch.float32, "d_scale"), _stream()), "llmq_amax_static")
 
 
 def llmq_quantize_fp8(x: torch.Tensor, d_scale: torch.Tensor, fmt: int, q: torch.Tensor,

@@ -58,6 +58,15 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.llmq_amax(ok_ptr, 8, 0, ok_ptr, ok_ptr, None, n(aw), None) == -1
     assert L.llmq_amax(ok_ptr, 0, 0, ok_ptr, ok_ptr, ok_ptr, n(aw), None) == -2
     assert L.llmq_amax(ok_ptr, 8, 2, ok_ptr, ok_ptr, ok_ptr, n(aw), None) == -4
+    assert L.llmq_amax_static(None, 8, 0, ok_ptr, ok_ptr, None) == -1
+    assert L.llmq_amax_static(ok_ptr, 8, 0, None, ok_ptr, None) == -1
+    assert L.llmq_amax_static(ok_ptr, 0, 0, ok_ptr, ok_ptr, None) == -2
+    assert L.llmq_amax_static(ok_ptr, n(1 << 40), 0, ok_ptr, ok_ptr, None) == -2
+    assert L.llmq_amax_static(ok_ptr, 8, 2, ok_ptr, ok_ptr, None) == -4
+    assert L.llmq_amax_static(odd_ptr, 8, 0, ok_ptr, ok_ptr, None) == -3
+    assert L.llmq_amax(odd_ptr, 8, 0, ok_ptr, ok_ptr, ok_ptr, n(aw), None) == -3
+    assert L.llmq_amax(ok_ptr, 8, 0, ok_ptr + 2, ok_ptr, ok_ptr, n(aw), None) == -3
+    assert L.llmq_amax(ok_ptr, 8, 0, ok_ptr, ok_ptr, ok_ptr, n(aw - 1), None) == -5
     assert L.llmq_quantize_fp8(ok_ptr, 4, 4, None, 0, ok_ptr, ok_ptr, None) == -1
     assert L.llmq_quantize_fp8(ok_ptr, 0, 4, ok_ptr, 0, ok_ptr, ok_ptr, None) == -2
     assert L.llmq_quantize_fp8(ok_ptr, 4, -1, ok_ptr, 0, ok_ptr, ok_ptr, None) == -2
