@@ -168,7 +168,9 @@ size_t llmq_fp8_linear_workspace_bytes_no_transpose(int64_t M, int64_t N, int64_
 int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t offsets[6]);
 
 /* `flags` of the linear calls: the named operand's FP8 copies are already in the workspace (written by
- * an earlier call with the same M, N, K and the same scale) and are not produced again.  Weights are
+ * an earlier call with the same M, N, K and the same scale) and are not produced again.  The library takes the
+ * caller's word for it: nothing in the workspace records what it holds, and a call that claims copies that are
+ * not there computes on stale bytes and still returns LLMQ_OK.  Weights are
  * quantized once per optimizer step and reused across micro-steps and in the backward pass (Section 3,
  * weight caching), and the backward pass reuses the forward's copies of X. */
 #define LLMQ_REUSE_X  1
