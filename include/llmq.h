@@ -143,6 +143,32 @@ int llmq_fp8_gemm(const uint8_t* A, int fmtA, int a_t_major, const uint8_t* B, i
                   void* c_bf16, int accumulate, float* d_amax_c, void* stream);
 
 /*
+ * The same contraction with caller-owned scratch, which lets the library share out a ragged last round of
+ * output tiles: the chip computes one tile per CU at a time, and when the number of tiles is not a multiple of
+ * the number of CUs the last round leaves CUs idle (560 tiles on 256 CUs take three rounds, the third with 48
+ * tiles).  With scratch, the left-over tiles are cut along the contraction index and dealt to all CUs; every
+ * piece is written to the scratch as binary32 accumulators, and a second launch adds the pieces of a tile in
+ * the fixed order of their contraction ranges and finishes the tile (de-scale, BF16, absmax).  No atomic
+ * additions, no dependence on timing: same inputs, same bytes (Section 3 "Reproducibility": an intermediate
+ * buffer and a second step instead of atomics).  The sums are grouped differently from a call without scratch,
+ * so the two may differ in the last bit of an output; both are within the error bound above.
+ *   scratch        device memory, 256-byte aligned, at least llmq_fp8_gemm_scratch_bytes(R, C, T) bytes for the
+ *                  sharing to happen; NULL or a smaller buffer: every tile is computed whole (as llmq_fp8_gemm).
+ *                  Contents on entry do not matter; calls that may overlap on the device need separate scratch.
+ * llmq_fp8_gemm_scratch_bytes returns 0 for shapes the library computes whole anyway: whole rounds, small
+ * problems, T-major operands, and every shape for which sharing was not measured to win.  The chip is
+ * power-limited on real data, so CUs left idle by a ragged round let the busy ones clock higher and the round
+ * costs less than a full one; sharing pays (3-7 % of one isolated GEMM) only for long contractions
+ * (T >= 16384) whose left-over tiles all fit one group of pieces.  The linear calls below do not use it.
+ */
+size_t llmq_fp8_gemm_scratch_bytes(int64_t R, int64_t C, int64_t T);
+int llmq_fp8_gemm_with_scratch(const uint8_t* A, int fmtA, int a_t_major, const uint8_t* B, int fmtB, int b_t_major,
+                               int64_t R, int64_t C, int64_t T,
+                               const float* d_scaleA, const float* d_scaleB,
+                               void* c_bf16, int accumulate, float* d_amax_c,
+                               void* scratch, size_t scratch_bytes, void* stream);
+
+/*
  * BF16 baseline of the same contraction, for the FP8-versus-BF16 comparison the paper reports (Section 4,
  * "Impact of FP8", speed-up column of Table 1): no quantization, no scales,
  *   c[r,cc] = bf16( sum_t A[r,t] * B[cc,t] )   (+ c[r,cc] first when accumulate != 0)

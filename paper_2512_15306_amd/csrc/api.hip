@@ -49,6 +49,10 @@ WsLayout ws_layout(int64_t M, int64_t N, int64_t K) {
     return l;
 }
 
+// The linear calls compute every output tile whole: sharing a ragged last round among all CUs
+// (llmq_fp8_gemm_with_scratch) did not pay inside a block's sequence of GEMMs on this power-limited chip.
+constexpr llmq::GemmScratch kNoScratch{nullptr, 0};
+
 int check_linear(int64_t M, int64_t N, int64_t K, const void* ws, size_t ws_bytes, int flags) {
     if (!dim_ok(M) || !dim_ok(N) || !dim_ok(K)) return LLMQ_ERR_SHAPE;
     if (M * K >= kMaxElems || N * K >= kMaxElems || M * N >= kMaxElems) return LLMQ_ERR_SHAPE;
@@ -100,7 +104,7 @@ const char* llmq_status_string(int status) {
     }
 }
 
-int llmq_version(void) { return 120; }
+int llmq_version(void) { return 200; }
 
 size_t llmq_amax_workspace_bytes(void) { return (size_t)llmq::kAmaxMaxPartials * sizeof(unsigned); }
 
@@ -142,21 +146,35 @@ int llmq_fp8_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int
         !aligned(d_scaleB, 4) || !aligned(d_amax_c, 4))
         return LLMQ_ERR_ALIGN;
     return llmq::launch_gemm_tn(A, fmtA, B, fmtB, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, d_amax_c, false,
-                                static_cast<hipStream_t>(stream), num_cus());
+                                static_cast<hipStream_t>(stream), num_cus(), llmq::GemmScratch{nullptr, 0});
 }
 
 int llmq_fp8_gemm(const uint8_t* A, int fmtA, int a_t_major, const uint8_t* B, int fmtB, int b_t_major, int64_t R,
                   int64_t C, int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16, int accumulate,
                   float* d_amax_c, void* stream) {
+    return llmq_fp8_gemm_with_scratch(A, fmtA, a_t_major, B, fmtB, b_t_major, R, C, T, d_scaleA, d_scaleB, c_bf16,
+                                      accumulate, d_amax_c, nullptr, 0, stream);
+}
+
+size_t llmq_fp8_gemm_scratch_bytes(int64_t R, int64_t C, int64_t T) {
+    if (!dim_ok(R) || !dim_ok(C) || !dim_ok(T)) return 0;
+    return llmq::gemm_scratch_bytes(R, C, T, num_cus());
+}
+
+int llmq_fp8_gemm_with_scratch(const uint8_t* A, int fmtA, int a_t_major, const uint8_t* B, int fmtB, int b_t_major,
+                               int64_t R, int64_t C, int64_t T, const float* d_scaleA, const float* d_scaleB,
+                               void* c_bf16, int accumulate, float* d_amax_c, void* scratch, size_t scratch_bytes,
+                               void* stream) {
     if (!A || !B || !d_scaleA || !d_scaleB || !c_bf16) return LLMQ_ERR_NULL;
     if (!dim_ok(R) || !dim_ok(C) || !dim_ok(T)) return LLMQ_ERR_SHAPE;
     if (R * T >= kMaxElems || C * T >= kMaxElems || R * C >= kMaxElems) return LLMQ_ERR_SHAPE;
     if (!fmt_ok(fmtA) || !fmt_ok(fmtB)) return LLMQ_ERR_FORMAT;
     if (!aligned(A, 16) || !aligned(B, 16) || !aligned(c_bf16, 16) || !aligned(d_scaleA, 4) ||
-        !aligned(d_scaleB, 4) || !aligned(d_amax_c, 4))
+        !aligned(d_scaleB, 4) || !aligned(d_amax_c, 4) || !aligned(scratch, 256))
         return LLMQ_ERR_ALIGN;
+    const llmq::GemmScratch sc{scratch ? static_cast<float*>(scratch) : nullptr, scratch ? scratch_bytes : 0};
     return llmq::launch_gemm_fp8(A, fmtA, a_t_major != 0, B, fmtB, b_t_major != 0, R, C, T, d_scaleA, d_scaleB, c_bf16,
-                                 accumulate, d_amax_c, false, static_cast<hipStream_t>(stream), num_cus());
+                                 accumulate, d_amax_c, false, static_cast<hipStream_t>(stream), num_cus(), sc);
 }
 
 int llmq_bf16_gemm_tn(const void* A_bf16, const void* B_bf16, int64_t R, int64_t C, int64_t T, void* c_bf16,
@@ -210,7 +228,7 @@ int llmq_fp8_linear_fwd(const void* X, const void* W, int64_t M, int64_t N, int6
     if (qx && (st = quantize_operand(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, nt ? nullptr : base + l.xqt, (flags & LLMQ_JIT_X) != 0, part, zero, s))) return st;
     if (qw && (st = quantize_operand(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, nt ? nullptr : base + l.wqt, (flags & LLMQ_JIT_W) != 0, part + kPartWords, qx ? nullptr : zero, s))) return st;
     return llmq::launch_gemm_tn(base + l.xq, LLMQ_E4M3, base + l.wq, LLMQ_E4M3, M, N, K, d_scale_x, d_scale_w,
-                                Y, 0, d_amax_y, zeroed, s, num_cus());
+                                Y, 0, d_amax_y, zeroed, s, num_cus(), kNoScratch);
 }
 
 int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, int64_t K,
@@ -237,7 +255,7 @@ int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, i
     if (qw && (st = quantize_operand(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, nt ? nullptr : base + l.wqt, (flags & LLMQ_JIT_W) != 0, part + kPartWords, qd ? nullptr : zero, s))) return st;
     // dX[m,k] = sum_n dYq[m,n] * Wq_t[k,n] = sum_n dYq[m,n] * Wq[n,k]
     return llmq::launch_gemm_fp8(base + l.dyq, fmt_dy, false, nt ? base + l.wq : base + l.wqt, LLMQ_E4M3, nt, M, K, N,
-                                 d_scale_dy, d_scale_w, dX, 0, d_amax_dx, zeroed, s, num_cus());
+                                 d_scale_dy, d_scale_w, dX, 0, d_amax_dx, zeroed, s, num_cus(), kNoScratch);
 }
 
 int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, int64_t K,
@@ -262,7 +280,7 @@ int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, i
     if (qx && (st = quantize_operand(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, nt ? nullptr : base + l.xqt, (flags & LLMQ_JIT_X) != 0, part, nullptr, s))) return st;
     // dW[n,k] = sum_m dYq_t[n,m] * Xq_t[k,m] = sum_m dYq[m,n] * Xq[m,k]
     return llmq::launch_gemm_fp8(nt ? base + l.dyq : base + l.dyqt, fmt_dy, nt, nt ? base + l.xq : base + l.xqt, LLMQ_E4M3, nt,
-                                 N, K, M, d_scale_dy, d_scale_x, dW, accumulate, nullptr, false, s, num_cus());
+                                 N, K, M, d_scale_dy, d_scale_x, dW, accumulate, nullptr, false, s, num_cus(), kNoScratch);
 }
 
 int llmq_scale_from_amax(const float* d_amax, int fmt, float* d_scale, void* stream) {

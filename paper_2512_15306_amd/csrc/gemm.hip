@@ -107,7 +107,7 @@ __global__ void gemm_amax_reset_kernel(unsigned* amax_bits) {
 // model: every CU works through its share of the tiles, a tile costs NI * NJ MFMA blocks per K step
 // divided by the measured efficiency of that shape relative to 4 x 4 (smaller tiles read more LDS
 // and L2 bytes per MFMA; 2 x 2 tiles fit two workgroups per CU, which hide each other's stalls).
-TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus) {
+TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus, size_t scratch_bytes) {
     static const float eff[5][5] = {{0, 0, 0, 0, 0}, {0, 0, 0, 0, 0}, {0, 0, 0.90f, 0.74f, 0.77f},
                                     {0, 0, 0.74f, 0.70f, 0.83f}, {0, 0, 0.77f, 0.83f, 1.00f}};
     TileChoice best{0, 0};
@@ -124,12 +124,14 @@ TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus) {
             const int64_t tiles = (R / (64 * ni)) * (C / (64 * nj));
             if (tiles >= (1ll << 30)) continue;
             const int per_cu = (ni == 2 && nj == 2) ? 2 : 1;          // workgroups resident per CU
-            const int64_t slots = (int64_t)num_cus * per_cu;
+            const int64_t slots = resident_slots(num_cus, ni, nj);
             const int64_t rounds = (tiles + slots - 1) / slots;
             // two resident 2 x 2 workgroups overlap each other's prologue and epilogue, which pays most
             // when the contraction is short
             const double e = per_cu == 2 ? (T <= 3072 ? 0.90 : 0.80) : eff[ni][nj];
-            const double cost = (double)rounds * per_cu * ni * nj / e;
+            // a ragged last round may be shared out among all CUs (choose_split): the model's gain scales the cost
+            const SplitChoice sc = choose_split((int)tiles, (int)(T / BK), (int)slots, ni, nj, scratch_bytes);
+            const double cost = (double)rounds * per_cu * ni * nj / e * (sc.cost_us / sc.whole_cost_us);
             if (best.ni == 0 || cost < best_cost * 0.97) { best = {ni, nj}; best_cost = cost; }   // larger tile on near ties
         }
     return best;
@@ -138,8 +140,8 @@ TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus) {
 template <int FA, int FB>
 static void launch_one(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
                        const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
-                       hipStream_t stream, int num_cus) {
-    if (launch_chosen_tile<FA, FB, false, false>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus)) return;
+                       hipStream_t stream, int num_cus, GemmScratch scratch) {
+    if (launch_chosen_tile<FA, FB, false, false>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus, scratch)) return;
     if constexpr (FA == kFmtBf16) {
         const int64_t n = R * C;
         int64_t blocks = (n + 255) / 256;
@@ -169,21 +171,31 @@ void launch_gemm_amax_reset(unsigned* amax, hipStream_t stream) {
 
 int launch_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64_t R, int64_t C,
                    int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16,
-                   int accumulate, float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus) {
+                   int accumulate, float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus, GemmScratch scratch) {
     unsigned* amax = reinterpret_cast<unsigned*>(d_amax_c);
     if (amax && !amax_is_zeroed) hipLaunchKernelGGL(gemm_amax_reset_kernel, dim3(1), dim3(64), 0, stream, amax);
-    if (fmtA == 0 && fmtB == 0) launch_one<0, 0>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus);
-    else if (fmtA == 1 && fmtB == 0) launch_one<1, 0>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus);
-    else if (fmtA == 0 && fmtB == 1) launch_one<0, 1>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus);
-    else launch_one<1, 1>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus);
+    if (fmtA == 0 && fmtB == 0) launch_one<0, 0>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus, scratch);
+    else if (fmtA == 1 && fmtB == 0) launch_one<1, 0>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus, scratch);
+    else if (fmtA == 0 && fmtB == 1) launch_one<0, 1>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus, scratch);
+    else launch_one<1, 1>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus, scratch);
     return hipGetLastError() == hipSuccess ? 0 : -6;
+}
+
+// Scratch a launch of this shape would use when given as much as it likes (0: every tile is computed whole).
+size_t gemm_scratch_bytes(int64_t R, int64_t C, int64_t T, int num_cus) {
+    const size_t unlimited = ~(size_t)0;
+    const TileChoice tc = choose_tile(R, C, T, num_cus, unlimited);
+    if (tc.ni == 0) return 0;
+    const int64_t tiles = (R / (64 * tc.ni)) * (C / (64 * tc.nj));
+    const SplitChoice sc = choose_split((int)tiles, (int)(T / BK), resident_slots(num_cus, tc.ni, tc.nj), tc.ni, tc.nj, unlimited);
+    return sc.slots * (size_t)(4 * 4096 * tc.ni * tc.nj);
 }
 
 // BF16 baseline: same tile kernels with the BF16 MFMA; T counts elements here, rows are 2 T bytes long.
 int launch_gemm_bf16_tn(const void* A, const void* B, int64_t R, int64_t C, int64_t T, void* c_bf16,
                         int accumulate, hipStream_t stream, int num_cus) {
     launch_one<kFmtBf16, kFmtBf16>(reinterpret_cast<const uint8_t*>(A), reinterpret_cast<const uint8_t*>(B), R, C, 2 * T,
-                                   nullptr, nullptr, c_bf16, accumulate, nullptr, stream, num_cus);
+                                   nullptr, nullptr, c_bf16, accumulate, nullptr, stream, num_cus, GemmScratch{nullptr, 0});
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 

@@ -54,20 +54,54 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
 }
 
-// Linear workgroup id -> output tile, XCD-aware.  Returns false for the padding ids.
-__device__ inline bool tile_of_block(int pid, int tiles_r, int tiles_c, int band_rows, int& tr, int& tc) {
-    const int nt = tiles_r * tiles_c;
-    const int per_xcd = (nt + kXcds - 1) / kXcds;
-    const int id = (pid % kXcds) * per_xcd + pid / kXcds;
-    if (id >= nt) return false;
+// Workgroup id -> position in a walk of n items, XCD-aware: the hardware deals workgroup ids round-robin to
+// the XCDs, and every XCD gets a contiguous range of positions.  -1 for the padding ids.
+__device__ inline int walk_position(int pid, int n) {
+    const int per_xcd = (n + kXcds - 1) / kXcds;
+    const int pos = (pid % kXcds) * per_xcd + pid / kXcds;
+    return pos < n ? pos : -1;
+}
+
+// Position in the walk of tiles -> output tile: bands band_rows tile rows high, walked down the rows first.
+__device__ inline void tile_of_position(int pos, int tiles_r, int tiles_c, int band_rows, int& tr, int& tc) {
     const int band = band_rows * tiles_c;
-    const int first = (id / band) * band_rows;
+    const int first = (pos / band) * band_rows;
     const int h = tiles_r - first < band_rows ? tiles_r - first : band_rows;
-    const int in_band = id % band;
+    const int in_band = pos % band;
     tr = first + in_band % h;
     tc = in_band / h;
-    return true;
 }
+
+// How a launch shares out its tiles: a deterministic split of the contraction for a ragged last round of tiles
+// (paper Section 3 "Reproducibility": partial results go to an intermediate buffer and are added in a fixed
+// order by a second step, never with atomic additions).
+//   Positions [0, n_whole) of the walk are computed whole, one workgroup per tile, by a launch of the plain
+//   kernel (n_whole is a multiple of the number of workgroups the chip holds: whole rounds).  The remaining
+//   positions are served by a launch of the SPLIT instantiation, which comes first; they come in up to
+//   kMaxSplitGroups groups; the tiles of a group are each cut into `pieces` pieces of `steps` K steps (the last
+//   piece takes what is left), one workgroup per piece, and a group never has more workgroups than the chip holds
+//   at once, so the groups run one after the other like rounds of ever shorter pieces: 192 left-over tiles on
+//   256 CUs are 128 tiles in halves, then 64 tiles in quarters, 3/4 of a round instead of a whole one.
+//   pieces == 1: the tile is written as usual.  Otherwise the piece's accumulators go, as binary32, to slot
+//   (wg_begin + tile_in_group * pieces + piece) of `partials`, and a second launch of the SPLIT instantiation with
+//   fixup = 1, one workgroup per shared tile, adds the pieces of a tile in the order of their K ranges and runs the
+//   usual epilogue on the sums.
+constexpr int kMaxSplitGroups = 4;
+struct SplitGroup {
+    int tile_begin;      // first tile of the group, counted from n_whole
+    int tiles;
+    int pieces;          // per tile
+    int steps;           // K steps per piece
+    int wg_begin;        // first workgroup of the group in the sharing launch; also its first slot
+    int wgs;             // workgroups of the group, padded to a multiple of the XCD count
+};
+struct SplitPlan {
+    int n_whole;         // the plain kernel walks positions [0, n_whole); the shared tiles follow
+    int n_groups;        // 0: nothing is shared
+    int fixup;
+    SplitGroup group[kMaxSplitGroups];
+    float* partials;
+};
 
 // MFMA scheduling masks of __builtin_amdgcn_sched_group_barrier
 constexpr int kSchedMfma = 0x008, kSchedVmemRead = 0x020, kSchedDsRead = 0x100;
@@ -178,12 +212,14 @@ struct SlabShape {
     __device__ static int swizzle_of_row(int k) { return (NX == 4 ? k & 7 : NX == 2 ? (k >> 1) & 3 : (k >> 2) & 1) << 1; }
 };
 
-template <int FA, int FB, int NI, int NJ, bool ACCUM, class V = GemmTuning, bool TA = false, bool TB = false>
+// SPLIT: the instantiation that can share tiles among workgroups (SplitPlan); without it the plan is ignored and
+// every workgroup computes one whole tile, with nothing of the sharing logic in the code.
+template <int FA, int FB, int NI, int NJ, bool ACCUM, class V = GemmTuning, bool TA = false, bool TB = false, bool SPLIT = false>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ C,
     int Cn, int T, const float* __restrict__ d_sA, const float* __restrict__ d_sB,
     unsigned* __restrict__ amax_bits, int tiles_r, int tiles_c, int touch_ahead, int band_rows, int next_stride,
-    int ldA, int ldB, int share_a, int share_b) {
+    int ldA, int ldB, int share_a, int share_b, const SplitPlan plan) {
     static_assert(!(TA || TB) || (FA != kFmtBf16 && FB != kFmtBf16), "the transposing reads move single bytes");
     constexpr int BM = 64 * NI, BN = 64 * NJ;
     typedef SlabShape<NI, TA> SA;
@@ -201,8 +237,40 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     // of the slabs (8192 NJ bytes in the case of this one), so the end of the last slab is free by then; the
     // kernel's LDS is exactly its slabs.
     unsigned* s_amax = reinterpret_cast<unsigned*>(ldsB1 + kSlabB - 16);
+    // What this workgroup computes (uniform over the workgroup): the tile at position `pos` of the walk, K steps
+    // [kb, kb + nk), written as a whole tile (slot < 0) or as one piece of a shared tile.  In the fix-up launch
+    // slot is the first slot of the tile's pieces and nk their number.
+    int pos, kb = 0, nk = T / BK, slot = -1;
+    const bool fixup = SPLIT && plan.fixup != 0;
+    if constexpr (!SPLIT) {
+        pos = walk_position(blockIdx.x, plan.n_whole);
+        if (pos < 0) return;
+    } else {
+        const int q = (int)blockIdx.x;                     // shared tile (fix-up launch) or sharing workgroup
+        int gi = 0;
+        while (gi + 1 < plan.n_groups && q >= (plan.fixup ? plan.group[gi + 1].tile_begin : plan.group[gi + 1].wg_begin)) ++gi;
+        const SplitGroup grp = plan.group[gi];
+        if (plan.fixup) {
+            if (grp.pieces == 1) return;                   // written whole by the first launch
+            const int j = q - grp.tile_begin;
+            pos = plan.n_whole + q;
+            slot = grp.wg_begin + j * grp.pieces;
+            nk = grp.pieces;
+        } else {
+            const int w = walk_position(q - grp.wg_begin, grp.tiles * grp.pieces);   // neighbours on an XCD: neighbouring tiles, same K range
+            if (w < 0) return;
+            const int piece = w / grp.tiles, j = w - piece * grp.tiles;
+            pos = plan.n_whole + grp.tile_begin + j;
+            if (grp.pieces > 1) {
+                kb = piece * grp.steps;
+                nk = nk - kb < grp.steps ? nk - kb : grp.steps;
+                if (nk <= 0) return;                       // cannot happen with steps = ceil(K steps / pieces)
+                slot = grp.wg_begin + j * grp.pieces + piece;
+            }
+        }
+    }
     int tr, tc;
-    if (!tile_of_block(blockIdx.x, tiles_r, tiles_c, band_rows, tr, tc)) return;   // uniform over the workgroup
+    tile_of_position(pos, tiles_r, tiles_c, band_rows, tr, tc);
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -325,7 +393,6 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
     v8i a0[NI], b0[NJ], a1[NI], b1[NJ];    // fragment sets of the two 64-byte halves of a K step
-    const int nk = T / BK;
 
     // L2 touch loads: a wave reads the first dword of some rows of a slab that is still touch_ahead
     // steps ahead of the direct-to-LDS loads (touch_ahead <= 0: nothing is fetched).  The CUs of an XCD
@@ -365,7 +432,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
         if constexpr (kTouch) wait_vmcnt<2>(); else wait_vmcnt<0>();
         lds_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        issue_loads(curA, curB, kt + 2 < nk ? (kt + 2) * BK : -1);
+        issue_loads(curA, curB, kt + 2 < nk ? (kb + kt + 2) * BK : -1);
         read_fragsA(nxtA, 0, a0);               // past the last slab this reads bytes that are never used
         read_fragsB(nxtB, 0, b0);
         mma_block<FA, FB, NI, NJ>(acc, a1, b1);
@@ -375,19 +442,20 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
             const int kp = kt + 2 + touch_ahead;
             const bool on = touch_ahead > 0 && kp < nk;
             touch_sink ^= touchA[parity] ^ touchB[parity];          // issued two steps ago: long landed
-            touchA[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, on ? (TA ? kp * BK * ldA : kp * BK) : kOutOfRange, 0);
-            touchB[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, on ? (TB ? kp * BK * ldB : kp * BK) : kOutOfRange, 0);
+            touchA[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, on ? (TA ? (kb + kp) * BK * ldA : (kb + kp) * BK) : kOutOfRange, 0);
+            touchB[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, on ? (TB ? (kb + kp) * BK * ldB : (kb + kp) * BK) : kOutOfRange, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
+    if (!fixup) {
     // both stages are requested at once; only the first has to have landed before the first fragments
-    issue_loads(ldsA0, ldsB0, 0);
-    issue_loads(ldsA1, ldsB1, nk > 1 ? BK : -1);
+    issue_loads(ldsA0, ldsB0, kb * BK);
+    issue_loads(ldsA1, ldsB1, nk > 1 ? (kb + 1) * BK : -1);
     if constexpr (kTouch) {                       // keep "two touch loads are the newest" true from the start
         const bool on = touch_ahead > 0 && 2 < nk;
-        touchA[1] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, on ? (TA ? 2 * BK * ldA : 2 * BK) : kOutOfRange, 0);
-        touchB[1] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, on ? (TB ? 2 * BK * ldB : 2 * BK) : kOutOfRange, 0);
+        touchA[1] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, on ? (TA ? (kb + 2) * BK * ldA : (kb + 2) * BK) : kOutOfRange, 0);
+        touchB[1] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, on ? (TB ? (kb + 2) * BK * ldB : (kb + 2) * BK) : kOutOfRange, 0);
     }
     wait_vmcnt<kLoadsPerStep + (kTouch ? 2 : 0)>();
     lds_barrier();
@@ -410,13 +478,41 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
         asm volatile("" ::"v"(touch_sink));
     }
     stamp(2);
+    } else {
+        // Fix-up launch: the accumulators are the sums of the pieces the sharing workgroups left, added in the
+        // order of their K ranges; one row of 32 x 32 blocks at a time (4 NJ loads of 16 bytes in flight per lane:
+        // the launch has one workgroup per shared tile and is bound by the latency of these loads).
+        constexpr int kTileFloats = BM * BN;
+        for (int c = 0; c < nk; ++c) {
+            const v4f* src = reinterpret_cast<const v4f*>(plan.partials + (size_t)(slot + c) * kTileFloats) + threadIdx.x;
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                v4f v[NJ][4];
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) v[j][g] = __builtin_nontemporal_load(src + ((i * NJ + j) * 4 + g) * kGemmThreads);
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] += v[j][g][e];
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
     // The workgroup that follows on this XCD (id + next_stride: same XCD, and dispatched about when this
     // one retires) starts with two slabs of its own operands; one dword per 128-byte line of them is
     // requested here, so that they reach the L2 while this workgroup is busy with its epilogue.
     int next_touch[4] = {0, 0, 0, 0};
     if constexpr (kTouch) {
         int ntr, ntc;
-        if (next_stride > 0 && T >= 2 * BK && tile_of_block(blockIdx.x + next_stride, tiles_r, tiles_c, band_rows, ntr, ntc)) {
+        // (plain kernel only: the workgroups that share tiles have no such successor)
+        const int next_pid = (int)blockIdx.x + next_stride;
+        const int next_pos = (!SPLIT && next_stride > 0 && T >= 2 * BK) ? walk_position(next_pid, plan.n_whole) : -1;
+        if (next_pos >= 0) {
+            tile_of_position(next_pos, tiles_r, tiles_c, band_rows, ntr, ntc);
             if constexpr (TA) {                   // memory rows 0 .. 255, one per thread, kLines lines each
                 const uint8_t* na = A + (size_t)threadIdx.x * ldA + (size_t)ntr * BM;
                 next_touch[0] = *reinterpret_cast<const int*>(na);
@@ -553,7 +649,24 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
         }
     }
     };
-    if (one_mul) write_out(BoolTag<false>{}); else write_out(BoolTag<true>{});
+    if (SPLIT && !fixup && slot >= 0) {
+        // a piece of a shared tile: the accumulators as they are, 16 bytes per lane and store, 4 KB per store
+        // of the workgroup; the fix-up launch reads them back in the same arrangement
+        v4f* dst = reinterpret_cast<v4f*>(plan.partials + (size_t)slot * (BM * BN)) + threadIdx.x;
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    dst[((i * NJ + j) * 4 + g) * kGemmThreads] = v4f{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    } else if (one_mul) {
+        write_out(BoolTag<false>{});
+    } else {
+        write_out(BoolTag<true>{});
+    }
     if constexpr (kTouch) asm volatile("" ::"v"(next_touch[0] ^ next_touch[1] ^ next_touch[2] ^ next_touch[3]));
     unsigned mag = (unsigned)__builtin_bit_cast(uint16_t, (__bf16)maxabs);   // non-negative: magnitude bits
     if (amax_bits) {
@@ -579,7 +692,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
 struct TileChoice {
     int ni, nj;       // 0, 0: no tuned tile divides the problem, use the generic kernel
 };
-TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus);
+// scratch_bytes: what the launch may use for the pieces of shared tiles (0: every tile is computed whole)
+TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus, size_t scratch_bytes);
 
 // Distance of the L2 touch loads in K steps beyond the slab the direct-to-LDS loads are fetching (measured with
 // bands 4 high on the block configurations: 1 is 0.5-0.8 % faster than 2, 3 and 4 lose 1.5 % and 4 %);
@@ -607,19 +721,106 @@ inline bool touch_next(bool by_default) {
     return by_default;
 }
 
+// Workgroups of the tile kernel resident on the chip at once (a multiple of the XCD count);
+// LLMQ_GEMM_SLOTS overrides it for tests, so that small problems meet the many-rounds code paths.
+inline int resident_slots(int num_cus, int ni, int nj) {
+    if (const char* e = tuning_env("LLMQ_GEMM_SLOTS")) { const int v = atoi(e); if (v >= kXcds && v % kXcds == 0) return v; }
+    return (num_cus / kXcds) * kXcds * ((ni == 2 && nj == 2) ? 2 : 1);
+}
+
+// The tile shape whose kernels exist in the tile-sharing form (for contraction-contiguous operands only): the
+// largest one, which is what problems big enough to have a ragged last round worth sharing get.
+constexpr bool split_supported(int ni, int nj) { return ni == 4 && nj == 4; }
+
+// How a problem of nt tiles x nk K steps is shared out (see SplitPlan), and what it is expected to cost.
+struct SplitChoice {
+    int n_whole;             // tiles computed whole by the leading workgroups
+    int n_groups;            // 0: nothing is shared
+    SplitGroup group[kMaxSplitGroups];
+    int shared_tiles;        // tiles in the groups
+    int share_wgs;           // workgroups of the groups (padded)
+    size_t slots;            // binary32 tiles of scratch the launch may write (0: nothing is shared)
+    double cost_us;          // model time of the whole launch
+    double whole_cost_us;    // the same with every tile computed whole
+};
+
+// The r tiles of a ragged last round are served in groups: as long as at least half the chip's worth of tiles is
+// left, half a chip's worth is cut in two; what is left below that is cut into as many pieces as fill the chip
+// once (r = 192 on 256 CUs: 128 tiles in halves, 64 in quarters).  cost_us is a rough time model in microseconds
+// (~1.25 us per K step of a 256 x 256 tile, ~7 us of prologue + epilogue per tile or piece, ~4 TB/s for the
+// partial results written and read back, ~4 us for the extra launches); it only scales the tile choice.
+// Whether sharing is used at all is decided by what was measured on the chip, which is power-limited on real
+// data: CUs left idle by a ragged round let the busy ones clock higher, so a round a fifth to a half full costs
+// 0.4-0.9 of a full one, while the pieces launch costs its K steps + ~30 us and the fix-up launch 45-70 us.
+// Sharing won (3-7 % of the GEMM) only for long contractions (T >= 16384) with all left-over tiles in one
+// group of pieces of at least 24 K steps; it lost 4-13 % on shorter contractions and with several groups.
+inline SplitChoice choose_split(int nt, int nk, int slots, int ni, int nj, size_t scratch_bytes) {
+    const double unit = 1.25 * ni * nj / 16.0, ovh = 7.0;
+    const double tile_f32 = 4.0 * 4096 * ni * nj, tile_out = 2.0 * 4096 * ni * nj;
+    const int rounds = (nt + slots - 1) / slots;
+    SplitChoice whole{};
+    whole.n_whole = nt;
+    whole.cost_us = whole.whole_cost_us = rounds * (nk * unit + ovh);
+    const int full = nt / slots, r = nt - full * slots;
+    const char* force = tuning_env("LLMQ_GEMM_SPLIT");
+    if (r == 0 || nk < 2 || !split_supported(ni, nj) || (force && force[0] == '0')) return whole;
+    int min_steps = 8;                             // shorter pieces are all overhead
+    int forced_pieces = 0;                         // tests: LLMQ_GEMM_SPLIT=a<n> cuts every left-over tile into n pieces
+    if (force && force[0] == 'a') { forced_pieces = atoi(force + 1); min_steps = 1; }
+    SplitChoice c{};
+    c.n_whole = full * slots;
+    c.whole_cost_us = whole.whole_cost_us;
+    c.cost_us = full * (nk * unit + ovh);
+    int left = r, tile_at = 0, wg_at = 0;
+    double pieces_total = 0;
+    while (left > 0 && c.n_groups < kMaxSplitGroups) {
+        int pieces = forced_pieces > 0 ? forced_pieces : left * 2 >= slots ? 2 : slots / left;
+        if (pieces > nk / min_steps) pieces = nk / min_steps;
+        if (pieces < 1) pieces = 1;
+        if (c.n_groups == kMaxSplitGroups - 1 && forced_pieces == 0 && pieces * left > slots) pieces = 1;   // last group takes all that is left
+        int tiles = pieces > 1 ? slots / pieces : left;
+        if (tiles > left) tiles = left;
+        if (tiles < 1) { tiles = left; pieces = 1; }
+        const int steps = (nk + pieces - 1) / pieces;
+        pieces = (nk + steps - 1) / steps;         // no empty last piece
+        SplitGroup& g = c.group[c.n_groups++];
+        g.tile_begin = tile_at; g.tiles = tiles; g.pieces = pieces; g.steps = steps; g.wg_begin = wg_at;
+        g.wgs = ((tiles * pieces + kXcds - 1) / kXcds) * kXcds;
+        tile_at += tiles; wg_at += g.wgs; left -= tiles;
+        c.cost_us += ((tiles * pieces + slots - 1) / slots) * (steps * unit + ovh);
+        if (pieces > 1) pieces_total += (double)tiles * pieces;
+    }
+    if (left > 0) return whole;                    // does not fit the groups
+    c.shared_tiles = r;
+    c.share_wgs = wg_at;
+    c.slots = (size_t)wg_at;
+    if (pieces_total == 0) return whole;
+    c.cost_us += 4.0 + (2.0 * pieces_total * tile_f32 + r * tile_out) / 4.0e6;
+    if ((double)c.slots * tile_f32 > (double)scratch_bytes) return whole;
+    // LLMQ_GEMM_SPLIT=1 or a<n>: whenever possible; otherwise only where it was measured to win
+    if (!force && !(nk >= 128 && c.n_groups == 1 && c.group[0].steps >= 24)) return whole;
+    if (c.cost_us > whole.cost_us) c.cost_us = whole.cost_us;
+    return c;
+}
+
 template <int FA, int FB, int NI, int NJ, bool TA = false, bool TB = false>
 static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
                         const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
-                        hipStream_t stream, int num_cus) {
+                        hipStream_t stream, int num_cus, GemmScratch scratch) {
     const int tiles_r = (int)(R / (64 * NI)), tiles_c = (int)(C / (64 * NJ));
     const int nt = tiles_r * tiles_c;
-    const int grid = ((nt + kXcds - 1) / kXcds) * kXcds;
     const int touch = (NI == 2 && NJ == 2) ? touch_ahead_pair() : touch_ahead();
-    // workgroups resident on the chip at once (a multiple of the XCD count): the distance to the
-    // workgroup that takes over a slot
+    // workgroups resident on the chip at once: the distance to the workgroup that takes over a slot
     // (measured: +3 % on a GEMM of 19 rounds of tiles, whose later workgroups otherwise start on cold
     // operands; nothing or slightly less on GEMMs of 2-4 rounds, so it is used from 6 rounds on)
-    const int slots = (num_cus / kXcds) * kXcds * ((NI == 2 && NJ == 2) ? 2 : 1);
+    const int slots = resident_slots(num_cus, NI, NJ);
+    const SplitChoice sc = choose_split(nt, (int)(T / BK), slots, NI, NJ, (scratch.ptr && !TA && !TB && FA != kFmtBf16) ? scratch.bytes : 0);
+    SplitPlan plan{};
+    plan.n_whole = sc.n_whole;
+    plan.n_groups = sc.n_groups;
+    for (int g = 0; g < sc.n_groups; ++g) plan.group[g] = sc.group[g];
+    plan.partials = scratch.ptr;
+    const int grid = ((sc.n_whole + kXcds - 1) / kXcds) * kXcds;        // of the plain kernel
     // Touch shares (LLMQ_GEMM_SHARE_A / _B override them): the band_rows tile rows that run side by side on an
     // XCD cover a B slab together, each a different part.  Of the tile columns side by side (the XCD's workgroups
     // / band_rows: 8 at band height 4) four cover an A slab together, so every A line is requested by two
@@ -630,14 +831,28 @@ static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C
     if (const char* e = tuning_env("LLMQ_GEMM_SHARE_A")) { const int v = atoi(e); if (v >= 1 && v <= 64) share_a = v; }
     if (const char* e = tuning_env("LLMQ_GEMM_SHARE_B")) { const int v = atoi(e); if (v >= 1 && v <= 64) share_b = v; }
     const int next_stride = touch_next(nt >= 6 * slots) ? slots : 0;
-    if (accumulate)
-        hipLaunchKernelGGL((gemm_tile_kernel<FA, FB, NI, NJ, true, GemmTuning, TA, TB>), dim3(grid), dim3(kGemmThreads), 0, stream,
+    auto launch = [&](auto kernel, int blocks, const SplitPlan& pl) {
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kGemmThreads), 0, stream,
                            A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c,
-                           touch, band, next_stride, (int)R, (int)C, share_a, share_b);
-    else
-        hipLaunchKernelGGL((gemm_tile_kernel<FA, FB, NI, NJ, false, GemmTuning, TA, TB>), dim3(grid), dim3(kGemmThreads), 0, stream,
-                           A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c,
-                           touch, band, next_stride, (int)R, (int)C, share_a, share_b);
+                           touch, band, next_stride, (int)R, (int)C, share_a, share_b, pl);
+    };
+    // The pieces first (all CUs start and end them together), their sums next, the whole rounds last.
+    if constexpr (split_supported(NI, NJ) && FA != kFmtBf16 && !TA && !TB) {
+        if (sc.n_groups) {
+            SplitPlan fix = plan;
+            fix.fixup = 1;
+            if (accumulate) {
+                launch(gemm_tile_kernel<FA, FB, NI, NJ, true, GemmTuning, TA, TB, true>, sc.share_wgs, plan);
+                launch(gemm_tile_kernel<FA, FB, NI, NJ, true, GemmTuning, TA, TB, true>, sc.shared_tiles, fix);
+            } else {
+                launch(gemm_tile_kernel<FA, FB, NI, NJ, false, GemmTuning, TA, TB, true>, sc.share_wgs, plan);
+                launch(gemm_tile_kernel<FA, FB, NI, NJ, false, GemmTuning, TA, TB, true>, sc.shared_tiles, fix);
+            }
+        }
+    }
+    if (sc.n_whole == 0) return;
+    if (accumulate) launch(gemm_tile_kernel<FA, FB, NI, NJ, true, GemmTuning, TA, TB>, grid, plan);
+    else launch(gemm_tile_kernel<FA, FB, NI, NJ, false, GemmTuning, TA, TB>, grid, plan);
 }
 
 
@@ -645,11 +860,11 @@ static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C
 template <int FA, int FB, bool TA, bool TB>
 static bool launch_chosen_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
                                const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
-                               hipStream_t stream, int num_cus) {
-    const TileChoice tc = choose_tile(R, C, T, num_cus);
+                               hipStream_t stream, int num_cus, GemmScratch scratch) {
+    const TileChoice tc = choose_tile(R, C, T, num_cus, (scratch.ptr && !TA && !TB && FA != kFmtBf16) ? scratch.bytes : 0);
 #define LLMQ_TILE_CASE(I, J)                                                                              \
     case I * 8 + J:                                                                                       \
-        launch_tile<FA, FB, I, J, TA, TB>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus);   \
+        launch_tile<FA, FB, I, J, TA, TB>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus, scratch); \
         return true;
     switch (tc.ni * 8 + tc.nj) {
         LLMQ_TILE_CASE(4, 4) LLMQ_TILE_CASE(4, 3) LLMQ_TILE_CASE(4, 2)

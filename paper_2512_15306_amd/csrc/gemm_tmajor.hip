@@ -16,17 +16,17 @@ void launch_gemm_amax_reset(unsigned* amax, hipStream_t stream);
 template <int FA, int FB>
 static bool launch_layout(bool ta, bool tb, const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
                           const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
-                          hipStream_t stream, int num_cus) {
-    if (ta && tb) return launch_chosen_tile<FA, FB, true, true>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus);
-    if (tb) return launch_chosen_tile<FA, FB, false, true>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus);
-    return launch_chosen_tile<FA, FB, true, false>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus);
+                          hipStream_t stream, int num_cus, GemmScratch scratch) {
+    if (ta && tb) return launch_chosen_tile<FA, FB, true, true>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus, scratch);
+    if (tb) return launch_chosen_tile<FA, FB, false, true>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus, scratch);
+    return launch_chosen_tile<FA, FB, true, false>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus, scratch);
 }
 
 int launch_gemm_fp8(const uint8_t* A, int fmtA, bool ta, const uint8_t* B, int fmtB, bool tb, int64_t R, int64_t C,
                     int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16, int accumulate,
-                    float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus) {
+                    float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus, GemmScratch scratch) {
     if (!ta && !tb)
-        return launch_gemm_tn(A, fmtA, B, fmtB, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, d_amax_c, amax_is_zeroed, stream, num_cus);
+        return launch_gemm_tn(A, fmtA, B, fmtB, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, d_amax_c, amax_is_zeroed, stream, num_cus, scratch);
     unsigned* amax = reinterpret_cast<unsigned*>(d_amax_c);
     if (amax && !amax_is_zeroed) launch_gemm_amax_reset(amax, stream);
     // The tile kernel addresses a T-major operand with 32-bit byte offsets from its first tile column and
@@ -36,8 +36,8 @@ int launch_gemm_fp8(const uint8_t* A, int fmtA, bool ta, const uint8_t* B, int f
     const bool fits = (!ta || (T + 256) * R < lim) && (!tb || (T + 256) * C < lim);
     bool done = false;
     if (fits && fmtB == 0) {
-        if (fmtA == 0) done = launch_layout<0, 0>(ta, tb, A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus);
-        else done = launch_layout<1, 0>(ta, tb, A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus);
+        if (fmtA == 0) done = launch_layout<0, 0>(ta, tb, A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus, scratch);
+        else done = launch_layout<1, 0>(ta, tb, A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus, scratch);
     }
     if (!done) launch_gemm_generic(A, fmtA, ta, B, fmtB, tb, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream);
     return hipGetLastError() == hipSuccess ? 0 : -6;

@@ -52,15 +52,24 @@ int launch_quantize_from(const void* x, int64_t rows, int64_t cols, const ScaleS
 // First stage of the absmax only: one BF16 magnitude pattern per workgroup into partial; returns the number
 // of workgroups (<= kAmaxMaxPartials) through n_partial.
 int launch_amax_partial(const void* x, size_t n, unsigned* partial, int* n_partial, hipStream_t stream, int num_cus);
+// Caller-owned device scratch for the binary32 pieces of output tiles whose contraction is shared among
+// several workgroups (a ragged last round of tiles); {nullptr, 0}: every tile is computed by one workgroup.
+struct GemmScratch {
+    float* ptr;
+    size_t bytes;
+};
+// What a contraction of this shape would use of it (0: nothing).
+size_t gemm_scratch_bytes(int64_t R, int64_t C, int64_t T, int num_cus);
 int launch_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64_t R, int64_t C,
                    int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16,
-                   int accumulate, float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus);
+                   int accumulate, float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus,
+                   GemmScratch scratch);
 
 // The same contraction with either operand optionally T-major: ta: A is [T, R], tb: B is [T, C] (the
 // contraction index runs down the rows), so the backward GEMMs can read the untransposed quantized tensors.
 int launch_gemm_fp8(const uint8_t* A, int fmtA, bool ta, const uint8_t* B, int fmtB, bool tb, int64_t R, int64_t C,
                     int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16, int accumulate,
-                    float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus);
+                    float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus, GemmScratch scratch);
 
 // SwiGLU with its extra outputs.  h, d_amax (with partial, the per-workgroup scratch), q and q_t are
 // optional; q_fmt is only read when q is given.  swiglu_blocks() is the number of scratch words.

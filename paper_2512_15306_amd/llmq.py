@@ -25,7 +25,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libllmq.so")
 _lib = None
 
-EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "llmq_amax", "llmq_amax_static", "llmq_quantize_fp8", "llmq_fp8_gemm_tn", "llmq_fp8_gemm", "llmq_bf16_gemm_tn",
+EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "llmq_amax", "llmq_amax_static", "llmq_quantize_fp8", "llmq_fp8_gemm_tn", "llmq_fp8_gemm", "llmq_fp8_gemm_scratch_bytes", "llmq_fp8_gemm_with_scratch", "llmq_bf16_gemm_tn",
            "llmq_fp8_linear_workspace_bytes", "llmq_fp8_linear_workspace_bytes_no_transpose", "llmq_fp8_linear_workspace_offsets",
            "llmq_fp8_linear_fwd", "llmq_fp8_linear_dgrad", "llmq_fp8_linear_wgrad",
            "llmq_scale_from_amax", "llmq_swiglu_workspace_bytes", "llmq_swiglu_fwd", "llmq_swiglu_fwd_fp8",
@@ -66,6 +66,10 @@ def lib() -> ctypes.CDLL:
     L.llmq_fp8_gemm_tn.argtypes = [vp, i32, vp, i32, i64, i64, i64, vp, vp, vp, i32, vp, vp]
     L.llmq_fp8_gemm.restype = i32
     L.llmq_fp8_gemm.argtypes = [vp, i32, i32, vp, i32, i32, i64, i64, i64, vp, vp, vp, i32, vp, vp]
+    L.llmq_fp8_gemm_scratch_bytes.restype = sz
+    L.llmq_fp8_gemm_scratch_bytes.argtypes = [i64, i64, i64]
+    L.llmq_fp8_gemm_with_scratch.restype = i32
+    L.llmq_fp8_gemm_with_scratch.argtypes = [vp, i32, i32, vp, i32, i32, i64, i64, i64, vp, vp, vp, i32, vp, vp, sz, vp]
     L.llmq_bf16_gemm_tn.restype = i32
     L.llmq_bf16_gemm_tn.argtypes = [vp, vp, i64, i64, i64, vp, i32, vp]
     L.llmq_fp8_linear_workspace_bytes.restype = sz
@@ -185,6 +189,27 @@ def llmq_fp8_gemm(A: torch.Tensor, fmtA: int, a_t_major: bool, B: torch.Tensor, 
                                int(bool(b_t_major)), R, C, T, _dev(d_scaleA, torch.float32),
                                _dev(d_scaleB, torch.float32), _dev(c, torch.bfloat16, "c"), int(bool(accumulate)),
                                _dev(d_amax_c, torch.float32), _stream()), "llmq_fp8_gemm")
+
+
+def llmq_fp8_gemm_scratch_bytes(R: int, C: int, T: int) -> int:
+    return int(lib().llmq_fp8_gemm_scratch_bytes(R, C, T))
+
+
+def llmq_fp8_gemm_with_scratch(A: torch.Tensor, fmtA: int, a_t_major: bool, B: torch.Tensor, fmtB: int, b_t_major: bool,
+                               d_scaleA: torch.Tensor, d_scaleB: torch.Tensor, c: torch.Tensor, accumulate: bool,
+                               d_amax_c: Optional[torch.Tensor], scratch: Optional[torch.Tensor]) -> None:
+    """llmq_fp8_gemm with scratch (a uint8 tensor or None) for sharing out a ragged last round of tiles."""
+    T, R = A.shape if a_t_major else A.shape[::-1]
+    T2, C = B.shape if b_t_major else B.shape[::-1]
+    if T != T2 or tuple(c.shape) != (R, C):
+        raise ValueError("shape mismatch: A %s, B %s, c %s" % (tuple(A.shape), tuple(B.shape), tuple(c.shape)))
+    _check(lib().llmq_fp8_gemm_with_scratch(_dev(A, torch.uint8, "A"), fmtA, int(bool(a_t_major)), _dev(B, torch.uint8, "B"),
+                                            fmtB, int(bool(b_t_major)), R, C, T, _dev(d_scaleA, torch.float32),
+                                            _dev(d_scaleB, torch.float32), _dev(c, torch.bfloat16, "c"),
+                                            int(bool(accumulate)), _dev(d_amax_c, torch.float32),
+                                            _dev(scratch, torch.uint8, "scratch"),
+                                            0 if scratch is None else scratch.numel(), _stream()),
+           "llmq_fp8_gemm_with_scratch")
 
 
 def llmq_bf16_gemm_tn(A: torch.Tensor, B: torch.Tensor, c: torch.Tensor, accumulate: bool = False) -> None:

@@ -10,6 +10,7 @@
 #include "../../paper_2512_15306_amd/csrc/llmq_kernels.h"
 
 static int g_launches = 0;
+static size_t g_scratch_seen = 0;
 namespace llmq {
 int launch_amax(const void*, size_t, int, float*, float*, void*, hipStream_t, int) { ++g_launches; return 0; }
 int launch_amax_static(const void*, size_t, int, float*, float*, hipStream_t, int) { ++g_launches; return 0; }
@@ -19,8 +20,9 @@ int launch_scale_from_amax(const float*, int, float*, hipStream_t) { ++g_launche
 int launch_quantize(const void*, int64_t, int64_t, const float*, int, uint8_t*, uint8_t*, unsigned*, hipStream_t) { ++g_launches; return 0; }
 int launch_quantize_from(const void*, int64_t, int64_t, const ScaleSource&, int, uint8_t*, uint8_t*, unsigned*, hipStream_t) { ++g_launches; return 0; }
 int launch_amax_partial(const void*, size_t, unsigned*, int* n_partial, hipStream_t, int) { ++g_launches; *n_partial = 7; return 0; }
-int launch_gemm_tn(const uint8_t*, int, const uint8_t*, int, int64_t, int64_t, int64_t, const float*, const float*, void*, int, float*, bool, hipStream_t, int) { ++g_launches; return 0; }
-int launch_gemm_fp8(const uint8_t*, int, bool, const uint8_t*, int, bool, int64_t, int64_t, int64_t, const float*, const float*, void*, int, float*, bool, hipStream_t, int) { ++g_launches; return 0; }
+size_t gemm_scratch_bytes(int64_t R, int64_t C, int64_t, int) { return (size_t)((R / 256) * (C / 256) % 7) * 262144; }
+int launch_gemm_tn(const uint8_t*, int, const uint8_t*, int, int64_t, int64_t, int64_t, const float*, const float*, void*, int, float*, bool, hipStream_t, int, GemmScratch sc) { ++g_launches; g_scratch_seen = sc.ptr ? sc.bytes : 0; return 0; }
+int launch_gemm_fp8(const uint8_t*, int, bool, const uint8_t*, int, bool, int64_t, int64_t, int64_t, const float*, const float*, void*, int, float*, bool, hipStream_t, int, GemmScratch sc) { ++g_launches; g_scratch_seen = sc.ptr ? sc.bytes : 0; return 0; }
 int64_t swiglu_blocks(int64_t M, int64_t I) { return (M + 31) / 32 * ((I + 255) / 256); }
 int launch_swiglu_fwd(const void*, int64_t, int64_t, void*, unsigned*, int, float*, float*, const float*, int, uint8_t*, uint8_t*, hipStream_t) { ++g_launches; return 0; }
 int launch_swiglu_bwd(const void*, const void*, int64_t, int64_t, void*, unsigned*, int, float*, float*, hipStream_t) { ++g_launches; return 0; }
@@ -71,6 +73,12 @@ int main() {
     EXPECT(llmq_fp8_gemm_tn(B8, 0, B8, 3, 256, 256, 128, F, F, P, 0, F, nullptr), LLMQ_ERR_FORMAT, 0);
     EXPECT(llmq_fp8_gemm(B8, 1, 1, B8, 0, 1, 256, 256, 128, F, F, P, 1, nullptr, nullptr), LLMQ_OK, 1);
     EXPECT(llmq_fp8_gemm(B8, 1, 1, B8, 0, 1, 256, 0, 128, F, F, P, 1, nullptr, nullptr), LLMQ_ERR_SHAPE, 0);
+    EXPECT(llmq_fp8_gemm_with_scratch(B8, 1, 0, B8, 0, 1, 256, 256, 128, F, F, P, 0, nullptr, P, 1 << 20, nullptr), LLMQ_OK, 1);
+    if (g_scratch_seen != (1u << 20)) ++g_fail;
+    EXPECT(llmq_fp8_gemm_with_scratch(B8, 1, 0, B8, 0, 1, 256, 256, 128, F, F, P, 0, nullptr, nullptr, 1 << 20, nullptr), LLMQ_OK, 1);
+    if (g_scratch_seen != 0) ++g_fail;
+    EXPECT(llmq_fp8_gemm_with_scratch(B8, 1, 0, B8, 0, 1, 256, 256, 128, F, F, P, 0, nullptr, odd, 1 << 20, nullptr), LLMQ_ERR_ALIGN, 0);
+    if (llmq_fp8_gemm_scratch_bytes(0, 256, 128) != 0) ++g_fail;
     EXPECT(llmq_bf16_gemm_tn(P, P, 256, 256, 64, P, 0, nullptr), LLMQ_OK, 1);
     EXPECT(llmq_bf16_gemm_tn(P, nullptr, 256, 256, 64, P, 0, nullptr), LLMQ_ERR_NULL, 0);
     // the three linear calls: explicit scales (quantize x2 + GEMM), just-in-time scaling (first absmax stage +
