@@ -44,6 +44,9 @@ def parse():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--prequantized-w", action="store_true",
                    help="weights quantized once outside the timed region (reused across micro-steps)")
+    p.add_argument("--power-probe", action="store_true",
+                   help="instead of the benchmark: one 8192^3 FP8 GEMM on operands of different bit content (zeros, one "
+                        "constant, quantized Gaussian data, random codes) with the board power sampled from sysfs")
     return p.parse_args()
 
 
@@ -258,6 +261,91 @@ def measure_rmsnorm(cfg, dev, reps):
     return out
 
 
+def power_probe(dev):
+    """The same 8192 x 8192 x 8192 contraction on operands that differ only in their bits, each run for about a
+    second while a thread samples the board power (hwmon power1_input, microwatts).  Shows what bounds the GEMM
+    on real data: the power cap, not the kernel."""
+    import glob
+    import threading
+    import torch
+    from paper_2512_15306_amd import llmq
+    hw = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*"))
+
+    def read(name):
+        for h in hw:
+            try:
+                return float(open(os.path.join(h, name)).read())
+            except (OSError, ValueError):
+                pass
+        return None
+
+    class Poller(threading.Thread):
+        def __init__(self):
+            super().__init__(daemon=True)
+            self.stop, self.samples = False, []
+
+        def run(self):
+            while not self.stop:
+                v = read("power1_input")
+                if v is None:
+                    v = read("power1_average")
+                if v is not None:
+                    self.samples.append(v / 1e6)
+                time.sleep(0.02)
+
+    n = 8192
+    g = torch.Generator(device=dev)
+    g.manual_seed(5)
+    aws = torch.empty(llmq.llmq_amax_workspace_bytes(), dtype=torch.uint8, device=dev)
+    f = torch.zeros(2, dtype=torch.float32, device=dev)
+
+    def quantized(x):                       # through the library: absmax scale, E4M3 codes
+        q = torch.empty((n, n), dtype=torch.uint8, device=dev)
+        llmq.llmq_amax(x, llmq.E4M3, f[0:1], f[1:2], aws)
+        llmq.llmq_quantize_fp8(x, f[1:2], llmq.E4M3, q, None)
+        return q
+
+    def operand(kind, seed):
+        g.manual_seed(seed)
+        if kind == "zeros":
+            return torch.zeros((n, n), dtype=torch.uint8, device=dev)
+        if kind == "one_constant":
+            return torch.full((n, n), 0x38, dtype=torch.uint8, device=dev)
+        if kind == "quantized_gaussian":
+            return quantized(torch.randn((n, n), generator=g, device=dev).to(torch.bfloat16))
+        if kind == "quantized_gaussian_outlier_channels":      # 0.5 % of the columns x 50, as config 3's activations
+            x = torch.randn((n, n), generator=g, device=dev)
+            x[:, torch.randperm(n, generator=torch.Generator().manual_seed(seed))[:41].to(dev)] *= 50.0
+            return quantized(x.to(torch.bfloat16))
+        # random finite codes: random sign and mantissa, exponent field 3 .. 10
+        e = torch.randint(3, 11, (n, n), generator=g, device=dev, dtype=torch.int32)
+        m = torch.randint(0, 8, (n, n), generator=g, device=dev, dtype=torch.int32)
+        sg = torch.randint(0, 2, (n, n), generator=g, device=dev, dtype=torch.int32)
+        return ((sg << 7) | (e << 3) | m).to(torch.uint8)
+
+    one = torch.ones(1, dtype=torch.float32, device=dev)
+    c = torch.empty((n, n), dtype=torch.bfloat16, device=dev)
+    out = {"what": "8192^3 E4M3 x E4M3 GEMM (llmq_fp8_gemm_tn), about one second per operand pattern, board power "
+                   "from hwmon power1_input sampled every 20 ms (second half of the run averaged)",
+           "power_cap_watts": (read("power1_cap") or 0) / 1e6, "patterns": {}}
+    for kind in ("zeros", "one_constant", "quantized_gaussian_outlier_channels", "quantized_gaussian", "random_codes"):
+        A, B = operand(kind, 11), operand(kind, 12)
+        fn = lambda: llmq.llmq_fp8_gemm_tn(A, 0, B, 0, one, one, c, False, None)
+        ms1 = timed(fn, 20)
+        reps = max(50, int(1000.0 / ms1))
+        p = Poller()
+        p.start()
+        ms = timed(fn, reps)
+        p.stop = True
+        p.join()
+        half = p.samples[len(p.samples) // 2:]
+        out["patterns"][kind] = {"tflops": round(2.0 * n ** 3 / (ms * 1e-3) / 1e12, 1), "ms": round(ms, 4),
+                                 "watts": round(sum(half) / len(half), 1) if half else None, "samples": len(half)}
+        del A, B
+        time.sleep(0.5)
+    return out
+
+
 def cpu_baseline(cfg):
     """The oracle as it stands on a bounded sample: the largest linear of the block restricted to the
     first rows of the token dimension, whole path (3 absmax, 3 quantize+transpose, 3 fp64 GEMMs)."""
@@ -387,6 +475,9 @@ def main():
     llmq.lib()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.power_probe:
+        print(json.dumps({"power_probe": power_probe(dev)}))
+        return
     cfg = synth.CONFIGS[args.config or HEADLINE_CONFIG]
     peaks = measure_peaks(dev)
     r = measure_config(cfg, args, dev, full=True)

@@ -112,6 +112,68 @@ __global__ __launch_bounds__(kQThreads) void quantize_patch_kernel(
     }
 }
 
+// Workgroup-tile variant for tensors whose rows are a multiple of 128 and whose columns a multiple of 256 (every
+// benchmark tensor): full 128-byte lines on all three streams.  A lane owns the same 16 x 8 patch, but a wave is
+// 4 lanes stacked x 16 side by side (64 rows x 128 columns), so that its loads cover 256 contiguous bytes of a
+// row and its row-major stores a whole 128-byte line; the four waves tile 128 rows x 256 columns.  The transposed
+// copy cannot be written that way from registers (4 stacked lanes hold 64 contiguous bytes of a transposed row),
+// so the transposed patches go through LDS: every lane writes its eight 16-byte column pieces into a
+// [256 columns][128 rows] byte tile (rows padded to 144 bytes against bank conflicts), and after one barrier the
+// workgroup writes the tile out, 8 lanes per transposed row = one 128-byte line per group of 8 lanes.
+constexpr int kTileRows = 128, kTileCols = 256, kTilePitch = kTileRows + 16;
+
+template <int FMT>
+__global__ __launch_bounds__(kQThreads) void quantize_tile_kernel(
+    const uint16_t* __restrict__ x, int64_t rows, int64_t cols, const ScaleSource scale_src,
+    uint8_t* __restrict__ q, uint8_t* __restrict__ qt, unsigned* __restrict__ zero_word, unsigned grid_cols) {
+    __shared__ unsigned s_part[kQThreads / kWave];
+    __shared__ __attribute__((aligned(16))) uint8_t s_t[kTileCols * kTilePitch];
+    if (zero_word && blockIdx.x == 0 && threadIdx.x == 0) *zero_word = 0u;
+    const float s = resolve_scale(scale_src, blockIdx.x == 0, s_part);
+    const unsigned brow = blockIdx.x / grid_cols, bcol = blockIdx.x - brow * grid_cols;   // along the columns first
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int tr = (wave >> 1) * 64 + (lane & 3) * kPatchRows;      // patch origin inside the tile
+    const int tc = (wave & 1) * 128 + (lane >> 2) * 8;
+    const int64_t r0 = (int64_t)brow * kTileRows + tr, c0 = (int64_t)bcol * kTileCols + tc;
+    v4u in[kPatchRows];
+    const uint16_t* src = x + r0 * cols + c0;
+#pragma unroll
+    for (int i = 0; i < kPatchRows; ++i) in[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(src + (int64_t)i * cols));
+    __builtin_amdgcn_sched_barrier(0);
+    unsigned w[kPatchRows][2];
+#pragma unroll
+    for (int i = 0; i < kPatchRows; ++i) quantize8<FMT>(in[i], s, w[i][0], w[i][1]);
+    uint8_t* dst = q + r0 * cols + c0;
+#pragma unroll
+    for (int i = 0; i < kPatchRows; ++i) *reinterpret_cast<v2u*>(dst + (int64_t)i * cols) = v2u{w[i][0], w[i][1]};
+    // column j of the patch -> 16 consecutive bytes of row (tc + j) of the LDS tile, at byte tr
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        unsigned col[4][4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            unsigned blk[4] = {w[4 * t][k], w[4 * t + 1][k], w[4 * t + 2][k], w[4 * t + 3][k]};
+            unsigned o[4];
+            transpose4x4_bytes(blk, o);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) col[c][t] = o[c];
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            *reinterpret_cast<v4u*>(s_t + (tc + 4 * k + c) * kTilePitch + tr) = v4u{col[c][0], col[c][1], col[c][2], col[c][3]};
+    }
+    __syncthreads();
+    uint8_t* dt = qt + (int64_t)bcol * kTileCols * rows + (int64_t)brow * kTileRows;
+#pragma unroll
+    for (int m = 0; m < kTileCols * (kTileRows / 16) / kQThreads; ++m) {
+        const int p = threadIdx.x + m * kQThreads;          // 16-byte piece: column p / 8, rows 16 (p % 8) ..
+        const int c = p >> 3, ch = p & 7;
+        const v4u v = *reinterpret_cast<const v4u*>(s_t + c * kTilePitch + ch * 16);
+        *reinterpret_cast<v4u*>(dt + (int64_t)c * rows + ch * 16) = v;
+    }
+}
+
 // No transposed copy wanted: the conversion is element-wise and the tensor can be taken as a flat array.  A
 // workgroup converts kFlatUnits * 256 runs of 8 elements; load j of a wave covers 1 KB of contiguous input,
 // its store 512 contiguous bytes (the patch kernel without the transposed copy writes 64-byte pieces of rows and
@@ -183,6 +245,12 @@ static void launch_patch(const uint16_t* xb, int64_t rows, int64_t cols, const S
     }
 }
 
+// LLMQ_QUANT_TILE=0 / 1 (tuning override): the register-only patch kernel or the workgroup-tile kernel.
+static bool use_tile_kernel() {
+    if (const char* e = tuning_env("LLMQ_QUANT_TILE")) return atoi(e) != 0;
+    return true;
+}
+
 int launch_quantize(const void* x, int64_t rows, int64_t cols, const float* d_scale, int fmt,
                     uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream) {
     const ScaleSource src{d_scale, nullptr, 0, fp8_max(fmt), nullptr};
@@ -197,6 +265,10 @@ int launch_quantize_from(const void* x, int64_t rows, int64_t cols, const ScaleS
         const dim3 grid((unsigned)((n8 + kQThreads * kFlatUnits - 1) / (kQThreads * kFlatUnits)));
         if (fmt == 0) hipLaunchKernelGGL((quantize_flat_kernel<0>), grid, dim3(kQThreads), 0, stream, xb, n8, d_scale, q, zero_word);
         else hipLaunchKernelGGL((quantize_flat_kernel<1>), grid, dim3(kQThreads), 0, stream, xb, n8, d_scale, q, zero_word);
+    } else if (q_t && rows % kTileRows == 0 && cols % kTileCols == 0 && use_tile_kernel()) {
+        const unsigned gc = (unsigned)(cols / kTileCols), gr = (unsigned)(rows / kTileRows);
+        if (fmt == 0) hipLaunchKernelGGL((quantize_tile_kernel<0>), dim3(gr * gc), dim3(kQThreads), 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word, gc);
+        else hipLaunchKernelGGL((quantize_tile_kernel<1>), dim3(gr * gc), dim3(kQThreads), 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word, gc);
     } else if (rows % kPatchRows == 0 && cols % QuantTuning::kPatchCols == 0) {
         launch_patch<QuantTuning>(xb, rows, cols, d_scale, fmt, q, q_t, zero_word, stream);
     } else {
