@@ -28,7 +28,7 @@ PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E, published
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by a plain 1 GiB copy
 # (profiles/bench_config<N>_gemm_quantize_amax.md); None where not measured.  They include hits in the
 # memory-side last-level cache: the 8 XCDs have private L2s and each re-reads the operands of its tiles.
-MEASURED_GEMM_TRAFFIC_BYTES = {2: 222.8e6, 3: 986.6e6, 5: 3792.3e6}
+MEASURED_GEMM_TRAFFIC_BYTES = {2: 223.5e6, 3: 983.4e6, 4: 1096.9e6, 5: 3780.6e6}
 HEADLINE_CONFIG = 5           # the largest single-GPU configuration (32B-class block)
 SIDE_CONFIGS = (3, 4)         # 7B- and 14B-class blocks: reported in the same line
 
@@ -44,6 +44,8 @@ def parse():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--prequantized-w", action="store_true",
                    help="weights quantized once outside the timed region (reused across micro-steps)")
+    p.add_argument("--phase-stamps", action="store_true",
+                   help="instead of the benchmark: cycle stamps of the phases of the GEMM tile kernel on two forward GEMMs")
     p.add_argument("--power-probe", action="store_true",
                    help="instead of the benchmark: one 8192^3 FP8 GEMM on operands of different bit content (zeros, one "
                         "constant, quantized Gaussian data, random codes) with the board power sampled from sysfs")
@@ -346,6 +348,46 @@ def power_probe(dev):
     return out
 
 
+def phase_stamps(dev):
+    """Cycle stamps of the phases of the 256 x 256 tile kernel (llmq_calibrate_gemm_phases) on the forward GEMM of
+    config 3's gate/up projection (19 rounds of tiles, 28 K steps) and of config 2's attention-out projection (one
+    round, 24 K steps), operands quantized from the configs' tensors; averages over the workgroups, for the fused
+    absmax as the library computes it and for the maxNum form it replaced."""
+    import torch
+    from paper_2512_15306_amd import llmq, synth
+    out = {}
+    aws = torch.empty(llmq.llmq_amax_workspace_bytes(), dtype=torch.uint8, device=dev)
+    for ci, li in ((3, 2), (2, 1)):
+        cfg = synth.CONFIGS[ci]
+        lin = cfg.linears[li]
+        f = torch.zeros(5, dtype=torch.float32, device=dev)
+        ops = []
+        for t, sl in ((synth.make_x(cfg, li, device=dev), 0), (synth.make_w(cfg, li, device=dev), 2)):
+            q = torch.empty(t.shape, dtype=torch.uint8, device=dev)
+            llmq.llmq_amax(t, llmq.E4M3, f[sl:sl + 1], f[sl + 1:sl + 2], aws)
+            llmq.llmq_quantize_fp8(t, f[sl + 1:sl + 2], llmq.E4M3, q, None)
+            ops.append(q)
+        c = torch.empty((cfg.M, lin.N), dtype=torch.bfloat16, device=dev)
+        entry = {"R": cfg.M, "C": lin.N, "T": lin.K, "tiles": (cfg.M // 256) * (lin.N // 256), "k_steps": lin.K // 128}
+        for name, ieee in (("ieee_maximum", True), ("maxnum", False)):
+            for _ in range(3):
+                st = llmq.llmq_calibrate_gemm_phases(ops[0], ops[1], f[1:2], f[3:4], c, f[4:5], ieee)
+            torch.cuda.synchronize()
+            s = st.cpu().double()
+            s = s[s[:, 0] > 0]
+            cyc = lambda a, b: float((s[:, b] - s[:, a]).mean())
+            ns = lambda a, b: float((s[:, 8 + b] - s[:, 8 + a]).mean()) * 10.0          # 100 MHz stamps
+            entry[name] = {
+                "workgroups": int(s.shape[0]),
+                "prologue_cycles": round(cyc(0, 1)), "k_loop_cycles": round(cyc(1, 2)),
+                "k_loop_cycles_per_step": round(cyc(1, 2) / (lin.K // 128), 1),
+                "epilogue_to_last_store_issued_cycles": round(cyc(2, 4)), "absmax_tail_cycles": round(cyc(4, 5)),
+                "epilogue_until_stores_complete_cycles": round(cyc(2, 3)), "whole_tile_cycles": round(cyc(0, 3)),
+                "whole_tile_ns": round(ns(0, 3)), "clock_ghz": round(cyc(0, 3) / ns(0, 3), 3)}
+        out["config %d %s forward" % (ci, lin.name)] = entry
+    return out
+
+
 def cpu_baseline(cfg):
     """The oracle as it stands on a bounded sample: the largest linear of the block restricted to the
     first rows of the token dimension, whole path (3 absmax, 3 quantize+transpose, 3 fp64 GEMMs)."""
@@ -475,6 +517,9 @@ def main():
     llmq.lib()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.phase_stamps:
+        print(json.dumps({"phase_stamps": phase_stamps(dev)}))
+        return
     if args.power_probe:
         print(json.dumps({"power_probe": power_probe(dev)}))
         return

@@ -333,6 +333,21 @@ int llmq_rmsnorm_apply_fp8(const void* res_bf16, const void* w_bf16, const float
  * llmq_calibrate_copy: plain device copy of `bytes` (multiple of 16, 16-byte aligned pointers): 2 * bytes of
  *   HBM traffic.
  */
+/*
+ * llmq_calibrate_gemm_phases: one E4M3 x E4M3 contraction (arguments as llmq_fp8_gemm_tn; R, C multiples of 256,
+ *   T a multiple of 128) by the 256 x 256 tile kernel built with phase stamps: wave 0 of every workgroup writes
+ *   the cycle counter into d_stamps[16 * workgroup + s] and the 100 MHz clock into d_stamps[16 * workgroup + 8 + s]
+ *   (64-bit words) for s = 0 start, 1 first operand fragments in registers (end of the prologue), 2 end of the
+ *   contraction loop, 4 last output store issued, 5 absmax done, 3 all stores completed.  Workgroup ids beyond the
+ *   number of tiles leave their words untouched.  d_stamps: device, 8-byte aligned, at least
+ *   llmq_calibrate_gemm_phases_bytes(R, C) bytes.  ieee_maximum != 0: the fused absmax as the library computes
+ *   it (IEEE 754-2019 maximum); 0: the maxNum form it replaced, for comparison.  The results c and d_amax_c are
+ *   those of llmq_fp8_gemm_tn.
+ */
+size_t llmq_calibrate_gemm_phases_bytes(int64_t R, int64_t C);
+int llmq_calibrate_gemm_phases(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
+                               const float* d_scaleA, const float* d_scaleB, void* c_bf16, float* d_amax_c,
+                               void* d_stamps, size_t stamps_bytes, int ieee_maximum, void* stream);
 int llmq_calibrate_mfma(int fmtA, int fmtB, int random_bits, int iters, float* d_sink, double* flops,
                         void* stream);
 int llmq_calibrate_copy(const void* src, void* dst, size_t bytes, void* stream);

@@ -381,6 +381,27 @@ int llmq_calibrate_mfma(int fmtA, int fmtB, int random_bits, int iters, float* d
                                        num_cus());
 }
 
+size_t llmq_calibrate_gemm_phases_bytes(int64_t R, int64_t C) {
+    if (!dim_ok(R) || !dim_ok(C) || R % 256 != 0 || C % 256 != 0) return 0;
+    return (size_t)llmq::gemm_phase_stamp_blocks(R, C) * 16 * sizeof(long long);
+}
+
+int llmq_calibrate_gemm_phases(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T, const float* d_scaleA,
+                               const float* d_scaleB, void* c_bf16, float* d_amax_c, void* d_stamps, size_t stamps_bytes,
+                               int ieee_maximum, void* stream) {
+    if (!A || !B || !d_scaleA || !d_scaleB || !c_bf16 || !d_amax_c || !d_stamps) return LLMQ_ERR_NULL;
+    if (!dim_ok(R) || !dim_ok(C) || !dim_ok(T) || R % 256 != 0 || C % 256 != 0 || T % 128 != 0 || T >= ((int64_t)1 << 23) ||
+        (R / 256) * (C / 256) >= ((int64_t)1 << 30))
+        return LLMQ_ERR_SHAPE;
+    if (!aligned(A, 16) || !aligned(B, 16) || !aligned(c_bf16, 16) || !aligned(d_scaleA, 4) || !aligned(d_scaleB, 4) ||
+        !aligned(d_amax_c, 4) || !aligned(d_stamps, 8))
+        return LLMQ_ERR_ALIGN;
+    if (stamps_bytes < llmq_calibrate_gemm_phases_bytes(R, C)) return LLMQ_ERR_WORKSPACE;
+    return llmq::launch_gemm_phase_stamps(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, d_amax_c,
+                                          static_cast<long long*>(d_stamps), ieee_maximum, static_cast<hipStream_t>(stream),
+                                          num_cus());
+}
+
 int llmq_calibrate_copy(const void* src, void* dst, size_t bytes, void* stream) {
     if (!src || !dst) return LLMQ_ERR_NULL;
     if (bytes < 16 || bytes % 16 != 0 || bytes >= ((size_t)1 << 40)) return LLMQ_ERR_SHAPE;

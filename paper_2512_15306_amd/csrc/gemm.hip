@@ -191,6 +191,44 @@ size_t gemm_scratch_bytes(int64_t R, int64_t C, int64_t T, int num_cus) {
     return sc.slots * (size_t)(4 * 4096 * tc.ni * tc.nj);
 }
 
+// Phase stamps of the 256 x 256 tile kernel (E4M3 x E4M3, contraction-contiguous operands): the same kernel with
+// kProfile, which makes wave 0 of every workgroup record cycle and 100 MHz stamps of its phases, 16 words of 64 bits
+// per workgroup id (see GemmTuning::kProfile).
+template <bool IEEE>
+struct GemmPhaseTuning : GemmTuning {
+    static constexpr bool kProfile = true;
+    static constexpr bool kIeeeMaximum = IEEE;
+    static __device__ void record(float* buf, int block, int slot, long long value) {
+        reinterpret_cast<long long*>(buf)[(size_t)block * 16 + slot] = value;
+    }
+};
+
+int gemm_phase_stamp_blocks(int64_t R, int64_t C) { return (int)((((R / 256) * (C / 256) + kXcds - 1) / kXcds) * kXcds); }
+
+int launch_gemm_phase_stamps(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T, const float* sA,
+                             const float* sB, void* c_bf16, float* d_amax_c, long long* stamps, int ieee_maximum,
+                             hipStream_t stream, int num_cus) {
+    const int tiles_r = (int)(R / 256), tiles_c = (int)(C / 256), nt = tiles_r * tiles_c;
+    const int grid = gemm_phase_stamp_blocks(R, C);
+    const int slots = resident_slots(num_cus, 4, 4);
+    const int band = band_rows();
+    const int share_b = band < tiles_r ? band : tiles_r, share_a = 4 < tiles_c ? 4 : tiles_c;
+    const int next_stride = touch_next(nt >= 6 * slots) ? slots : 0;
+    SplitPlan plan{};
+    plan.n_whole = nt;
+    plan.partials = reinterpret_cast<float*>(stamps);
+    unsigned* amax = reinterpret_cast<unsigned*>(d_amax_c);
+    hipLaunchKernelGGL(gemm_amax_reset_kernel, dim3(1), dim3(64), 0, stream, amax);
+    auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(kGemmThreads), 0, stream, A, B, reinterpret_cast<uint16_t*>(c_bf16),
+                           (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c, touch_ahead(), band, next_stride, (int)R, (int)C,
+                           share_a, share_b, plan);
+    };
+    if (ieee_maximum) launch(gemm_tile_kernel<0, 0, 4, 4, false, GemmPhaseTuning<true>>);
+    else launch(gemm_tile_kernel<0, 0, 4, 4, false, GemmPhaseTuning<false>>);
+    return hipGetLastError() == hipSuccess ? 0 : -6;
+}
+
 // BF16 baseline: same tile kernels with the BF16 MFMA; T counts elements here, rows are 2 T bytes long.
 int launch_gemm_bf16_tn(const void* A, const void* B, int64_t R, int64_t C, int64_t T, void* c_bf16,
                         int accumulate, hipStream_t stream, int num_cus) {

@@ -119,10 +119,16 @@ struct GemmTuning {
     // Scheduling fences between the 32-row blocks of the epilogue: without them the compiler hoists every
     // de-scale multiply to the front and parks the products in accumulator registers.
     static constexpr bool kEpilogueFence = true;
-    // Development aid: a tuning struct with kProfile = true also provides
-    //   static __device__ void record(int block, int slot, long long value)
-    // and gets cycle stamps of the phases of wave 0 of every workgroup.
+    // Phase stamps (llmq_calibrate_gemm_phases): a tuning struct with kProfile = true also provides
+    //   static __device__ void record(float* buf, int block, int slot, long long value)
+    // and wave 0 of every workgroup stamps the cycle counter and the 100 MHz clock at the start (slots 0, 8),
+    // after the first fragments are in registers (1, 9), after the K loop (2, 10), after the last output store
+    // is issued (4, 12), after the absmax (5, 13) and after all stores have completed (3, 11); buf is the
+    // `partials` pointer of the plan, which the plain kernel does not use otherwise.
     static constexpr bool kProfile = false;
+    // The fused output absmax with the IEEE 754-2019 maximum (v_maximum3_f32: two elements per instruction, NaN
+    // propagates) or, for comparison in the phase stamps only, with maxNum (v_max_f32 per element, NaN dropped).
+    static constexpr bool kIeeeMaximum = true;
     // LDS swizzle of the operand slabs: the 16-byte chunk index of a row is XOR-ed with
     // (row >> kSwizzleShift) & 7.
     static constexpr int kSwizzleShift = 1;
@@ -278,8 +284,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     auto stamp = [&](int slot) {
         if constexpr (V::kProfile) {
             if (threadIdx.x == 0) {
-                V::record(blockIdx.x, slot, (long long)__builtin_readcyclecounter());
-                V::record(blockIdx.x, slot + 8, (long long)__builtin_amdgcn_s_memrealtime());
+                V::record(plan.partials, blockIdx.x, slot, (long long)__builtin_readcyclecounter());
+                V::record(plan.partials, blockIdx.x, slot + 8, (long long)__builtin_amdgcn_s_memrealtime());
             }
         }
     };
@@ -558,8 +564,13 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     // absmax kernel run over the stored tensor.
     float maxabs = 0.0f;
     auto track4 = [&](const v4f& y) {
-        maxabs = __builtin_elementwise_maximum(__builtin_elementwise_maximum(maxabs, __builtin_fabsf(y[0])), __builtin_fabsf(y[1]));
-        maxabs = __builtin_elementwise_maximum(__builtin_elementwise_maximum(maxabs, __builtin_fabsf(y[2])), __builtin_fabsf(y[3]));
+        if constexpr (V::kIeeeMaximum) {
+            maxabs = __builtin_elementwise_maximum(__builtin_elementwise_maximum(maxabs, __builtin_fabsf(y[0])), __builtin_fabsf(y[1]));
+            maxabs = __builtin_elementwise_maximum(__builtin_elementwise_maximum(maxabs, __builtin_fabsf(y[2])), __builtin_fabsf(y[3]));
+        } else {
+            maxabs = __builtin_fmaxf(__builtin_fmaxf(maxabs, __builtin_fabsf(y[0])), __builtin_fabsf(y[1]));
+            maxabs = __builtin_fmaxf(__builtin_fmaxf(maxabs, __builtin_fabsf(y[2])), __builtin_fabsf(y[3]));
+        }
     };
     // The body exists twice, for one and for two de-scale multiplies; the choice is uniform over the grid.
     auto write_out = [&](auto two_mul) {

@@ -65,6 +65,12 @@ int launch_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64
                    int accumulate, float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus,
                    GemmScratch scratch);
 
+// The 256 x 256 tile kernel with phase stamps: 16 words of 64 bits per workgroup id, gemm_phase_stamp_blocks() ids.
+int gemm_phase_stamp_blocks(int64_t R, int64_t C);
+int launch_gemm_phase_stamps(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T, const float* sA,
+                             const float* sB, void* c_bf16, float* d_amax_c, long long* stamps, int ieee_maximum,
+                             hipStream_t stream, int num_cus);
+
 // The same contraction with either operand optionally T-major: ta: A is [T, R], tb: B is [T, C] (the
 // contraction index runs down the rows), so the backward GEMMs can read the untransposed quantized tensors.
 int launch_gemm_fp8(const uint8_t* A, int fmtA, bool ta, const uint8_t* B, int fmtB, bool tb, int64_t R, int64_t C,

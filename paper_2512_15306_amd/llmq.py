@@ -30,7 +30,7 @@ EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "l
            "llmq_fp8_linear_fwd", "llmq_fp8_linear_dgrad", "llmq_fp8_linear_wgrad",
            "llmq_scale_from_amax", "llmq_swiglu_workspace_bytes", "llmq_swiglu_fwd", "llmq_swiglu_fwd_fp8",
            "llmq_swiglu_bwd", "llmq_rmsnorm_workspace_bytes", "llmq_rmsnorm_fwd", "llmq_rmsnorm_apply_fp8",
-           "llmq_calibrate_mfma", "llmq_calibrate_copy"]
+           "llmq_calibrate_mfma", "llmq_calibrate_copy", "llmq_calibrate_gemm_phases_bytes", "llmq_calibrate_gemm_phases"]
 
 
 class LlmqError(RuntimeError):
@@ -102,6 +102,10 @@ def lib() -> ctypes.CDLL:
     L.llmq_rmsnorm_apply_fp8.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, vp, vp, vp]
     L.llmq_calibrate_mfma.restype = i32
     L.llmq_calibrate_mfma.argtypes = [i32, i32, i32, i32, vp, c.POINTER(c.c_double), vp]
+    L.llmq_calibrate_gemm_phases_bytes.restype = sz
+    L.llmq_calibrate_gemm_phases_bytes.argtypes = [i64, i64]
+    L.llmq_calibrate_gemm_phases.restype = i32
+    L.llmq_calibrate_gemm_phases.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp, vp, vp, sz, i32, vp]
     L.llmq_calibrate_copy.restype = i32
     L.llmq_calibrate_copy.argtypes = [vp, vp, sz, vp]
     _lib = L
@@ -351,3 +355,19 @@ def llmq_calibrate_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
         raise ValueError("sizes differ")
     _check(lib().llmq_calibrate_copy(_dev(src, None, "src"), _dev(dst, None, "dst"), src.numel() * src.element_size(),
                                      _stream()), "llmq_calibrate_copy")
+
+
+def llmq_calibrate_gemm_phases(A: torch.Tensor, B: torch.Tensor, d_scaleA: torch.Tensor, d_scaleB: torch.Tensor,
+                               c: torch.Tensor, d_amax_c: torch.Tensor, ieee_maximum: bool = True) -> torch.Tensor:
+    """Runs the stamped 256 x 256 tile kernel; returns the stamps as an int64 tensor [workgroup ids, 16]
+    (rows of ids beyond the number of tiles stay zero)."""
+    R, T = A.shape
+    C = B.shape[0]
+    nbytes = int(lib().llmq_calibrate_gemm_phases_bytes(R, C))
+    stamps = torch.zeros((max(nbytes, 8) // 128, 16), dtype=torch.int64, device=A.device)
+    _check(lib().llmq_calibrate_gemm_phases(_dev(A, torch.uint8, "A"), _dev(B, torch.uint8, "B"), R, C, T,
+                                            _dev(d_scaleA, torch.float32), _dev(d_scaleB, torch.float32),
+                                            _dev(c, torch.bfloat16, "c"), _dev(d_amax_c, torch.float32),
+                                            _dev(stamps, torch.int64, "stamps"), stamps.numel() * 8,
+                                            int(bool(ieee_maximum)), _stream()), "llmq_calibrate_gemm_phases")
+    return stamps

@@ -23,6 +23,8 @@ int launch_amax_partial(const void*, size_t, unsigned*, int* n_partial, hipStrea
 size_t gemm_scratch_bytes(int64_t R, int64_t C, int64_t, int) { return (size_t)((R / 256) * (C / 256) % 7) * 262144; }
 int launch_gemm_tn(const uint8_t*, int, const uint8_t*, int, int64_t, int64_t, int64_t, const float*, const float*, void*, int, float*, bool, hipStream_t, int, GemmScratch sc) { ++g_launches; g_scratch_seen = sc.ptr ? sc.bytes : 0; return 0; }
 int launch_gemm_fp8(const uint8_t*, int, bool, const uint8_t*, int, bool, int64_t, int64_t, int64_t, const float*, const float*, void*, int, float*, bool, hipStream_t, int, GemmScratch sc) { ++g_launches; g_scratch_seen = sc.ptr ? sc.bytes : 0; return 0; }
+int gemm_phase_stamp_blocks(int64_t R, int64_t C) { return (int)((R / 256) * (C / 256)); }
+int launch_gemm_phase_stamps(const uint8_t*, const uint8_t*, int64_t, int64_t, int64_t, const float*, const float*, void*, float*, long long*, int, hipStream_t, int) { ++g_launches; return 0; }
 int64_t swiglu_blocks(int64_t M, int64_t I) { return (M + 31) / 32 * ((I + 255) / 256); }
 int launch_swiglu_fwd(const void*, int64_t, int64_t, void*, unsigned*, int, float*, float*, const float*, int, uint8_t*, uint8_t*, hipStream_t) { ++g_launches; return 0; }
 int launch_swiglu_bwd(const void*, const void*, int64_t, int64_t, void*, unsigned*, int, float*, float*, hipStream_t) { ++g_launches; return 0; }
@@ -115,6 +117,9 @@ int main() {
     double flops = 0;
     EXPECT(llmq_calibrate_mfma(0, 1, 1, 100, F, &flops, nullptr), LLMQ_OK, 1);
     EXPECT(llmq_calibrate_mfma(0, 1, 1, 0, F, &flops, nullptr), LLMQ_ERR_SHAPE, 0);
+    EXPECT(llmq_calibrate_gemm_phases(B8, B8, 512, 256, 128, F, F, P, F, P, llmq_calibrate_gemm_phases_bytes(512, 256), 1, nullptr), LLMQ_OK, 1);
+    EXPECT(llmq_calibrate_gemm_phases(B8, B8, 512, 256, 128, F, F, P, F, P, 8, 1, nullptr), LLMQ_ERR_WORKSPACE, 0);
+    EXPECT(llmq_calibrate_gemm_phases(B8, B8, 500, 256, 128, F, F, P, F, P, 1 << 20, 1, nullptr), LLMQ_ERR_SHAPE, 0);
     EXPECT(llmq_calibrate_copy(P, P, 4096, nullptr), LLMQ_OK, 1);
     EXPECT(llmq_calibrate_copy(P, P, 4097, nullptr), LLMQ_ERR_SHAPE, 0);
     if (llmq_version() < 100 || ws <= ws_nt || !(flops > 0)) ++g_fail;
