@@ -7,17 +7,18 @@
 // Tuned kernel (template on the wave tile NI x NJ in units of 32: workgroup tile BM x BN with
 // BM = 64 NI, BN = 64 NJ, both in {128, 192, 256}; R % BM == 0, Cn % BN == 0, T % 128 == 0)
 //   - one workgroup of 4 wavefronts (2 x 2) per output tile, one workgroup per CU; a wavefront owns
-//     NI x NJ blocks of v_mfma_f32_32x32x64_f8f6f4 with fp32 accumulators (256 registers per lane
-//     at 4 x 4);
-//   - K advances 128 bytes per step; the A and B slabs (BM / BN rows x 128 B) go from global memory
-//     straight into LDS with buffer_load ... lds (16 bytes per lane, no VGPR staging), double buffered;
+//     2 NI x 2 NJ blocks of v_mfma_f32_16x16x128_f8f6f4 with fp32 accumulators (256 registers per lane at
+//     4 x 4: the whole accumulator file);
+//   - K advances 128 bytes per step, one MFMA deep; the A and B slabs (BM / BN rows x 128 B) go from global
+//     memory straight into LDS with buffer_load ... lds (16 bytes per lane, no VGPR staging), double buffered;
 //   - LDS rows are 128 B; the 16-byte chunk index is XOR-ed with (row >> 1) & 7, applied on the
 //     global side of the load, so that ds_read_b128 fragment reads of 16 consecutive rows spread
 //     over all 64 banks;
 //   - the order of the contraction index inside one MFMA does not matter as long as A and B use
-//     the same order, so every lane simply reads 32 contiguous bytes of its row;
-//   - every step is software pipelined in two halves: the MFMAs of one 64-byte half run while the
-//     fragments of the next half are read and the slab after next is requested; one barrier per step;
+//     the same order, so lane L simply reads the 32 contiguous bytes [32 (L / 16), +32) of row L % 16;
+//   - every step is software pipelined in four quarters (half the block rows x half the block columns): the MFMAs
+//     of one quarter run while the one fragment set that is free by then is read for the next quarter but one,
+//     and the slab after next is requested during the second half; one barrier per step;
 //   - the MFMA takes the B rows as its first operand, which leaves every lane with 4 consecutive
 //     output columns of one row; the epilogue de-scales in fp32, rounds to BF16 with the hardware
 //     conversion, takes the output absmax on the rounded bits, stages the wave's quadrant in LDS
@@ -77,15 +78,15 @@ __device__ inline void tile_of_position(int pos, int tiles_r, int tiles_c, int b
 // order by a second step, never with atomic additions).
 //   Positions [0, n_whole) of the walk are computed whole, one workgroup per tile, by a launch of the plain
 //   kernel (n_whole is a multiple of the number of workgroups the chip holds: whole rounds).  The remaining
-//   positions are served by a launch of the SPLIT instantiation, which comes first; they come in up to
+//   positions are served by a launch of the kSharePieces instantiation, which comes first; they come in up to
 //   kMaxSplitGroups groups; the tiles of a group are each cut into `pieces` pieces of `steps` K steps (the last
 //   piece takes what is left), one workgroup per piece, and a group never has more workgroups than the chip holds
 //   at once, so the groups run one after the other like rounds of ever shorter pieces: 192 left-over tiles on
 //   256 CUs are 128 tiles in halves, then 64 tiles in quarters, 3/4 of a round instead of a whole one.
-//   pieces == 1: the tile is written as usual.  Otherwise the piece's accumulators go, as binary32, to slot
-//   (wg_begin + tile_in_group * pieces + piece) of `partials`, and a second launch of the SPLIT instantiation with
-//   fixup = 1, one workgroup per shared tile, adds the pieces of a tile in the order of their K ranges and runs the
-//   usual epilogue on the sums.
+//   A piece's accumulators go, as binary32, to slot (wg_begin + tile_in_group * pieces + piece) of `partials`
+//   (also those of a tile left whole, pieces == 1, in a last group: the kernel of the pieces has no other way
+//   out), and a launch of the kShareFixup instantiation, one workgroup per shared tile, adds the pieces of a tile
+//   in the order of their K ranges and runs the usual epilogue on the sums.
 constexpr int kMaxSplitGroups = 4;
 struct SplitGroup {
     int tile_begin;      // first tile of the group, counted from n_whole
@@ -98,23 +99,23 @@ struct SplitGroup {
 struct SplitPlan {
     int n_whole;         // the plain kernel walks positions [0, n_whole); the shared tiles follow
     int n_groups;        // 0: nothing is shared
-    int fixup;
     SplitGroup group[kMaxSplitGroups];
     float* partials;
 };
-
-// MFMA scheduling masks of __builtin_amdgcn_sched_group_barrier
-constexpr int kSchedMfma = 0x008, kSchedVmemRead = 0x020, kSchedDsRead = 0x100;
 
 // Tuning knobs of the tuned kernel.
 struct GemmTuning {
     // Whether the kernel contains the L2 touch loads at all (their distance is a run-time argument).
     static constexpr bool kTouch = true;
-    // Fragment reads ride along with the first 1 / kDsSpread of a half step's MFMAs (4 x 4 tiles) or
-    // 1 / kDsSpreadSmall (smaller tiles: fewer MFMAs per read, and three reads per MFMA slot from four waves
-    // are more than the LDS delivers; measured +1-4 % on 4 x 3, while 4 x 4 loses 1-4 % on whole rounds with
-    // the reads spread over the whole half), the direct-to-LDS loads with the first 1 / kVmSpread.
-    static constexpr int kDsSpread = 2, kDsSpreadSmall = 1, kVmSpread = 1;
+    // Fragment reads ride along with the first 1 / kDsSpread of a quarter step's MFMAs (4 x 4 tiles) or
+    // 1 / kDsSpreadSmall (smaller tiles: fewer MFMAs per read); on the 4 x 4 tile spreading them over the whole
+    // quarter measured the same.
+    static constexpr int kDsSpread = 2, kDsSpreadSmall = 1;
+    // The direct-to-LDS loads of a step travel with the third quarter's MFMAs (1) or the third and fourth (2).
+    // An MFMA of this shape occupies the matrix pipe for 32 cycles only: with a fragment read, a load and its
+    // address arithmetic behind every MFMA of the third quarter the wave cannot issue the next MFMA in time
+    // (measured on 8192^3: 3.6 PFLOP/s on all-zero operands with 1, 4.04 with 2; 2.77 and 2.89 on random codes).
+    static constexpr int kLoadQuarters = 2;
     static constexpr bool kNtStoreC = false;     // streaming hint on the output stores
     // Scheduling fences between the 32-row blocks of the epilogue: without them the compiler hoists every
     // de-scale multiply to the front and parks the products in accumulator registers.
@@ -136,6 +137,8 @@ struct GemmTuning {
 
 template <bool B>
 struct BoolTag { static constexpr bool value = B; };
+template <int N>
+struct IntTag { static constexpr int value = N; };
 
 template <int N>
 __device__ inline void wait_vmcnt() {
@@ -156,39 +159,63 @@ __device__ inline void lds_barrier() {
 constexpr int kFmtBf16 = 2;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-template <int FA, int FB, int NI, int NJ>
-__device__ inline void mma_block(v16f (&acc)[NI][NJ], const v8i (&a)[NI], const v8i (&b)[NJ]) {
-    static_assert((FA == kFmtBf16) == (FB == kFmtBf16), "BF16 operands come in pairs");
-#pragma unroll
-    for (int i = 0; i < NI; ++i)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            if constexpr (FA == kFmtBf16) {
-                // two v_mfma_f32_32x32x16_bf16, one per 16-byte half of the fragments
-                const v4i a_lo = {a[i][0], a[i][1], a[i][2], a[i][3]}, a_hi = {a[i][4], a[i][5], a[i][6], a[i][7]};
-                const v4i b_lo = {b[j][0], b[j][1], b[j][2], b[j][3]}, b_hi = {b[j][4], b[j][5], b[j][6], b[j][7]};
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b_lo), __builtin_bit_cast(bf16x8, a_lo), acc[i][j], 0, 0, 0);
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b_hi), __builtin_bit_cast(bf16x8, a_hi), acc[i][j], 0, 0, 0);
-            } else {
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[i][j], FB, FA, 0, 0, 0, 0);
-            }
-        }
+// The accumulators of a wave tile of MI x MJ blocks of 16 x 16, four registers per block and lane.
+template <int MI, int MJ>
+struct BlockAcc {
+    v4f t[MI][MJ];
+    __device__ inline v4f get(int i, int j) const { return t[i][j]; }
+    __device__ inline void set(int i, int j, const v4f& v) { t[i][j] = v; }
+};
+
+// Calls f(IntTag<0>{}), ..., f(IntTag<N - 1>{}).
+template <int N, int I = 0, class F>
+__device__ inline void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(IntTag<I>{});
+        static_for<N, I + 1>(f);
+    }
 }
 
-// Interleave NM MFMAs with ND LDS reads, spread over the first NM / DS_SPREAD MFMAs (so that they have
-// landed when the MFMAs end), and NV global loads, spread over the first NM / VM_SPREAD.
-template <int NM, int ND, int NV, int DS_SPREAD, int VM_SPREAD, int SYNC, int M = 0>
-__device__ inline void interleave() {
-    if constexpr (M < NM) {
-        constexpr int kDsSpan = (NM + DS_SPREAD - 1) / DS_SPREAD, kVmSpan = (NM + VM_SPREAD - 1) / VM_SPREAD;
-        constexpr int kDsPer = (ND + kDsSpan - 1) / kDsSpan;
-        constexpr int kVmPer = (NV + kVmSpan - 1) / kVmSpan;
-        constexpr int kDsLeft = ND - M * kDsPer, kVmLeft = NV - M * kVmPer;
-        __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, SYNC);
-        if constexpr (kDsLeft > 0) __builtin_amdgcn_sched_group_barrier(kSchedDsRead, kDsLeft < kDsPer ? kDsLeft : kDsPer, SYNC);
-        if constexpr (kVmLeft > 0) __builtin_amdgcn_sched_group_barrier(kSchedVmemRead, kVmLeft < kVmPer ? kVmLeft : kVmPer, SYNC);
-        interleave<NM, ND, NV, DS_SPREAD, VM_SPREAD, SYNC, M + 1>();
+// One 16 x 16 block update: acc(16 x 16) += a(16 x 128 bytes) b(16 x 128 bytes)^T.
+// v_mfma_f32_16x16x128_f8f6f4 rather than 32x32x64: on random FP8 bits, where the board's power cap and not the
+// issue rate sets the speed, a register-only loop of the 16x16x128 form sustains 4.22 PFLOP/s against 3.83-3.85
+// for 32x32x64 (both 4.98 on constant bits): it adds 128 products per accumulator update instead of 64.
+template <int FA, int FB>
+__device__ inline void mma_block(v4f& c, const v8i& a, const v8i& b) {
+    static_assert((FA == kFmtBf16) == (FB == kFmtBf16), "BF16 operands come in pairs");
+    if constexpr (FA == kFmtBf16) {
+        // two v_mfma_f32_16x16x32_bf16, one per 16-byte half of the fragments
+        const v4i a_lo = {a[0], a[1], a[2], a[3]}, a_hi = {a[4], a[5], a[6], a[7]};
+        const v4i b_lo = {b[0], b[1], b[2], b[3]}, b_hi = {b[4], b[5], b[6], b[7]};
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b_lo), __builtin_bit_cast(bf16x8, a_lo), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b_hi), __builtin_bit_cast(bf16x8, a_hi), c, 0, 0, 0);
+    } else {
+        // The instruction is written out so that its accumulator can be constrained to the accumulator register
+        // file and tied to the result.  Given the builtin, whose accumulators may sit in either file, the register
+        // allocator moves the 4-register blocks between the files inside the K loop (hundreds of copies and a
+        // handful of spills per K step, which made the kernel issue-bound at half its speed).  The compiler does
+        // not know what the statement is, so it adds none of the MFMA wait states; the kernel needs none: fragments
+        // come from LDS reads (waited for by counter), a block is updated again 16 or more MFMAs later, and
+        // the epilogue starts behind a counter wait and a barrier.  cbsz / blgp: formats of the first / second operand.
+        asm("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 cbsz:%3 blgp:%4" : "+a"(c) : "v"(b), "v"(a), "n"(FB), "n"(FA));
     }
+}
+
+// One quarter of a wave tile's MFMAs of a K step: the 16 x 16 blocks (I0 + i, J0 + j) of the accumulators from HI
+// fragments of A and HJ fragments of B (32 bytes per lane each: the 128-byte K step of 16 operand rows), i running
+// slowest (or j with J_OUTER: the set that was read last is then needed one fragment at a time).  After block update
+// number m the caller's side(IntTag<m>) issues whatever memory instructions are to travel with it; scheduling fences
+// keep that order (the written-out MFMA is invisible to the scheduler's instruction classes, so the order is fixed
+// here rather than asked for with group barriers).
+template <int FA, int FB, int I0, int J0, bool J_OUTER, int MI, int MJ, int HI, int HJ, class Side>
+__device__ inline void mma_quadrant(BlockAcc<MI, MJ>& acc, const v8i (&a)[HI], const v8i (&b)[HJ], Side&& side) {
+    static_for<HI * HJ>([&](auto tag) {
+        constexpr int m = decltype(tag)::value;
+        constexpr int i = J_OUTER ? m % HI : m / HJ, j = J_OUTER ? m / HI : m % HJ;
+        mma_block<FA, FB>(acc.t[I0 + i][J0 + j], a[i], b[j]);
+        side(tag);
+        __builtin_amdgcn_sched_barrier(0);
+    });
 }
 
 // How one operand slab sits in memory and in LDS, and how its MFMA fragments are read.
@@ -215,12 +242,17 @@ struct SlabShape {
     // XOR mask of the 16-byte unit index of LDS row k.  One transposing read of 32 lanes touches 8 consecutive
     // rows x 2 neighbouring units (x 2 halves); the mask moves in steps of two units so that these 16 units fall
     // into 16 different groups of four banks: rows are 64 / 48 / 32 banks long for NX = 4 / 3 / 2.
-    __device__ static int swizzle_of_row(int k) { return (NX == 4 ? k & 7 : NX == 2 ? (k >> 1) & 3 : (k >> 2) & 1) << 1; }
+    // The two halves of 16 lanes of such a read sit 32 LDS rows apart (K quarters of the 16x16x128 fragment), i.e. a
+    // multiple of 64 banks: bit 5 of the row goes into the lowest bit of the mask to separate them.
+    __device__ static int swizzle_of_row(int k) { return ((NX == 4 ? k & 7 : NX == 2 ? (k >> 1) & 3 : (k >> 2) & 1) << 1) | ((k >> 5) & 1); }
 };
 
-// SPLIT: the instantiation that can share tiles among workgroups (SplitPlan); without it the plan is ignored and
-// every workgroup computes one whole tile, with nothing of the sharing logic in the code.
-template <int FA, int FB, int NI, int NJ, bool ACCUM, class V = GemmTuning, bool TA = false, bool TB = false, bool SPLIT = false>
+// MODE: kWholeTiles ignores the plan and computes one whole tile per workgroup, with nothing of the sharing logic
+// in the code; kSharePieces computes the pieces of shared tiles; kShareFixup adds them up and has no K loop.  Three
+// kernels rather than branches of one: the accumulators fill the accumulator file, and code that reaches them from
+// two sides (loaded sums or MFMA results) made the register allocator spill them around the K loop.
+constexpr int kWholeTiles = 0, kSharePieces = 1, kShareFixup = 2;
+template <int FA, int FB, int NI, int NJ, bool ACCUM, class V = GemmTuning, bool TA = false, bool TB = false, int MODE = kWholeTiles>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ C,
     int Cn, int T, const float* __restrict__ d_sA, const float* __restrict__ d_sB,
@@ -247,17 +279,16 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     // [kb, kb + nk), written as a whole tile (slot < 0) or as one piece of a shared tile.  In the fix-up launch
     // slot is the first slot of the tile's pieces and nk their number.
     int pos, kb = 0, nk = T / BK, slot = -1;
-    const bool fixup = SPLIT && plan.fixup != 0;
+    constexpr bool SPLIT = MODE != kWholeTiles, fixup = MODE == kShareFixup;
     if constexpr (!SPLIT) {
         pos = walk_position(blockIdx.x, plan.n_whole);
         if (pos < 0) return;
     } else {
         const int q = (int)blockIdx.x;                     // shared tile (fix-up launch) or sharing workgroup
         int gi = 0;
-        while (gi + 1 < plan.n_groups && q >= (plan.fixup ? plan.group[gi + 1].tile_begin : plan.group[gi + 1].wg_begin)) ++gi;
+        while (gi + 1 < plan.n_groups && q >= (fixup ? plan.group[gi + 1].tile_begin : plan.group[gi + 1].wg_begin)) ++gi;
         const SplitGroup grp = plan.group[gi];
-        if (plan.fixup) {
-            if (grp.pieces == 1) return;                   // written whole by the first launch
+        if constexpr (fixup) {
             const int j = q - grp.tile_begin;
             pos = plan.n_whole + q;
             slot = grp.wg_begin + j * grp.pieces;
@@ -267,12 +298,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
             if (w < 0) return;
             const int piece = w / grp.tiles, j = w - piece * grp.tiles;
             pos = plan.n_whole + grp.tile_begin + j;
-            if (grp.pieces > 1) {
-                kb = piece * grp.steps;
-                nk = nk - kb < grp.steps ? nk - kb : grp.steps;
-                if (nk <= 0) return;                       // cannot happen with steps = ceil(K steps / pieces)
-                slot = grp.wg_begin + j * grp.pieces + piece;
-            }
+            kb = piece * grp.steps;
+            nk = nk - kb < grp.steps ? nk - kb : grp.steps;
+            if (nk <= 0) return;                           // cannot happen with steps = ceil(K steps / pieces)
+            slot = grp.wg_begin + j * grp.pieces + piece;
         }
     }
     int tr, tc;
@@ -310,7 +339,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     auto tmajor_voff = [&](auto shape, int m, int ld) {             // pattern m of a T-major operand
         typedef decltype(shape) S;
         const int unit = 64 * m + lane, row = unit / S::kUnits, col = unit % S::kUnits;
-        return row * ld + ((col ^ S::swizzle_of_row(row)) << 4);
+        return row * ld + ((col ^ S::swizzle_of_row(row + 32 * wave)) << 4);      // the wave moves slab rows [32 wave, 32 wave + 32)
     };
     int ld_voffA[3], ld_voffB[3];
 #pragma unroll
@@ -319,86 +348,97 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
         ld_voffB[m] = TB ? (m < SB::kPeriod ? tmajor_voff(SB{}, m, ldB) : 0) : (m & 1) ? ld_voff1 : ld_voff0;
     }
     const int ld_soffA = TA ? wave * 32 * ldA : wave * 16 * NI * T, ld_soffB = TB ? wave * 32 * ldB : wave * 16 * NJ * T;
-    // k0: first contraction index of the slab, or a negative value for "no slab" (nothing is fetched)
-    auto issue_loads = [&](uint8_t* slabA, uint8_t* slabB, int k0) {
-        uint8_t* sa = slabA + wave * 16 * NI * BK;
-        uint8_t* sb = slabB + wave * 16 * NJ * BK;
-        const int baseA = k0 < 0 ? kOutOfRange : ld_soffA + (TA ? k0 * ldA : k0);
-        const int baseB = k0 < 0 ? kOutOfRange : ld_soffB + (TB ? k0 * ldB : k0);
-#pragma unroll
-        for (int j = 0; j < 2 * (NI > NJ ? NI : NJ); ++j) {
-            if (j < 2 * NI) {
-                const int voff = TA ? ld_voffA[j % SA::kPeriod] : ld_voffA[j & 1];
-                const int soff = TA ? (j / SA::kPeriod) * SA::kPeriodRows * ldA : j * 8 * T;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_void*)(sa + j * 8 * BK), 16, voff, baseA + soff, 0, 0);
-            }
-            if (j < 2 * NJ) {
-                const int voff = TB ? ld_voffB[j % SB::kPeriod] : ld_voffB[j & 1];
-                const int soff = TB ? (j / SB::kPeriod) * SB::kPeriodRows * ldB : j * 8 * T;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_void*)(sb + j * 8 * BK), 16, voff, baseB + soff, 0, 0);
-            }
+    // The direct-to-LDS loads of one slab pair: pieces 0 .. 2 NI - 1 fill the wave's share of the A slab, the
+    // next 2 NJ that of the B slab.  k0: first contraction index of the slab, or a negative value for "no slab"
+    // (nothing is fetched).
+    auto load_base = [&](int k0, int& baseA, int& baseB) {
+        baseA = k0 < 0 ? kOutOfRange : ld_soffA + (TA ? k0 * ldA : k0);
+        baseB = k0 < 0 ? kOutOfRange : ld_soffB + (TB ? k0 * ldB : k0);
+    };
+    auto issue_load = [&](uint8_t* slabA, uint8_t* slabB, int baseA, int baseB, auto piece) {
+        constexpr int p = decltype(piece)::value;
+        if constexpr (p < 2 * NI) {
+            constexpr int j = p;
+            const int voff = TA ? ld_voffA[j % SA::kPeriod] : ld_voffA[j & 1];
+            const int soff = TA ? (j / SA::kPeriod) * SA::kPeriodRows * ldA : j * 8 * T;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_void*)(slabA + wave * 16 * NI * BK + j * 8 * BK), 16, voff, baseA + soff, 0, 0);
+        } else {
+            constexpr int j = p - 2 * NI;
+            const int voff = TB ? ld_voffB[j % SB::kPeriod] : ld_voffB[j & 1];
+            const int soff = TB ? (j / SB::kPeriod) * SB::kPeriodRows * ldB : j * 8 * T;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_void*)(slabB + wave * 16 * NJ * BK + j * 8 * BK), 16, voff, baseB + soff, 0, 0);
         }
     };
     constexpr int kLoadsPerStep = 2 * (NI + NJ);
-    constexpr int kReadsPerHalf = SA::kReadsPerFrag * NI + SB::kReadsPerFrag * NJ;      // LDS reads of one fragment set
-    constexpr int kMfmaPerHalf = NI * NJ * (FA == kFmtBf16 ? 2 : 1);
-    // T-major operands take twice as many (half as wide) LDS reads: spread over the whole half step they cost
+    auto issue_loads = [&](uint8_t* slabA, uint8_t* slabB, int k0) {
+        int baseA, baseB;
+        load_base(k0, baseA, baseB);
+        static_for<kLoadsPerStep>([&](auto piece) { issue_load(slabA, slabB, baseA, baseB, piece); });
+    };
+    // The wave tile as 16 x 16 blocks: MI x MJ of them, handled in halves of HI block rows / HJ block columns.
+    constexpr int MI = 2 * NI, MJ = 2 * NJ, HI = NI, HJ = NJ;
+    constexpr int kReadsA = SA::kReadsPerFrag * HI, kReadsB = SB::kReadsPerFrag * HJ;   // LDS reads of one fragment set
+    constexpr int kSlots = HI * HJ;                // block updates of one quarter: the slots its side work is spread over
+    // T-major operands take twice as many (half as wide) LDS reads: spread over the whole phase they cost
     // nothing, bunched into its first half the both-T-major 4 x 4 kernel measured 4-8 % slower
     constexpr int kDsSpread = (TA || TB) ? 1 : NI * NJ >= 16 ? V::kDsSpread : V::kDsSpreadSmall;
 
-    // ---- LDS -> registers: lane reads 32 contiguous bytes (two swizzled 16-byte chunks) of its row
-    const int fr_row = lane & 31;
-    const int fr_half = lane >> 5;                                  // which 32 bytes of the 64-byte K half
+    // ---- LDS -> registers.  The fragment of a 16-row block for v_mfma_f32_16x16x128: lane L holds the 32
+    // contiguous bytes [32 (L / 16), 32 (L / 16) + 32) of the K step of operand row L % 16 (two swizzled 16-byte
+    // chunks of its LDS row).
+    const int fr_row = lane & 15;
+    const int fr_q = lane >> 4;                                     // which 32 bytes of the 128-byte K step
     const int swz = (fr_row >> kSw) & 7;                            // same for every row this lane reads
     const int offA = (wr * 32 * NI + fr_row) * BK, offB = (wc * 32 * NJ + fr_row) * BK;
-    const int ch00 = ((fr_half * 2) ^ swz) << 4, ch01 = ((fr_half * 2 + 1) ^ swz) << 4;
-    const int ch10 = ((4 + fr_half * 2) ^ swz) << 4, ch11 = ((4 + fr_half * 2 + 1) ^ swz) << 4;
-    auto read_frags_rows = [&](const uint8_t* slab, int off, int ks, auto& f) {
-        const int c0 = ks ? ch10 : ch00, c1 = ks ? ch11 : ch01;
-#pragma unroll
-        for (int i = 0; i < (int)(sizeof(f) / sizeof(f[0])); ++i) {
-            const uint8_t* p = slab + off + i * 32 * BK;
-            v4i lo = *reinterpret_cast<const v4i*>(p + c0);
-            v4i hi = *reinterpret_cast<const v4i*>(p + c1);
-            f[i] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        }
+    const int ch0 = ((fr_q * 2) ^ swz) << 4, ch1 = ((fr_q * 2 + 1) ^ swz) << 4;
+    // read number p of a fragment set: 16-byte half p % 2 of fragment p / 2
+    auto read_piece_rows = [&](const uint8_t* slab, int off, int first_block, auto& f, auto piece) {
+        constexpr int p = decltype(piece)::value, i = p >> 1, h = (p & 1) * 4;
+        const v4i v = *reinterpret_cast<const v4i*>(slab + off + (first_block + i) * 16 * BK + ((p & 1) ? ch1 : ch0));
+        f[i][h] = v[0], f[i][h + 1] = v[1], f[i][h + 2] = v[2], f[i][h + 3] = v[3];
     };
-    // T-major: byte offset of this lane's first transposing read of 32-row block i (half 0): LDS row
-    // 32 fr_half + (lane & 15) / 2, unit 2 (2 NX w + i) + ((lane >> 4) & 1) swizzled, half (lane & 1) of the unit.
-    const int tm_row = fr_half * 32 + ((lane & 15) >> 1);
-    int tm_offA[NI], tm_offB[NJ];
+    // T-major: byte offset of this lane's first transposing read of the wave's 16-row block 0: LDS row
+    // 32 fr_q + (lane & 15) / 2, 16-byte unit (first unit of the wave) swizzled, half (lane & 1) of the unit; block i
+    // is unit + i, read q of a fragment is 8 LDS rows further down.
+    const int tm_row = fr_q * 32 + ((lane & 15) >> 1);
+    int tm_offA[MI], tm_offB[MJ];
 #pragma unroll
-    for (int i = 0; i < NI; ++i)
-        tm_offA[i] = tm_row * BM + (((2 * (NI * wr + i) + ((lane >> 4) & 1)) ^ SA::swizzle_of_row(tm_row)) << 4) + ((lane & 1) << 3);
+    for (int i = 0; i < MI; ++i)
+        tm_offA[i] = tm_row * BM + (((MI * wr + i) ^ SA::swizzle_of_row(tm_row)) << 4) + ((lane & 1) << 3);
 #pragma unroll
-    for (int i = 0; i < NJ; ++i)
-        tm_offB[i] = tm_row * BN + (((2 * (NJ * wc + i) + ((lane >> 4) & 1)) ^ SB::swizzle_of_row(tm_row)) << 4) + ((lane & 1) << 3);
-    auto read_frags_tmajor = [&](const uint8_t* slab, const auto& offs, int pitch, int ks, auto& f) {
-#pragma unroll
-        for (int i = 0; i < (int)(sizeof(f) / sizeof(f[0])); ++i) {
-            v2i r[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                r[q] = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i*)(slab + offs[i] + (64 * ks + 8 * q) * pitch));
-            f[i] = v8i{r[0][0], r[0][1], r[1][0], r[1][1], r[2][0], r[2][1], r[3][0], r[3][1]};
-        }
+    for (int i = 0; i < MJ; ++i)
+        tm_offB[i] = tm_row * BN + (((MJ * wc + i) ^ SB::swizzle_of_row(tm_row)) << 4) + ((lane & 1) << 3);
+    // read number p of a fragment set: 8-byte quarter p % 4 of fragment p / 4
+    auto read_piece_tmajor = [&](const uint8_t* slab, const int* offs, int pitch, auto& f, auto piece) {
+        constexpr int p = decltype(piece)::value, i = p >> 2, q = p & 3;
+        const v2i r = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i*)(slab + offs[i] + 8 * q * pitch));
+        f[i][2 * q] = r[0], f[i][2 * q + 1] = r[1];
     };
-    auto read_fragsA = [&](uint8_t* slab, int ks, auto& f) {
-        if constexpr (TA) read_frags_tmajor(slab, tm_offA, BM, ks, f); else read_frags_rows(slab, offA, ks, f);
+    // first_block: 0 or HI / HJ, the half of the wave tile's block rows / columns the set f is for
+    auto read_pieceA = [&](uint8_t* slab, auto first_block, auto& f, auto piece) {
+        constexpr int kFirst = decltype(first_block)::value;
+        if constexpr (TA) read_piece_tmajor(slab, tm_offA + kFirst, BM, f, piece); else read_piece_rows(slab, offA, kFirst, f, piece);
     };
-    auto read_fragsB = [&](uint8_t* slab, int ks, auto& f) {
-        if constexpr (TB) read_frags_tmajor(slab, tm_offB, BN, ks, f); else read_frags_rows(slab, offB, ks, f);
+    auto read_pieceB = [&](uint8_t* slab, auto first_block, auto& f, auto piece) {
+        constexpr int kFirst = decltype(first_block)::value;
+        if constexpr (TB) read_piece_tmajor(slab, tm_offB + kFirst, BN, f, piece); else read_piece_rows(slab, offB, kFirst, f, piece);
     };
 
-    v16f acc[NI][NJ];
+    // The accumulators start from a zero the compiler cannot see through: a known constant it would re-create
+    // wherever it likes (also by copying one zeroed accumulator register to the next), and the build checks that
+    // nothing but MFMAs reads accumulator registers while MFMAs are under way.
+    BlockAcc<MI, MJ> acc;
+    float zero;
+    asm("v_mov_b32 %0, 0" : "=v"(zero));
 #pragma unroll
-    for (int i = 0; i < NI; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
+        for (int j = 0; j < MJ; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+            for (int e = 0; e < 4; ++e) acc.t[i][j][e] = zero;
 
-    v8i a0[NI], b0[NJ], a1[NI], b1[NJ];    // fragment sets of the two 64-byte halves of a K step
+    // Fragment sets: the low and high halves of the wave tile's block rows (A) and block columns (B).
+    v8i aL[HI], aH[HI], bL[HJ], bH[HJ];
 
     // L2 touch loads: a wave reads the first dword of some rows of a slab that is still touch_ahead
     // steps ahead of the direct-to-LDS loads (touch_ahead <= 0: nothing is fetched).  The CUs of an XCD
@@ -421,29 +461,66 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     int touchA[2] = {0, 0}, touchB[2] = {0, 0};   // results are only kept so that the loads stay tracked
     int touch_sink = 0;
 
-    // One K step on the stage (curA, curB) while the other stage (nxtA, nxtB) is being filled:
-    //   first half : read the second-half fragments            | MFMAs on the first-half fragments
-    //   barrier    : the next slab has landed, everybody is done reading the current one
-    //   second half: start loading slab kt+2 into the current stage, read the first-half
-    //                fragments of slab kt+1                     | MFMAs on the second-half fragments
+    // The side work of slot m of a quarter: its share of the LDS reads of a fragment set, spread evenly over the
+    // first kSlots / kDsSpread slots so that they have landed when the quarter ends, and its share of the step's
+    // direct-to-LDS loads, spread over the third quarter or (kLoadQuarters = 2) the third and fourth.  Of n pieces
+    // spread over `span` slots, slot m takes the pieces [ceil(m n / span), ceil((m + 1) n / span)).
+    constexpr int kDsSpan = (kSlots + kDsSpread - 1) / kDsSpread;
+    constexpr int kVmSpan = kSlots * V::kLoadQuarters;
+    auto pieces_of_slot = [&](auto n_pieces, auto span, auto m, auto&& issue) {
+        constexpr int n = decltype(n_pieces)::value, sp = decltype(span)::value, mm = decltype(m)::value;
+        constexpr int first = (mm * n + sp - 1) / sp, last = ((mm + 1) * n + sp - 1) / sp;
+        static_for<(last < n ? last : n) - (first < n ? first : n)>([&](auto u) { issue(IntTag<first + decltype(u)::value>{}); });
+    };
+    auto readsA_of_slot = [&](uint8_t* slab, auto first_block, auto& f, auto m) {
+        pieces_of_slot(IntTag<kReadsA>{}, IntTag<kDsSpan>{}, m, [&](auto piece) { read_pieceA(slab, first_block, f, piece); });
+    };
+    auto readsB_of_slot = [&](uint8_t* slab, auto first_block, auto& f, auto m) {
+        pieces_of_slot(IntTag<kReadsB>{}, IntTag<kDsSpan>{}, m, [&](auto piece) { read_pieceB(slab, first_block, f, piece); });
+    };
+    auto loads_of_slot = [&](uint8_t* slabA, uint8_t* slabB, int baseA, int baseB, auto m) {
+        pieces_of_slot(IntTag<kLoadsPerStep>{}, IntTag<kVmSpan>{}, m, [&](auto piece) { issue_load(slabA, slabB, baseA, baseB, piece); });
+    };
+    auto read_fragsA = [&](uint8_t* slab, auto first_block, auto& f) {
+        static_for<kReadsA>([&](auto piece) { read_pieceA(slab, first_block, f, piece); });
+    };
+    auto read_fragsB = [&](uint8_t* slab, auto first_block, auto& f) {
+        static_for<kReadsB>([&](auto piece) { read_pieceB(slab, first_block, f, piece); });
+    };
+
+    // One K step on the stage (curA, curB) while the other stage (nxtA, nxtB) is being filled.  The wave tile's
+    // MFMAs of the step run as four quarters (half of the block rows x half of the block columns), and each
+    // quarter covers the LDS reads of the one fragment set that is free by then.  On entry the sets aX (one half
+    // of the block rows: the low one on even steps, the high one on odd steps) and bL hold the current slab:
+    //   quarter 0: MFMAs (aX, bL) | read aY of the current slab
+    //   quarter 1: MFMAs (aY, bL) | read bH of the current slab
+    //   barrier  : the next slab has landed, everybody is done reading the current one
+    //   quarter 2: MFMAs (aY, bH) | start loading slab kt+2 into the current stage, read bL of the next slab
+    //   quarter 3: MFMAs (aX, bH) | read aY of the next slab, which is the next step's aX
     // Loads that would start beyond the last slab are pointed outside the buffer range instead:
     // the hardware then fetches nothing (LDS receives zeros), and that stage is never used.
-    auto k_step = [&](uint8_t* curA, uint8_t* curB, uint8_t* nxtA, uint8_t* nxtB, int kt, int parity) {
-        read_fragsA(curA, 1, a1);
-        read_fragsB(curB, 1, b1);
-        mma_block<FA, FB, NI, NJ>(acc, a0, b0);
-        interleave<kMfmaPerHalf, kReadsPerHalf, 0, kDsSpread, V::kVmSpread, 0>();
+    auto k_step = [&](uint8_t* curA, uint8_t* curB, uint8_t* nxtA, uint8_t* nxtB, int kt, int parity, auto x_is_high) {
+        constexpr bool XH = decltype(x_is_high)::value;
+        constexpr int X0 = XH ? HI : 0, Y0 = XH ? 0 : HI;
+        auto& aX = *(XH ? &aH : &aL);
+        auto& aY = *(XH ? &aL : &aH);
+        mma_quadrant<FA, FB, X0, 0, false>(acc, aX, bL, [&](auto m) { readsA_of_slot(curA, IntTag<Y0>{}, aY, m); });
+        mma_quadrant<FA, FB, Y0, 0, false>(acc, aY, bL, [&](auto m) { readsB_of_slot(curB, IntTag<HJ>{}, bH, m); });
         // the direct-to-LDS loads of the previous step must have landed; its two touch loads, issued
         // after them, may still be in flight
         if constexpr (kTouch) wait_vmcnt<2>(); else wait_vmcnt<0>();
         lds_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        issue_loads(curA, curB, kt + 2 < nk ? (kb + kt + 2) * BK : -1);
-        read_fragsA(nxtA, 0, a0);               // past the last slab this reads bytes that are never used
-        read_fragsB(nxtB, 0, b0);
-        mma_block<FA, FB, NI, NJ>(acc, a1, b1);
-        interleave<kMfmaPerHalf, kReadsPerHalf, kLoadsPerStep, kDsSpread, V::kVmSpread, 1>();
-        __builtin_amdgcn_sched_barrier(0);
+        int baseA, baseB;
+        load_base(kt + 2 < nk ? (kb + kt + 2) * BK : -1, baseA, baseB);
+        mma_quadrant<FA, FB, Y0, HJ, true>(acc, aY, bH, [&](auto m) {
+            readsB_of_slot(nxtB, IntTag<0>{}, bL, m);     // past the last slab this reads bytes that are never used
+            loads_of_slot(curA, curB, baseA, baseB, m);
+        });
+        mma_quadrant<FA, FB, X0, HJ, false>(acc, aX, bH, [&](auto m) {
+            readsA_of_slot(nxtA, IntTag<Y0>{}, aY, m);
+            loads_of_slot(curA, curB, baseA, baseB, IntTag<kSlots + decltype(m)::value>{});
+        });
         if constexpr (kTouch) {
             const int kp = kt + 2 + touch_ahead;
             const bool on = touch_ahead > 0 && kp < nk;
@@ -454,7 +531,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
         }
     };
 
-    if (!fixup) {
+    if constexpr (!fixup) {
     // both stages are requested at once; only the first has to have landed before the first fragments
     issue_loads(ldsA0, ldsB0, kb * BK);
     issue_loads(ldsA1, ldsB1, nk > 1 ? (kb + 1) * BK : -1);
@@ -465,15 +542,18 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     }
     wait_vmcnt<kLoadsPerStep + (kTouch ? 2 : 0)>();
     lds_barrier();
-    read_fragsA(ldsA0, 0, a0);
-    read_fragsB(ldsB0, 0, b0);
+    read_fragsA(ldsA0, IntTag<0>{}, aL);
+    read_fragsB(ldsB0, IntTag<0>{}, bL);
     stamp(1);
     int kt = 0;
     for (; kt + 1 < nk; kt += 2) {
-        k_step(ldsA0, ldsB0, ldsA1, ldsB1, kt, 0);
-        k_step(ldsA1, ldsB1, ldsA0, ldsB0, kt + 1, 1);
+        k_step(ldsA0, ldsB0, ldsA1, ldsB1, kt, 0, BoolTag<false>{});
+        k_step(ldsA1, ldsB1, ldsA0, ldsB0, kt + 1, 1, BoolTag<true>{});
     }
-    if (kt < nk) k_step(ldsA0, ldsB0, ldsA1, ldsB1, kt, 0);
+    if (kt < nk) k_step(ldsA0, ldsB0, ldsA1, ldsB1, kt, 0, BoolTag<false>{});
+    // The last block updates must have left the matrix pipeline before ordinary instructions read the accumulators
+    // (the compiler cannot count these wait states for a written-out MFMA).
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     // Every wave waits for its own direct-to-LDS loads (the out-of-range ones of the last two steps
     // still write zeros into the slabs), then all meet: after this barrier nothing lands in LDS any
     // more and nobody reads the slabs, so the epilogue may reuse them.
@@ -486,27 +566,43 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     stamp(2);
     } else {
         // Fix-up launch: the accumulators are the sums of the pieces the sharing workgroups left, added in the
-        // order of their K ranges; one row of 32 x 32 blocks at a time (4 NJ loads of 16 bytes in flight per lane:
+        // order of their K ranges; two rows of 16 x 16 blocks at a time (4 NJ loads of 16 bytes in flight per lane:
         // the launch has one workgroup per shared tile and is bound by the latency of these loads).
         constexpr int kTileFloats = BM * BN;
         for (int c = 0; c < nk; ++c) {
-            const v4f* src = reinterpret_cast<const v4f*>(plan.partials + (size_t)(slot + c) * kTileFloats) + threadIdx.x;
+            const v4f* src = reinterpret_cast<const v4f*>(plan.partials + (size_t)(slot + c) * kTileFloats);
 #pragma unroll
-            for (int i = 0; i < NI; ++i) {
-                v4f v[NJ][4];
+            for (int i = 0; i < MI; i += 2) {
+                v4f v[2][MJ];
 #pragma unroll
-                for (int j = 0; j < NJ; ++j)
+                for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) v[j][g] = __builtin_nontemporal_load(src + ((i * NJ + j) * 4 + g) * kGemmThreads);
+                    for (int j = 0; j < MJ; ++j) v[ii][j] = __builtin_nontemporal_load(src + ((i + ii) * MJ + j) * kGemmThreads + threadIdx.x);
 #pragma unroll
-                for (int j = 0; j < NJ; ++j)
+                for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g)
+                    for (int j = 0; j < MJ; ++j) {
+                        v4f c = acc.get(i + ii, j);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] += v[j][g][e];
+                        for (int e = 0; e < 4; ++e) c[e] += v[ii][j][e];
+                        acc.set(i + ii, j, c);
+                    }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+    }
+    if constexpr (MODE == kSharePieces) {
+        // a piece of a shared tile: the accumulators as they are, 16 bytes per lane and store, 4 KB per store
+        // of the workgroup; the fix-up launch reads them back in the same arrangement
+        // (uniform base + lane index per store: one address register pair instead of one per store)
+        v4f* dst = reinterpret_cast<v4f*>(plan.partials + (size_t)slot * (BM * BN));
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+#pragma unroll
+            for (int j = 0; j < MJ; ++j) (dst + (i * MJ + j) * kGemmThreads)[threadIdx.x] = acc.get(i, j);
+            if ((i & 1) == 1) __builtin_amdgcn_sched_barrier(0);
+        }
+        return;
     }
     // The workgroup that follows on this XCD (id + next_stride: same XCD, and dispatched about when this
     // one retires) starts with two slabs of its own operands; one dword per 128-byte line of them is
@@ -544,9 +640,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
         }
     }
 
-    // ---- epilogue.  Per 32x32 block a lane holds 4 groups of 4 consecutive columns of row (lane % 32).
-    // Storing those 8-byte pieces directly scatters every store over 32 rows; instead each wave
-    // stages one 32-row block of its quadrant at a time (32 rows x 32 NJ BF16 columns) at the start of one
+    // ---- epilogue.  Per 16 x 16 block a lane holds 4 consecutive columns of row (lane % 16).
+    // Storing those 8-byte pieces directly scatters every store over 16 rows; instead each wave
+    // stages 32 rows of its quadrant at a time (32 rows x 32 NJ BF16 columns) at the start of one
     // of the four slabs, which nobody reads any more, and writes it out as full row segments, 16 bytes per lane.  The
     // 16-byte slot index of a staged row is rotated by the row number, so that the 8-byte writes of
     // 32 rows and the 16-byte reads spread over the banks.  The region is private to the wave and LDS
@@ -573,12 +669,14 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
         }
     };
     // The body exists twice, for one and for two de-scale multiplies; the choice is uniform over the grid.
+    // A lane holds, of the 16 x 16 block (i, j), the four consecutive columns 16 j + 4 (lane / 16) .. of row
+    // 16 i + lane % 16.
     auto write_out = [&](auto two_mul) {
-    auto descale4 = [&](const v16f& block, int g) -> v4f {
+    auto descale4 = [&](const v4f& block) -> v4f {
         v4f y;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            y[e] = block[4 * g + e] * m1;
+            y[e] = block[e] * m1;
             if constexpr (decltype(two_mul)::value) y[e] *= inv_b;
         }
         return y;
@@ -586,36 +684,29 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     if constexpr (!ACCUM) {
         constexpr int kSlots = 4 * NJ;                                       // 16-byte slots per staged row
         constexpr int kPitch = 16 * kSlots;
-        constexpr bool kPow2 = (kSlots & (kSlots - 1)) == 0;
         uint8_t* stage = wave == 0 ? ldsA0 : wave == 1 ? ldsB0 : wave == 2 ? ldsA1 : ldsB1;
-        // byte offset inside a staged row of the 8 bytes this lane writes for column group c8 = col / 8;
-        // with a power-of-two slot count it does not depend on the row block (32 rows apart)
-        int slot_off[kSlots];
-        if constexpr (kPow2) {
-#pragma unroll
-            for (int c8 = 0; c8 < kSlots; ++c8) slot_off[c8] = (((c8 + fr_row) & (kSlots - 1)) << 4) | (fr_half << 3);
-        }
+        // 8 bytes per block: columns 16 j + 4 fr_q .. are slot 2 j + fr_q / 2 of the staged row, half fr_q % 2
+        const int slot0 = fr_q >> 1, half_off = (fr_q & 1) << 3;
         uint16_t* cbase = C + (size_t)(tr * BM + wr * 32 * NI) * Cn + tc * BN + wc * 32 * NJ;
-        constexpr int kBlockPieces = 32 * kSlots;                            // 16-byte pieces of one block of 32 rows
-        // one block of 32 rows at a time: while its stores are in flight the next block is converted
+        constexpr int kBlockPieces = 32 * kSlots;                            // 16-byte pieces of 32 staged rows
+        // 32 rows (two rows of blocks) at a time: while their stores are in flight the next ones are converted
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             if constexpr (V::kEpilogueFence) __builtin_amdgcn_sched_barrier(0);
-            const int row = fr_row;             // the 32 staged rows are reused by every block: LDS runs a wave's accesses in order
-            uint8_t* srow = stage + row * kPitch;
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) {
+            for (int ii = 0; ii < 2; ++ii) {
+                const int row = 16 * ii + fr_row;     // the 32 staged rows are reused every time: LDS runs a wave's accesses in order
+                uint8_t* srow = stage + row * kPitch;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const v4f y = descale4(acc[i][j], g);
+                for (int j = 0; j < MJ; ++j) {
+                    const v4f y = descale4(acc.get(2 * i + ii, j));
                     track4(y);
                     bf16x4 o = __builtin_convertvector(y, bf16x4);
-                    const int c8 = j * 4 + g;                                // columns 8 c8 + 4 fr_half + 0..3
-                    const int off = kPow2 ? slot_off[c8] : ((((c8 + row) % kSlots) << 4) | (fr_half << 3));
+                    const int off = (((2 * j + slot0 + row) % kSlots) << 4) | half_off;
                     *reinterpret_cast<bf16x4*>(srow + off) = o;
                 }
             }
-            // all pieces of the block are read back before the first is stored, so that the LDS round
+            // all pieces of the 32 rows are read back before the first is stored, so that the LDS round
             // trips overlap instead of each store waiting for its own read
             constexpr int kPiecesPerLane = kBlockPieces / kWave;
             v4u piece[kPiecesPerLane];
@@ -638,42 +729,26 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     } else {
         // BF16 accumulation needs the old value before the single rounding: straight from the registers.
         const int row_base = tr * BM + wr * 32 * NI + fr_row;
-        const int col_base = tc * BN + wc * 32 * NJ + fr_half * 4;
+        const int col_base = tc * BN + wc * 32 * NJ + fr_q * 4;
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            uint16_t* crow = C + (size_t)(row_base + i * 32) * Cn + col_base;
+        for (int i = 0; i < MI; ++i) {
+            uint16_t* crow = C + (size_t)(row_base + i * 16) * Cn + col_base;
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    uint16_t* dst = crow + j * 32 + g * 8;
-                    v4f y = descale4(acc[i][j], g);
-                    v2u old = *reinterpret_cast<const v2u*>(dst);
-                    y[0] += __uint_as_float(old[0] << 16);
-                    y[1] += __uint_as_float(old[0] & 0xFFFF0000u);
-                    y[2] += __uint_as_float(old[1] << 16);
-                    y[3] += __uint_as_float(old[1] & 0xFFFF0000u);
-                    track4(y);
-                    *reinterpret_cast<bf16x4*>(dst) = __builtin_convertvector(y, bf16x4);
-                }
+            for (int j = 0; j < MJ; ++j) {
+                uint16_t* dst = crow + j * 16;
+                v4f y = descale4(acc.get(i, j));
+                v2u old = *reinterpret_cast<const v2u*>(dst);
+                y[0] += __uint_as_float(old[0] << 16);
+                y[1] += __uint_as_float(old[0] & 0xFFFF0000u);
+                y[2] += __uint_as_float(old[1] << 16);
+                y[3] += __uint_as_float(old[1] & 0xFFFF0000u);
+                track4(y);
+                *reinterpret_cast<bf16x4*>(dst) = __builtin_convertvector(y, bf16x4);
             }
         }
     }
     };
-    if (SPLIT && !fixup && slot >= 0) {
-        // a piece of a shared tile: the accumulators as they are, 16 bytes per lane and store, 4 KB per store
-        // of the workgroup; the fix-up launch reads them back in the same arrangement
-        v4f* dst = reinterpret_cast<v4f*>(plan.partials + (size_t)slot * (BM * BN)) + threadIdx.x;
-#pragma unroll
-        for (int i = 0; i < NI; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-#pragma unroll
-                for (int g = 0; g < 4; ++g)
-                    dst[((i * NJ + j) * 4 + g) * kGemmThreads] = v4f{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                __builtin_amdgcn_sched_barrier(0);
-            }
-    } else if (one_mul) {
+    if (one_mul) {
         write_out(BoolTag<false>{});
     } else {
         write_out(BoolTag<true>{});
@@ -850,15 +925,9 @@ static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C
     // The pieces first (all CUs start and end them together), their sums next, the whole rounds last.
     if constexpr (split_supported(NI, NJ) && FA != kFmtBf16 && !TA && !TB) {
         if (sc.n_groups) {
-            SplitPlan fix = plan;
-            fix.fixup = 1;
-            if (accumulate) {
-                launch(gemm_tile_kernel<FA, FB, NI, NJ, true, GemmTuning, TA, TB, true>, sc.share_wgs, plan);
-                launch(gemm_tile_kernel<FA, FB, NI, NJ, true, GemmTuning, TA, TB, true>, sc.shared_tiles, fix);
-            } else {
-                launch(gemm_tile_kernel<FA, FB, NI, NJ, false, GemmTuning, TA, TB, true>, sc.share_wgs, plan);
-                launch(gemm_tile_kernel<FA, FB, NI, NJ, false, GemmTuning, TA, TB, true>, sc.shared_tiles, fix);
-            }
+            launch(gemm_tile_kernel<FA, FB, NI, NJ, false, GemmTuning, TA, TB, kSharePieces>, sc.share_wgs, plan);
+            if (accumulate) launch(gemm_tile_kernel<FA, FB, NI, NJ, true, GemmTuning, TA, TB, kShareFixup>, sc.shared_tiles, plan);
+            else launch(gemm_tile_kernel<FA, FB, NI, NJ, false, GemmTuning, TA, TB, kShareFixup>, sc.shared_tiles, plan);
         }
     }
     if (sc.n_whole == 0) return;
@@ -867,11 +936,14 @@ static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C
 }
 
 
-// Dispatch on the tile chosen for the problem; false if none divides it.
+// Dispatch on the tile chosen for the problem; false if none divides it.  One translation unit per operand kinds and
+// layout instantiates this (gemm_tiles_*.hip: each holds the kernels of all tile shapes for its case, and the files
+// compile side by side); everybody else sees the declarations below.
+#define LLMQ_TILE_LAUNCH_PARAMS                                                                                   \
+    const uint8_t *A, const uint8_t *B, int64_t R, int64_t C, int64_t T, const float *sA, const float *sB, void *c, \
+        int accumulate, unsigned *amax, hipStream_t stream, int num_cus, GemmScratch scratch
 template <int FA, int FB, bool TA, bool TB>
-static bool launch_chosen_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
-                               const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
-                               hipStream_t stream, int num_cus, GemmScratch scratch) {
+bool launch_chosen_tile(LLMQ_TILE_LAUNCH_PARAMS) {
     const TileChoice tc = choose_tile(R, C, T, num_cus, (scratch.ptr && !TA && !TB && FA != kFmtBf16) ? scratch.bytes : 0);
 #define LLMQ_TILE_CASE(I, J)                                                                              \
     case I * 8 + J:                                                                                       \
@@ -886,5 +958,18 @@ static bool launch_chosen_tile(const uint8_t* A, const uint8_t* B, int64_t R, in
 #undef LLMQ_TILE_CASE
     return false;
 }
+// contraction-contiguous operands: every mix of E4M3 and E5M2, and BF16 pairs
+extern template bool launch_chosen_tile<0, 0, false, false>(LLMQ_TILE_LAUNCH_PARAMS);
+extern template bool launch_chosen_tile<1, 0, false, false>(LLMQ_TILE_LAUNCH_PARAMS);
+extern template bool launch_chosen_tile<0, 1, false, false>(LLMQ_TILE_LAUNCH_PARAMS);
+extern template bool launch_chosen_tile<1, 1, false, false>(LLMQ_TILE_LAUNCH_PARAMS);
+extern template bool launch_chosen_tile<kFmtBf16, kFmtBf16, false, false>(LLMQ_TILE_LAUNCH_PARAMS);
+// T-major operands: B is E4M3 (weights and activations), A either format
+extern template bool launch_chosen_tile<0, 0, true, true>(LLMQ_TILE_LAUNCH_PARAMS);
+extern template bool launch_chosen_tile<0, 0, false, true>(LLMQ_TILE_LAUNCH_PARAMS);
+extern template bool launch_chosen_tile<0, 0, true, false>(LLMQ_TILE_LAUNCH_PARAMS);
+extern template bool launch_chosen_tile<1, 0, true, true>(LLMQ_TILE_LAUNCH_PARAMS);
+extern template bool launch_chosen_tile<1, 0, false, true>(LLMQ_TILE_LAUNCH_PARAMS);
+extern template bool launch_chosen_tile<1, 0, true, false>(LLMQ_TILE_LAUNCH_PARAMS);
 
 }  // namespace llmq

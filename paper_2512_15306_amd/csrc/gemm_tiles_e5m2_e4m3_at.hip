@@ -1,0 +1,6 @@
+// The tile kernels for E5M2 x E4M3 operands, A T-major.
+#include "gemm_tile.h"
+
+namespace llmq {
+template bool launch_chosen_tile<1, 0, true, false>(LLMQ_TILE_LAUNCH_PARAMS);
+}  // namespace llmq
