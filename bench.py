@@ -564,7 +564,7 @@ def main():
     torch.cuda.empty_cache()
     bf16_tflops = flops / (ms_bf16 * 1e-3) / 1e12
     out["bf16_baseline"] = {
-        "what": "fwd+dgrad+wgrad GEMMs of the same linears on BF16 operands (v_mfma_f32_32x32x16_bf16, same tile "
+        "what": "fwd+dgrad+wgrad GEMMs of the same linears on BF16 operands (v_mfma_f32_16x16x32_bf16, same tile "
                 "kernel), no quantization, pre-transposed operands",
         "ms_per_step": round(ms_bf16, 4), "tflops": round(bf16_tflops, 2),
         "pct_bf16_peak": round(100.0 * bf16_tflops / PEAK_BF16_TFLOPS, 2),

@@ -183,20 +183,21 @@ __device__ inline void static_for(F&& f) {
 template <int FA, int FB>
 __device__ inline void mma_block(v4f& c, const v8i& a, const v8i& b) {
     static_assert((FA == kFmtBf16) == (FB == kFmtBf16), "BF16 operands come in pairs");
+    // The instructions are written out so that the accumulator can be constrained to the accumulator register file
+    // and tied to the result.  Given the builtin, whose accumulators may sit in either file, the register
+    // allocator moves the 4-register blocks between the files inside the K loop (hundreds of copies and a
+    // handful of spills per K step, which made the kernel issue-bound at half its speed).  The compiler does
+    // not know what the statement is, so it adds none of the MFMA wait states; the kernel needs none: fragments
+    // come from LDS reads (waited for by counter), a block is updated again 16 or more MFMAs later, and
+    // the epilogue starts behind wait states of its own, a counter wait and a barrier.
     if constexpr (FA == kFmtBf16) {
         // two v_mfma_f32_16x16x32_bf16, one per 16-byte half of the fragments
         const v4i a_lo = {a[0], a[1], a[2], a[3]}, a_hi = {a[4], a[5], a[6], a[7]};
         const v4i b_lo = {b[0], b[1], b[2], b[3]}, b_hi = {b[4], b[5], b[6], b[7]};
-        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b_lo), __builtin_bit_cast(bf16x8, a_lo), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b_hi), __builtin_bit_cast(bf16x8, a_hi), c, 0, 0, 0);
+        asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(b_lo), "v"(a_lo));
+        asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(b_hi), "v"(a_hi));
     } else {
-        // The instruction is written out so that its accumulator can be constrained to the accumulator register
-        // file and tied to the result.  Given the builtin, whose accumulators may sit in either file, the register
-        // allocator moves the 4-register blocks between the files inside the K loop (hundreds of copies and a
-        // handful of spills per K step, which made the kernel issue-bound at half its speed).  The compiler does
-        // not know what the statement is, so it adds none of the MFMA wait states; the kernel needs none: fragments
-        // come from LDS reads (waited for by counter), a block is updated again 16 or more MFMAs later, and
-        // the epilogue starts behind a counter wait and a barrier.  cbsz / blgp: formats of the first / second operand.
+        // cbsz / blgp: formats of the first / second operand
         asm("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 cbsz:%3 blgp:%4" : "+a"(c) : "v"(b), "v"(a), "n"(FB), "n"(FA));
     }
 }
