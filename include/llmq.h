@@ -173,7 +173,7 @@ int llmq_fp8_gemm_with_scratch(const uint8_t* A, int fmtA, int a_t_major, const 
  * "Impact of FP8", speed-up column of Table 1): no quantization, no scales,
  *   c[r,cc] = bf16( sum_t A[r,t] * B[cc,t] )   (+ c[r,cc] first when accumulate != 0)
  * A [R,T], B [C,T] BF16 with the contraction index contiguous, binary32 accumulation on the matrix cores
- * (v_mfma_f32_32x32x16_bf16 in the same tile kernel), one RNE rounding.  Error per element is bounded by
+ * (v_mfma_f32_16x16x32_bf16 in the same tile kernel), one RNE rounding.  Error per element is bounded by
  * 2^-8 |c| + T 2^-24 sum_t |A[r,t] B[cc,t]|.  Shapes with R, C multiples of 128 and T a multiple of 64
  * take the tuned kernel, others a slow generic one.
  */
@@ -325,8 +325,9 @@ int llmq_rmsnorm_apply_fp8(const void* res_bf16, const void* w_bf16, const float
  * Peak calibration (the paper's appendix "A note on MFU" measures the attainable peak with a large-matmul
  * micro-benchmark instead of trusting the spec sheet).  Both calls only enqueue; the caller times them.
  *
- * llmq_calibrate_mfma: a register-only loop of the GEMM's FP8 MFMA instruction (4 x 4 block pattern, one
- *   workgroup of 4 waves per CU, `iters` passes of 16 MFMAs per wave) with operand registers holding
+ * llmq_calibrate_mfma: a register-only loop of the GEMM's FP8 MFMA instruction (v_mfma_f32_16x16x128_f8f6f4 in
+ *   the 8 x 8 block pattern of a wave tile, one workgroup of 4 waves per CU, `iters` passes of 64 MFMAs per wave;
+ *   the 32x32x64 form of the instruction sustains about a tenth less on random bits) with operand registers holding
  *   constants (random_bits == 0) or random FP8 bits (random_bits != 0; the matrix cores are power-limited and
  *   sustain a lower clock on random bits, as on real quantized data).  d_sink: [1] float, device, practically
  *   never written.  *flops (host pointer, may be NULL) receives the FLOP count of the launch.

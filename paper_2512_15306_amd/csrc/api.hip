@@ -376,7 +376,7 @@ int llmq_calibrate_mfma(int fmtA, int fmtB, int random_bits, int iters, float* d
     if (iters < 1 || iters > (1 << 24)) return LLMQ_ERR_SHAPE;
     if (!aligned(d_sink, 4)) return LLMQ_ERR_ALIGN;
     // workgroups x waves x iterations x 16 MFMAs x 2 * 32 * 32 * 64 FLOP
-    if (flops) *flops = (double)num_cus() * 4.0 * iters * 16.0 * 2.0 * 32 * 32 * 64;
+    if (flops) *flops = (double)num_cus() * 4.0 * iters * 64.0 * 2.0 * 16 * 16 * 128;
     return llmq::launch_calibrate_mfma(fmtA, fmtB, random_bits != 0, iters, d_sink, static_cast<hipStream_t>(stream),
                                        num_cus());
 }

@@ -1,6 +1,6 @@
 // Peak calibration kernels: what this chip actually sustains, to report next to the published peaks
 // (the paper's appendix "A note on MFU" calibrates its own peaks with a large-matmul micro-benchmark).
-//   - a register-only loop of v_mfma_f32_32x32x64_f8f6f4 in the 4 x 4 block pattern of the GEMM, with
+//   - a register-only loop of v_mfma_f32_16x16x128_f8f6f4 in the 8 x 8 block pattern of the GEMM's wave tile, with
 //     operand registers holding either constants or random FP8 bits: the matrix cores are power-limited,
 //     and random bits (like real quantized data) sustain a lower clock than constants do;
 //   - a 16-bytes-per-lane copy for the HBM read+write rate.
@@ -16,9 +16,9 @@ __device__ inline unsigned mix32(unsigned x) {
 
 template <int FA, int FB>
 __global__ __launch_bounds__(256, 1) void calibrate_mfma_kernel(float* sink, int iters, int random_bits) {
-    v8i a[4], b[4];
+    v8i a[8], b[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const unsigned ra = mix32(threadIdx.x * 64 + i * 8 + e + blockIdx.x * 7919u), rb = mix32(ra + 12345u);
@@ -26,25 +26,25 @@ __global__ __launch_bounds__(256, 1) void calibrate_mfma_kernel(float* sink, int
             a[i][e] = random_bits ? (int)(ra & 0xBFBFBFBFu) : 0x38383838;
             b[i][e] = random_bits ? (int)(rb & 0xBFBFBFBFu) : 0x38383838;
         }
-    v16f acc[4][4];
+    v4f acc[8][8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 8; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+            for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.0f;
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 8; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[i][j], FB, FA, 0, 0, 0, 0);
+            for (int j = 0; j < 8; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b[j], a[i], acc[i][j], FB, FA, 0, 0, 0, 0);
     }
     float s = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) s += acc[i][j][0] + acc[i][j][9];
+        for (int j = 0; j < 8; ++j) s += acc[i][j][0] + acc[i][j][3];
     if (s == 12345.678f) sink[0] = s;            // keeps the loop alive; practically never taken
 }
 

@@ -11,9 +11,8 @@
 //     4 x 4: the whole accumulator file);
 //   - K advances 128 bytes per step, one MFMA deep; the A and B slabs (BM / BN rows x 128 B) go from global
 //     memory straight into LDS with buffer_load ... lds (16 bytes per lane, no VGPR staging), double buffered;
-//   - LDS rows are 128 B; the 16-byte chunk index is XOR-ed with (row >> 1) & 7, applied on the
-//     global side of the load, so that ds_read_b128 fragment reads of 16 consecutive rows spread
-//     over all 64 banks;
+//   - LDS rows are 128 B; the 16-byte chunk index is XOR-ed with a function of the row (row_swizzle), applied
+//     on the global side of the load, so that the ds_read_b128 fragment reads run without bank conflicts;
 //   - the order of the contraction index inside one MFMA does not matter as long as A and B use
 //     the same order, so lane L simply reads the 32 contiguous bytes [32 (L / 16), +32) of row L % 16;
 //   - every step is software pipelined in four quarters (half the block rows x half the block columns): the MFMAs
@@ -130,9 +129,6 @@ struct GemmTuning {
     // The fused output absmax with the IEEE 754-2019 maximum (v_maximum3_f32: two elements per instruction, NaN
     // propagates) or, for comparison in the phase stamps only, with maxNum (v_max_f32 per element, NaN dropped).
     static constexpr bool kIeeeMaximum = true;
-    // LDS swizzle of the operand slabs: the 16-byte chunk index of a row is XOR-ed with
-    // (row >> kSwizzleShift) & 7.
-    static constexpr int kSwizzleShift = 1;
 };
 
 template <bool B>
@@ -219,9 +215,17 @@ __device__ inline void mma_quadrant(BlockAcc<MI, MJ>& acc, const v8i (&a)[HI], c
     });
 }
 
+// LDS swizzle of a row-wise slab: the 16-byte chunk index of a row (row index modulo 16) is XOR-ed with this.
+// A fragment read has lane L fetch chunks 2 (L / 16) and 2 (L / 16) + 1 of row L % 16 with ds_read_b128, which the
+// LDS serves 16 lanes (256 B) per cycle when their bank groups differ; which 16 lanes share a cycle was not
+// established, only what each candidate costs with four waves reading back to back: this function 4.0 cycles per
+// instruction (the same as a linear pattern), (row >> 1) & 7 and row & 7 8.0, no swizzle 16.0.  The GEMM itself runs
+// the same with 4 or 8 cycles per read (the LDS is a quarter or half busy), within 1 %.
+__device__ constexpr int row_swizzle(int row) { return (((row >> 1) & 3) << 1) | ((row >> 3) & 1); }
+
 // How one operand slab sits in memory and in LDS, and how its MFMA fragments are read.
 //   TMAJOR = false: the operand is [rows, T], a slab is 64 NX rows of 128 B; LDS keeps the rows, 128 B
-//     each, the 16-byte chunk index XOR-ed with (row >> kSwizzleShift) & 7; a lane reads the 32 contiguous
+//     each, the 16-byte chunk index XOR-ed with row_swizzle(row); a lane reads the 32 contiguous
 //     bytes of its row with two ds_read_b128.
 //   TMAJOR = true: the operand is [T, rows] (the contraction index runs down the rows, `ld` bytes apart),
 //     a slab is 128 rows of 64 NX bytes and LDS keeps it that way.  A lane's 32 contraction bytes then sit
@@ -333,10 +337,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
                                           : make_rsrc(A + (size_t)tr * BM * T, (unsigned)((size_t)BM * T));
     const __amdgpu_buffer_rsrc_t rsB = TB ? make_rsrc(B + (size_t)tc * BN, (unsigned)((size_t)T * ldB - (size_t)tc * BN))
                                           : make_rsrc(B + (size_t)tc * BN * T, (unsigned)((size_t)BN * T));
-    constexpr int kSw = V::kSwizzleShift;
     const int ld_row = lane >> 3;                                   // row inside the group of 8
-    const int ld_voff0 = ld_row * T + (((lane & 7) ^ ((ld_row >> kSw) & 7)) << 4);
-    const int ld_voff1 = ld_row * T + (((lane & 7) ^ (((8 + ld_row) >> kSw) & 7)) << 4);
+    const int ld_voff0 = ld_row * T + (((lane & 7) ^ row_swizzle(ld_row)) << 4);
+    const int ld_voff1 = ld_row * T + (((lane & 7) ^ row_swizzle(8 + ld_row)) << 4);
     auto tmajor_voff = [&](auto shape, int m, int ld) {             // pattern m of a T-major operand
         typedef decltype(shape) S;
         const int unit = 64 * m + lane, row = unit / S::kUnits, col = unit % S::kUnits;
@@ -389,7 +392,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     // chunks of its LDS row).
     const int fr_row = lane & 15;
     const int fr_q = lane >> 4;                                     // which 32 bytes of the 128-byte K step
-    const int swz = (fr_row >> kSw) & 7;                            // same for every row this lane reads
+    const int swz = row_swizzle(fr_row);                            // same for every row this lane reads
     const int offA = (wr * 32 * NI + fr_row) * BK, offB = (wc * 32 * NJ + fr_row) * BK;
     const int ch0 = ((fr_q * 2) ^ swz) << 4, ch1 = ((fr_q * 2 + 1) ^ swz) << 4;
     // read number p of a fragment set: 16-byte half p % 2 of fragment p / 2
