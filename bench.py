@@ -28,7 +28,7 @@ PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E, published
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by a plain 1 GiB copy
 # (profiles/bench_config<N>_gemm_quantize_amax.md); None where not measured.  They include hits in the
 # memory-side last-level cache: the 8 XCDs have private L2s and each re-reads the operands of its tiles.
-MEASURED_GEMM_TRAFFIC_BYTES = {2: 222.4e6, 3: 977.5e6, 4: 1084.3e6, 5: 3827.9e6}
+MEASURED_GEMM_TRAFFIC_BYTES = {2: 222.4e6, 3: 978.3e6, 4: 1091.5e6, 5: 3699.4e6}
 HEADLINE_CONFIG = 5           # the largest single-GPU configuration (32B-class block)
 SIDE_CONFIGS = (3, 4)         # 7B- and 14B-class blocks: reported in the same line
 
@@ -44,6 +44,8 @@ def parse():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--prequantized-w", action="store_true",
                    help="weights quantized once outside the timed region (reused across micro-steps)")
+    p.add_argument("--whole-tiles", action="store_true",
+                   help="linear calls without LLMQ_SHARE_TILES: every output tile is computed whole")
     p.add_argument("--phase-stamps", action="store_true",
                    help="instead of the benchmark: cycle stamps of the phases of the GEMM tile kernel on two forward GEMMs")
     p.add_argument("--power-probe", action="store_true",
@@ -62,7 +64,7 @@ class LinearState:
         self.X = synth.make_x(cfg, li, device=dev)
         self.W = synth.make_w(cfg, li, device=dev)
         self.dY = synth.make_dy(cfg, li, device=dev)
-        self.ws = torch.empty(llmq.llmq_fp8_linear_workspace_bytes(M, N, K), dtype=torch.uint8, device=dev)
+        self.ws = torch.empty(llmq.llmq_fp8_linear_workspace_bytes_shared(M, N, K), dtype=torch.uint8, device=dev)
         self.offs = llmq.llmq_fp8_linear_workspace_offsets(M, N, K)
         self.Y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
         self.dX = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
@@ -79,15 +81,22 @@ class LinearState:
         return self.ws[o:o + shape[0] * shape[1]].view(shape)
 
 
-def run_step(states, prequantized_w, producer_absmax=False, extra_flags=0):
+# Flags every linear call of the step carries unless a leg says otherwise (set in main from --whole-tiles).
+DEFAULT_LINEAR_FLAGS = {"flags": 0}
+
+
+def run_step(states, prequantized_w, producer_absmax=False, extra_flags=None):
     """Per linear: absmax + scale + quantize(+transpose) of X and W inside the forward call (just-in-time
     scaling: first absmax stage, then the quantize kernel finishes the reduction), forward GEMM, the same for
     dY inside the dgrad call, dgrad GEMM, wgrad GEMM on the copies already there.
     producer_absmax: the absmax passes over X and dY are left out, as when the producing kernel (RMSNorm,
     SwiGLU, the previous GEMM's epilogue) has already delivered them; the scales of the last full step are
     used.  Reported as a side figure only.
-    extra_flags: LLMQ_NO_TRANSPOSE for the side figure without transposed copies."""
+    extra_flags: LLMQ_NO_TRANSPOSE for the side figure without transposed copies; by default LLMQ_SHARE_TILES (the
+    contractions may share a ragged last round of tiles among all compute units; --whole-tiles turns it off)."""
     from paper_2512_15306_amd import llmq
+    if extra_flags is None:
+        extra_flags = DEFAULT_LINEAR_FLAGS["flags"]
     for s in states:
         M, K, N = s.M, s.K, s.N
         fx = extra_flags | (0 if producer_absmax else llmq.JIT_X)
@@ -99,10 +108,12 @@ def run_step(states, prequantized_w, producer_absmax=False, extra_flags=0):
                                    extra_flags | llmq.REUSE_X | llmq.REUSE_DY)
 
 
-def run_gemms_only(states, extra_flags=0):
+def run_gemms_only(states, extra_flags=None):
     """The three GEMM launches of every linear on the operands the step left in the workspace, through
     the same entry points as the step (all REUSE flags set: nothing is quantized)."""
     from paper_2512_15306_amd import llmq
+    if extra_flags is None:
+        extra_flags = DEFAULT_LINEAR_FLAGS["flags"]
     for s in states:
         M, K, N = s.M, s.K, s.N
         llmq.llmq_fp8_linear_fwd(None, None, M, N, K, s.sx, s.sw, s.Y, None, s.ws, extra_flags | llmq.REUSE_X | llmq.REUSE_W)
@@ -475,6 +486,8 @@ def workload_name(cfg, prequantized_w):
 
 
 def roofline_of(r):
+    """One "launch" is one contraction (a linear call with all REUSE flags): one kernel launch, or three where the
+    last round of tiles is shared out (pieces, their sums, the whole rounds; LLMQ_SHARE_TILES)."""
     gemm_tflops = r["flops"] / (r["ms_gemm"] * 1e-3) / 1e12
     return {"kernel": "gemm_tile_kernel", "bound": "mfma", "achieved": round(gemm_tflops, 2),
             "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / PEAK_FP8_TFLOPS, 4),
@@ -523,6 +536,7 @@ def main():
     if args.power_probe:
         print(json.dumps({"power_probe": power_probe(dev)}))
         return
+    DEFAULT_LINEAR_FLAGS["flags"] = 0 if args.whole_tiles else llmq.SHARE_TILES
     cfg = synth.CONFIGS[args.config or HEADLINE_CONFIG]
     peaks = measure_peaks(dev)
     r = measure_config(cfg, args, dev, full=True)
@@ -536,6 +550,7 @@ def main():
         "ms_per_step": rates["ms_per_step"], "wall_ms_per_step": round(r["wall"], 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "fp8", "data": "synthetic",
         "config": {"workload": workload_name(cfg, args.prequantized_w)},
+        "linear_flags": "LLMQ_JIT_* (scales found inside the calls)" + ("" if args.whole_tiles else " | LLMQ_SHARE_TILES"),
     }
     out.update({k: v for k, v in rates.items() if k not in ("ms_per_step", "step_tflops")})
     out.update({

@@ -187,10 +187,13 @@ int llmq_bf16_gemm_tn(const void* A_bf16, const void* B_bf16, int64_t R, int64_t
  * each starting at a multiple of 256 bytes.  llmq_fp8_linear_workspace_offsets() returns the byte offsets of
  * the copies in the order Xq, Xq_t, Wq, Wq_t, dYq, dYq_t.  Calls that carry LLMQ_NO_TRANSPOSE touch nothing
  * behind the scratch and accept a workspace of llmq_fp8_linear_workspace_bytes_no_transpose() bytes (half the
- * FP8 copies).  The caller owns the workspace and may read the copies between calls.
+ * FP8 copies); calls that carry LLMQ_SHARE_TILES need llmq_fp8_linear_workspace_bytes_shared() bytes: the same
+ * layout with a section for the binary32 pieces of shared tiles behind it (0-100 MB more, by the shapes).
+ * The caller owns the workspace and may read the copies between calls.
  */
 size_t llmq_fp8_linear_workspace_bytes(int64_t M, int64_t N, int64_t K);
 size_t llmq_fp8_linear_workspace_bytes_no_transpose(int64_t M, int64_t N, int64_t K);
+size_t llmq_fp8_linear_workspace_bytes_shared(int64_t M, int64_t N, int64_t K);
 int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t offsets[6]);
 
 /* `flags` of the linear calls: the named operand's FP8 copies are already in the workspace (written by
@@ -216,6 +219,15 @@ int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t of
  * under this flag can only be reused (LLMQ_REUSE_*) by calls that carry it too, copies made without it by
  * any call; results are bit-identical either way. */
 #define LLMQ_NO_TRANSPOSE 64
+/* The call's contraction may share the output tiles of a ragged last round among all compute units, as
+ * llmq_fp8_gemm_with_scratch does (pieces along the contraction index, added in a fixed order by a second
+ * launch: Section 3 "Reproducibility"; run to run the same bytes).  The planner shares only where it was
+ * measured to win (long contractions with few left-over tiles), so most shapes are not affected at all; where it
+ * shares, the binary32 sums are taken in another order than with whole tiles, so the BF16 results may differ in
+ * the last bit from those of a call without the flag (both within the error bound of llmq_fp8_gemm_tn).  In a
+ * block's sequence of contractions it measured +1 % (32B- and 14B-class shapes).  Not together with LLMQ_NO_TRANSPOSE
+ * (LLMQ_ERR_FLAGS); the workspace must hold llmq_fp8_linear_workspace_bytes_shared() bytes. */
+#define LLMQ_SHARE_TILES 128
 
 /*
  * Forward: Y[M,N] = X[M,K] W[N,K]^T in FP8 (E4M3 x E4M3), BF16 out.

@@ -30,6 +30,7 @@ int num_cus() {
 struct WsLayout {
     size_t xq, xqt, wq, wqt, dyq, dyqt, part;     // part: three absmax scratch areas (X, W, dY)
     size_t compact, total;                        // bytes needed without / with the transposed copies
+    size_t pieces, pieces_bytes, shared_total;    // LLMQ_SHARE_TILES: binary32 pieces of shared tiles behind everything else
 };
 
 // Row-major copies and the scratch first, the transposed copies behind them: a workspace that ends after the
@@ -46,17 +47,29 @@ WsLayout ws_layout(int64_t M, int64_t N, int64_t K) {
     l.wqt = off;  off += round256((size_t)N * K);
     l.dyqt = off; off += round256((size_t)M * N);
     l.total = off;
+    // what the largest of the three contractions may write when its ragged last round of tiles is shared out
+    size_t need = llmq::gemm_scratch_bytes(M, N, K, num_cus());
+    const size_t dgrad = llmq::gemm_scratch_bytes(M, K, N, num_cus()), wgrad = llmq::gemm_scratch_bytes(N, K, M, num_cus());
+    if (dgrad > need) need = dgrad;
+    if (wgrad > need) need = wgrad;
+    l.pieces = off; l.pieces_bytes = round256(need); off += l.pieces_bytes;
+    l.shared_total = off;
     return l;
 }
 
-// The linear calls compute every output tile whole: sharing a ragged last round among all CUs
-// (llmq_fp8_gemm_with_scratch) did not pay inside a block's sequence of GEMMs on this power-limited chip.
-constexpr llmq::GemmScratch kNoScratch{nullptr, 0};
+// The scratch a linear call hands to its contraction: the pieces section under LLMQ_SHARE_TILES, nothing otherwise
+// (every output tile is then computed whole).
+llmq::GemmScratch pieces_of(const WsLayout& l, void* ws, int flags) {
+    if (!(flags & LLMQ_SHARE_TILES) || l.pieces_bytes == 0) return llmq::GemmScratch{nullptr, 0};
+    return llmq::GemmScratch{reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + l.pieces), l.pieces_bytes};
+}
 
 int check_linear(int64_t M, int64_t N, int64_t K, const void* ws, size_t ws_bytes, int flags) {
     if (!dim_ok(M) || !dim_ok(N) || !dim_ok(K)) return LLMQ_ERR_SHAPE;
     if (M * K >= kMaxElems || N * K >= kMaxElems || M * N >= kMaxElems) return LLMQ_ERR_SHAPE;
-    if (flags & ~(LLMQ_REUSE_X | LLMQ_REUSE_W | LLMQ_REUSE_DY | LLMQ_JIT_X | LLMQ_JIT_W | LLMQ_JIT_DY | LLMQ_NO_TRANSPOSE)) return LLMQ_ERR_FLAGS;
+    if (flags & ~(LLMQ_REUSE_X | LLMQ_REUSE_W | LLMQ_REUSE_DY | LLMQ_JIT_X | LLMQ_JIT_W | LLMQ_JIT_DY | LLMQ_NO_TRANSPOSE | LLMQ_SHARE_TILES)) return LLMQ_ERR_FLAGS;
+    // tiles are shared only by the kernels for contraction-contiguous operands
+    if ((flags & LLMQ_SHARE_TILES) && (flags & LLMQ_NO_TRANSPOSE)) return LLMQ_ERR_FLAGS;
     // an operand is either reused or scaled just in time, not both
     if (((flags & LLMQ_REUSE_X) && (flags & LLMQ_JIT_X)) || ((flags & LLMQ_REUSE_W) && (flags & LLMQ_JIT_W)) ||
         ((flags & LLMQ_REUSE_DY) && (flags & LLMQ_JIT_DY)))
@@ -64,7 +77,7 @@ int check_linear(int64_t M, int64_t N, int64_t K, const void* ws, size_t ws_byte
     if (!ws) return LLMQ_ERR_NULL;
     if (!aligned(ws, 256)) return LLMQ_ERR_ALIGN;
     const WsLayout l = ws_layout(M, N, K);
-    if (ws_bytes < ((flags & LLMQ_NO_TRANSPOSE) ? l.compact : l.total)) return LLMQ_ERR_WORKSPACE;
+    if (ws_bytes < ((flags & LLMQ_NO_TRANSPOSE) ? l.compact : (flags & LLMQ_SHARE_TILES) ? l.shared_total : l.total)) return LLMQ_ERR_WORKSPACE;
     return LLMQ_OK;
 }
 
@@ -197,6 +210,11 @@ size_t llmq_fp8_linear_workspace_bytes_no_transpose(int64_t M, int64_t N, int64_
     return ws_layout(M, N, K).compact;
 }
 
+size_t llmq_fp8_linear_workspace_bytes_shared(int64_t M, int64_t N, int64_t K) {
+    if (!dim_ok(M) || !dim_ok(N) || !dim_ok(K)) return 0;
+    return ws_layout(M, N, K).shared_total;
+}
+
 int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t offsets[6]) {
     if (!offsets) return LLMQ_ERR_NULL;
     if (!dim_ok(M) || !dim_ok(N) || !dim_ok(K)) return LLMQ_ERR_SHAPE;
@@ -228,7 +246,7 @@ int llmq_fp8_linear_fwd(const void* X, const void* W, int64_t M, int64_t N, int6
     if (qx && (st = quantize_operand(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, nt ? nullptr : base + l.xqt, (flags & LLMQ_JIT_X) != 0, part, zero, s))) return st;
     if (qw && (st = quantize_operand(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, nt ? nullptr : base + l.wqt, (flags & LLMQ_JIT_W) != 0, part + kPartWords, qx ? nullptr : zero, s))) return st;
     return llmq::launch_gemm_tn(base + l.xq, LLMQ_E4M3, base + l.wq, LLMQ_E4M3, M, N, K, d_scale_x, d_scale_w,
-                                Y, 0, d_amax_y, zeroed, s, num_cus(), kNoScratch);
+                                Y, 0, d_amax_y, zeroed, s, num_cus(), pieces_of(l, ws, flags));
 }
 
 int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, int64_t K,
@@ -255,7 +273,7 @@ int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, i
     if (qw && (st = quantize_operand(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, nt ? nullptr : base + l.wqt, (flags & LLMQ_JIT_W) != 0, part + kPartWords, qd ? nullptr : zero, s))) return st;
     // dX[m,k] = sum_n dYq[m,n] * Wq_t[k,n] = sum_n dYq[m,n] * Wq[n,k]
     return llmq::launch_gemm_fp8(base + l.dyq, fmt_dy, false, nt ? base + l.wq : base + l.wqt, LLMQ_E4M3, nt, M, K, N,
-                                 d_scale_dy, d_scale_w, dX, 0, d_amax_dx, zeroed, s, num_cus(), kNoScratch);
+                                 d_scale_dy, d_scale_w, dX, 0, d_amax_dx, zeroed, s, num_cus(), pieces_of(l, ws, flags));
 }
 
 int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, int64_t K,
@@ -280,7 +298,7 @@ int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, i
     if (qx && (st = quantize_operand(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, nt ? nullptr : base + l.xqt, (flags & LLMQ_JIT_X) != 0, part, nullptr, s))) return st;
     // dW[n,k] = sum_m dYq_t[n,m] * Xq_t[k,m] = sum_m dYq[m,n] * Xq[m,k]
     return llmq::launch_gemm_fp8(nt ? base + l.dyq : base + l.dyqt, fmt_dy, nt, nt ? base + l.xq : base + l.xqt, LLMQ_E4M3, nt,
-                                 N, K, M, d_scale_dy, d_scale_x, dW, accumulate, nullptr, false, s, num_cus(), kNoScratch);
+                                 N, K, M, d_scale_dy, d_scale_x, dW, accumulate, nullptr, false, s, num_cus(), pieces_of(l, ws, flags));
 }
 
 int llmq_scale_from_amax(const float* d_amax, int fmt, float* d_scale, void* stream) {

@@ -20,13 +20,14 @@ JIT_X = 8
 JIT_W = 16
 JIT_DY = 32
 NO_TRANSPOSE = 64
+SHARE_TILES = 128
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libllmq.so")
 _lib = None
 
 EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "llmq_amax", "llmq_amax_static", "llmq_quantize_fp8", "llmq_fp8_gemm_tn", "llmq_fp8_gemm", "llmq_fp8_gemm_scratch_bytes", "llmq_fp8_gemm_with_scratch", "llmq_bf16_gemm_tn",
-           "llmq_fp8_linear_workspace_bytes", "llmq_fp8_linear_workspace_bytes_no_transpose", "llmq_fp8_linear_workspace_offsets",
+           "llmq_fp8_linear_workspace_bytes", "llmq_fp8_linear_workspace_bytes_no_transpose", "llmq_fp8_linear_workspace_bytes_shared", "llmq_fp8_linear_workspace_offsets",
            "llmq_fp8_linear_fwd", "llmq_fp8_linear_dgrad", "llmq_fp8_linear_wgrad",
            "llmq_scale_from_amax", "llmq_swiglu_workspace_bytes", "llmq_swiglu_fwd", "llmq_swiglu_fwd_fp8",
            "llmq_swiglu_bwd", "llmq_rmsnorm_workspace_bytes", "llmq_rmsnorm_fwd", "llmq_rmsnorm_apply_fp8",
@@ -76,6 +77,8 @@ def lib() -> ctypes.CDLL:
     L.llmq_fp8_linear_workspace_bytes.argtypes = [i64, i64, i64]
     L.llmq_fp8_linear_workspace_bytes_no_transpose.restype = sz
     L.llmq_fp8_linear_workspace_bytes_no_transpose.argtypes = [i64, i64, i64]
+    L.llmq_fp8_linear_workspace_bytes_shared.restype = sz
+    L.llmq_fp8_linear_workspace_bytes_shared.argtypes = [i64, i64, i64]
     L.llmq_fp8_linear_workspace_offsets.restype = i32
     L.llmq_fp8_linear_workspace_offsets.argtypes = [i64, i64, i64, c.POINTER(sz)]
     L.llmq_fp8_linear_fwd.restype = i32
@@ -231,6 +234,10 @@ def llmq_fp8_linear_workspace_bytes(M: int, N: int, K: int) -> int:
 
 def llmq_fp8_linear_workspace_bytes_no_transpose(M: int, N: int, K: int) -> int:
     return int(lib().llmq_fp8_linear_workspace_bytes_no_transpose(M, N, K))
+
+
+def llmq_fp8_linear_workspace_bytes_shared(M: int, N: int, K: int) -> int:
+    return int(lib().llmq_fp8_linear_workspace_bytes_shared(M, N, K))
 
 
 def llmq_fp8_linear_workspace_offsets(M: int, N: int, K: int) -> Tuple[int, ...]:

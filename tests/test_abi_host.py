@@ -43,6 +43,13 @@ def test_workspace_layout():
     offs = llmq.llmq_fp8_linear_workspace_offsets(3, 5, 7)
     assert all(o % 256 == 0 for o in offs) and len(set(offs)) == 6
     assert llmq.llmq_fp8_linear_workspace_bytes(0, 1, 1) == 0
+    assert llmq.llmq_fp8_linear_workspace_bytes_shared(1, 1, 0) == 0
+    # the section for the pieces of shared tiles comes behind everything else and is as large as the largest
+    # of the three contractions asks for (nothing for shapes that never share)
+    assert llmq.llmq_fp8_linear_workspace_bytes_shared(M, N, K) == total
+    big = (16384, 5120, 7168)
+    want = max(llmq.llmq_fp8_gemm_scratch_bytes(*rct) for rct in ((16384, 5120, 7168), (16384, 7168, 5120), (5120, 7168, 16384)))
+    assert want > 0 and llmq.llmq_fp8_linear_workspace_bytes_shared(*big) == llmq.llmq_fp8_linear_workspace_bytes(*big) + want
     assert llmq.llmq_fp8_linear_workspace_bytes_no_transpose(1, 0, 1) == 0
 
 
@@ -86,7 +93,12 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, None, n(need), 0, None) == -1
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need - 1), 0, None) == -5
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws + 16, n(need), 0, None) == -3
-    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 128, None) == -7
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 256, None) == -7
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 128 | 64, None) == -7  # shared tiles need the transposed copies
+    big = (16384, 5120, 7168)                                   # a shape whose weight gradient shares tiles
+    shared, plain = llmq.llmq_fp8_linear_workspace_bytes_shared(*big), llmq.llmq_fp8_linear_workspace_bytes(*big)
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, *big, ok_ptr, ok_ptr, ok_ptr, None, ws, n(plain), 128, None) == -5
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, *big, ok_ptr, ok_ptr, ok_ptr, None, ws, n(shared - 1), 128, None) == -5
     small = llmq.llmq_fp8_linear_workspace_bytes_no_transpose(16, 16, 16)
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(small), 0, None) == -5
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(small - 1), 64, None) == -5

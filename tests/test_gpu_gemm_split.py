@@ -145,3 +145,57 @@ def test_full_size_gemms_the_planner_shares(cfg_i, li, which):
     got = c[torch.from_numpy(rr).to(DEV), torch.from_numpy(cc).to(DEV)].cpu().to(torch.float64).numpy()
     assert np.all(np.abs(got - y) <= GEMM_TOL * S)
     assert not torch.isnan(c).any()
+
+
+@pytest.mark.parametrize("cfg_i,li", [(5, 0), (4, 2), (3, 1)])
+def test_linear_calls_that_may_share_tiles(cfg_i, li):
+    """LLMQ_SHARE_TILES on the three linear calls, as bench.py's step carries it: config 5's qkv projection (its
+    weight gradient shares tiles), config 4's gate/up projection (its input gradient does) and config 3's
+    attention-out projection (nothing is shared).  Outputs of contractions that share nothing are the bytes of the
+    calls without the flag; the others are checked against the oracle on sampled outputs, with the last tile row
+    and column among them, and must come out the same bytes when run again."""
+    cfg = synth.CONFIGS[cfg_i]
+    lin = cfg.linears[li]
+    M, K, N = cfg.M, lin.K, lin.N
+    print("config %d %s M=%d K=%d N=%d" % (cfg_i, lin.name, M, K, N), flush=True)
+    X, W, dY = synth.make_x(cfg, li, device=DEV), synth.make_w(cfg, li, device=DEV), synth.make_dy(cfg, li, device=DEV)
+    ws = torch.full((llmq.llmq_fp8_linear_workspace_bytes_shared(M, N, K),), 0xFF, dtype=torch.uint8, device=DEV)
+    sx, sw, sd = (torch.zeros(1, dtype=torch.float32, device=DEV) for _ in range(3))
+
+    def run(flags):
+        Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+        dX = torch.full((M, K), float("nan"), dtype=torch.bfloat16, device=DEV)
+        dW = torch.full((N, K), float("nan"), dtype=torch.bfloat16, device=DEV)
+        adx = torch.full((1,), -1.0, dtype=torch.float32, device=DEV)
+        llmq.llmq_fp8_linear_fwd(X, W, M, N, K, sx, sw, Y, None, ws, flags | llmq.JIT_X | llmq.JIT_W)
+        llmq.llmq_fp8_linear_dgrad(dY, None, M, N, K, sd, sw, llmq.E5M2, dX, adx, ws, flags | llmq.JIT_DY | llmq.REUSE_W)
+        llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, sd, sx, llmq.E5M2, dW, False, ws, flags | llmq.REUSE_X | llmq.REUSE_DY)
+        torch.cuda.synchronize()
+        return Y, dX, dW, adx
+
+    whole = run(0)
+    shared = run(llmq.SHARE_TILES)
+    again = run(llmq.SHARE_TILES)
+    offs = llmq.llmq_fp8_linear_workspace_offsets(M, N, K)
+    copy = lambda i, r, c: ws[offs[i]:offs[i] + r * c].view(r, c).cpu().numpy()
+    operands = {"fwd": (copy(0, M, K), 0, copy(2, N, K), 0, sx, sw, (M, N, K)),
+                "dgrad": (copy(4, M, N), 1, copy(3, K, N), 0, sd, sw, (M, K, N)),
+                "wgrad": (copy(5, N, M), 1, copy(1, K, M), 0, sd, sx, (N, K, M))}
+    any_shared = False
+    for k, which in enumerate(("fwd", "dgrad", "wgrad")):
+        A, fa, B, fb, sa, sb, (R, C, T) = operands[which]
+        assert torch.equal(shared[k].view(torch.int16), again[k].view(torch.int16)), which
+        assert not torch.isnan(shared[k]).any(), which
+        if llmq.llmq_fp8_gemm_scratch_bytes(R, C, T) == 0:
+            assert torch.equal(shared[k].view(torch.int16), whole[k].view(torch.int16)), which
+            continue
+        any_shared = True
+        rr, cc = _sample_positions(R, C, 2048, 7 + k)
+        extra_r = np.concatenate([np.full(C // 64, R - 1 - 256 * (i % 2)) for i in range(2)])
+        extra_c = np.concatenate([np.arange(0, C, 64) for _ in range(2)])
+        rr, cc = np.concatenate([rr, extra_r]), np.concatenate([cc, extra_c])
+        y, S = oracle.gemm_tn_sampled(A, fa, B, fb, sa.item(), sb.item(), rr, cc)
+        got = shared[k][torch.from_numpy(rr).to(DEV), torch.from_numpy(cc).to(DEV)].cpu().to(torch.float64).numpy()
+        assert np.all(np.abs(got - y) <= GEMM_TOL * S), which
+    assert any_shared == (cfg_i != 3)
+    assert shared[3].item() == shared[1].float().abs().max().item()
