@@ -842,8 +842,8 @@ struct SplitChoice {
 // Whether sharing is used at all is decided by what was measured on the chip, which is power-limited on real
 // data: CUs left idle by a ragged round let the busy ones clock higher, so a round a fifth to a half full costs
 // 0.4-0.9 of a full one, while the pieces launch costs its K steps + ~30 us and the fix-up launch 45-70 us.
-// Sharing won (3-7 % of the GEMM) only for long contractions (T >= 16384) with all left-over tiles in one
-// group of pieces of at least 24 K steps; it lost 4-13 % on shorter contractions and with several groups.
+// Sharing wins 1-13 % of the GEMM for contractions of 64 K steps or more (T >= 8192) with all left-over tiles in
+// one group (pieces of 8 K steps at least); it loses 4-30 % on shorter contractions and with several groups.
 inline SplitChoice choose_split(int nt, int nk, int slots, int ni, int nj, size_t scratch_bytes) {
     const double unit = 1.25 * ni * nj / 16.0, ovh = 7.0;
     const double tile_f32 = 4.0 * 4096 * ni * nj, tile_out = 2.0 * 4096 * ni * nj;
@@ -888,7 +888,7 @@ inline SplitChoice choose_split(int nt, int nk, int slots, int ni, int nj, size_
     c.cost_us += 4.0 + (2.0 * pieces_total * tile_f32 + r * tile_out) / 4.0e6;
     if ((double)c.slots * tile_f32 > (double)scratch_bytes) return whole;
     // LLMQ_GEMM_SPLIT=1 or a<n>: whenever possible; otherwise only where it was measured to win
-    if (!force && !(nk >= 128 && c.n_groups == 1 && c.group[0].steps >= 24)) return whole;
+    if (!force && !(nk >= 64 && c.n_groups == 1)) return whole;
     if (c.cost_us > whole.cost_us) c.cost_us = whole.cost_us;
     return c;
 }
