@@ -46,6 +46,8 @@ def parse():
                    help="weights quantized once outside the timed region (reused across micro-steps)")
     p.add_argument("--whole-tiles", action="store_true",
                    help="linear calls without LLMQ_SHARE_TILES: every output tile is computed whole")
+    p.add_argument("--plain-copies", action="store_true",
+                   help="linear calls without LLMQ_SLAB_COPIES: transposed FP8 copies as plain transposed tensors")
     p.add_argument("--phase-stamps", action="store_true",
                    help="instead of the benchmark: cycle stamps of the phases of the GEMM tile kernel on two forward GEMMs")
     p.add_argument("--power-probe", action="store_true",
@@ -93,7 +95,8 @@ def run_step(states, prequantized_w, producer_absmax=False, extra_flags=None):
     SwiGLU, the previous GEMM's epilogue) has already delivered them; the scales of the last full step are
     used.  Reported as a side figure only.
     extra_flags: LLMQ_NO_TRANSPOSE for the side figure without transposed copies; by default LLMQ_SHARE_TILES (the
-    contractions may share a ragged last round of tiles among all compute units; --whole-tiles turns it off)."""
+    contractions may share a ragged last round of tiles among all compute units; --whole-tiles turns it off) and
+    LLMQ_SLAB_COPIES (transposed copies stored in slabs of 128 contraction bytes; --plain-copies turns it off)."""
     from paper_2512_15306_amd import llmq
     if extra_flags is None:
         extra_flags = DEFAULT_LINEAR_FLAGS["flags"]
@@ -123,15 +126,22 @@ def run_gemms_only(states, extra_flags=None):
                                    extra_flags | llmq.REUSE_X | llmq.REUSE_DY)
 
 
+def quantizer():
+    """The quantize call of the standalone legs: the transposed copy in the layout the step's linear calls use."""
+    from paper_2512_15306_amd import llmq
+    return llmq.llmq_quantize_fp8_slabs if DEFAULT_LINEAR_FLAGS["flags"] & llmq.SLAB_COPIES else llmq.llmq_quantize_fp8
+
+
 def run_quant_only(states):
     from paper_2512_15306_amd import llmq
+    quantize = quantizer()
     for s in states:
         llmq.llmq_amax(s.X, 0, s.ax, s.sx, s.aws)
-        llmq.llmq_quantize_fp8(s.X, s.sx, 0, s.view(0), s.view(1))
+        quantize(s.X, s.sx, 0, s.view(0), s.view(1))
         llmq.llmq_amax(s.W, 0, s.aw, s.sw, s.aws)
-        llmq.llmq_quantize_fp8(s.W, s.sw, 0, s.view(2), s.view(3))
+        quantize(s.W, s.sw, 0, s.view(2), s.view(3))
         llmq.llmq_amax(s.dY, 1, s.ad, s.sd, s.aws)
-        llmq.llmq_quantize_fp8(s.dY, s.sd, 1, s.view(4), s.view(5))
+        quantize(s.dY, s.sd, 1, s.view(4), s.view(5))
 
 
 def run_amax_only(states):
@@ -143,11 +153,11 @@ def run_amax_only(states):
 
 
 def run_quantize_kernel_only(states):
-    from paper_2512_15306_amd import llmq
+    quantize = quantizer()
     for s in states:
-        llmq.llmq_quantize_fp8(s.X, s.sx, 0, s.view(0), s.view(1))
-        llmq.llmq_quantize_fp8(s.W, s.sw, 0, s.view(2), s.view(3))
-        llmq.llmq_quantize_fp8(s.dY, s.sd, 1, s.view(4), s.view(5))
+        quantize(s.X, s.sx, 0, s.view(0), s.view(1))
+        quantize(s.W, s.sw, 0, s.view(2), s.view(3))
+        quantize(s.dY, s.sd, 1, s.view(4), s.view(5))
 
 
 def run_quantize_row_major_only(states):
@@ -449,7 +459,7 @@ def measure_config(cfg, args, dev, full):
     if args.prequantized_w:
         for s in states:
             llmq.llmq_amax(s.W, llmq.E4M3, s.aw, s.sw, s.aws)
-            llmq.llmq_quantize_fp8(s.W, s.sw, llmq.E4M3, s.view(2), s.view(3))
+            quantizer()(s.W, s.sw, llmq.E4M3, s.view(2), s.view(3))
     for _ in range(args.warmup):
         run_step(states, args.prequantized_w)
     torch.cuda.synchronize()
@@ -536,7 +546,7 @@ def main():
     if args.power_probe:
         print(json.dumps({"power_probe": power_probe(dev)}))
         return
-    DEFAULT_LINEAR_FLAGS["flags"] = 0 if args.whole_tiles else llmq.SHARE_TILES
+    DEFAULT_LINEAR_FLAGS["flags"] = (0 if args.whole_tiles else llmq.SHARE_TILES) | (0 if args.plain_copies else llmq.SLAB_COPIES)
     cfg = synth.CONFIGS[args.config or HEADLINE_CONFIG]
     peaks = measure_peaks(dev)
     r = measure_config(cfg, args, dev, full=True)
@@ -550,7 +560,7 @@ def main():
         "ms_per_step": rates["ms_per_step"], "wall_ms_per_step": round(r["wall"], 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "fp8", "data": "synthetic",
         "config": {"workload": workload_name(cfg, args.prequantized_w)},
-        "linear_flags": "LLMQ_JIT_* (scales found inside the calls)" + ("" if args.whole_tiles else " | LLMQ_SHARE_TILES"),
+        "linear_flags": "LLMQ_JIT_* (scales found inside the calls)" + ("" if args.whole_tiles else " | LLMQ_SHARE_TILES") + ("" if args.plain_copies else " | LLMQ_SLAB_COPIES"),
     }
     out.update({k: v for k, v in rates.items() if k not in ("ms_per_step", "step_tflops")})
     out.update({

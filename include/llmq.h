@@ -100,6 +100,15 @@ int llmq_amax_static(const void* x_bf16, size_t n, int fmt, float* d_amax, float
  */
 int llmq_quantize_fp8(const void* x_bf16, int64_t rows, int64_t cols, const float* d_scale, int fmt,
                       uint8_t* q, uint8_t* q_t, void* stream);
+/*
+ * The same with the transposed copy stored in slabs of 128 contraction bytes, the form the backward contractions
+ * read fastest (LLMQ_LAYOUT_SLABS of llmq_fp8_gemm, there with rows = cols of x and T = rows of x):
+ *   q_t byte of element (j, i) of the transposed tensor at (i / 128) * cols * 128 + j * 128 + i % 128.
+ * A 128 x 256 tile of x is then one contiguous 32 KB piece of q_t instead of 256 pieces of 128 bytes.  rows must
+ * be a multiple of 128 and cols a multiple of 256 (LLMQ_ERR_SHAPE otherwise); q_t must not be NULL.
+ */
+int llmq_quantize_fp8_slabs(const void* x_bf16, int64_t rows, int64_t cols, const float* d_scale, int fmt,
+                            uint8_t* q, uint8_t* q_t, void* stream);
 
 /*
  * The FP8 contraction that forward, dgrad and wgrad share (Section 3: FP8 GEMM is TN-only):
@@ -121,9 +130,14 @@ int llmq_fp8_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB,
                      void* c_bf16, int accumulate, float* d_amax_c, void* stream);
 
 /*
- * The same contraction with either operand optionally "T-major": stored [T, rows] (the contraction index
- * runs down the rows, the rows index is contiguous) instead of [rows, T].
- *   a_t_major != 0: A is [T,R];   b_t_major != 0: B is [T,C];   both 0: identical to llmq_fp8_gemm_tn.
+ * The same contraction with either operand in another layout than [rows, T] (LLMQ_LAYOUT_ROWS = 0):
+ *   LLMQ_LAYOUT_T_MAJOR = 1: stored [T, rows] (the contraction index runs down the rows, the rows index is
+ *     contiguous);
+ *   LLMQ_LAYOUT_SLABS = 2: stored K step by K step, byte (r, t) at (t / 128) * rows * 128 + r * 128 + t % 128
+ *     (T a multiple of 128, else LLMQ_ERR_SHAPE): the 128 contraction bytes of all rows for one K step are one
+ *     contiguous piece.  The arithmetic and its order are those of LLMQ_LAYOUT_ROWS: same result bytes.
+ *   a_t_major: layout of A ([T,R] when T-major);   b_t_major: layout of B;   both 0: identical to
+ *   llmq_fp8_gemm_tn.  Other values: LLMQ_ERR_FLAGS.
  * The paper keeps transposed FP8 copies of every quantized tensor because the FP8 GEMM it builds on only
  * takes contraction-contiguous operands, and names the extra transposes and buffers as the cost of FP8
  * (Section 3, kernel-fusion paragraph; Section 4 "Impact of FP8").  Here the tile kernel transposes a
@@ -137,6 +151,9 @@ int llmq_fp8_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB,
  * whenever both calls run the same kind of kernel, which is the case for what the linear calls below launch
  * on operands below 2 GiB.  Arguments otherwise as above.
  */
+#define LLMQ_LAYOUT_ROWS    0
+#define LLMQ_LAYOUT_T_MAJOR 1
+#define LLMQ_LAYOUT_SLABS   2
 int llmq_fp8_gemm(const uint8_t* A, int fmtA, int a_t_major, const uint8_t* B, int fmtB, int b_t_major,
                   int64_t R, int64_t C, int64_t T,
                   const float* d_scaleA, const float* d_scaleB,
@@ -228,6 +245,16 @@ int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t of
  * block's sequence of contractions it measured +1 % (32B- and 14B-class shapes).  Not together with LLMQ_NO_TRANSPOSE
  * (LLMQ_ERR_FLAGS); the workspace must hold llmq_fp8_linear_workspace_bytes_shared() bytes. */
 #define LLMQ_SHARE_TILES 128
+/* The transposed copies Xq_t, Wq_t, dYq_t are stored in slabs of 128 contraction bytes (LLMQ_LAYOUT_SLABS of the
+ * contraction that reads them) instead of as plain transposed tensors, wherever the quantizer can write them so
+ * (the untransposed tensor has a multiple of 128 rows and of 256 columns, less than 0x70000000 elements; other
+ * tensors keep the plain form): a 128 x 256 tile of a tensor then lands as one contiguous 32 KB piece of its
+ * transposed copy instead of 256 pieces of 128 bytes, and every K step of a backward contraction reads one
+ * contiguous piece per operand.  Results are the same bytes as without the flag.  Copies made under this flag can
+ * only be reused (LLMQ_REUSE_*) by calls that carry it too, and copies made without it (or by the producers that
+ * write FP8 directly, llmq_swiglu_fwd_fp8 and llmq_rmsnorm_apply_fp8) only by calls without it.  Not together with
+ * LLMQ_NO_TRANSPOSE (LLMQ_ERR_FLAGS). */
+#define LLMQ_SLAB_COPIES 256
 
 /*
  * Forward: Y[M,N] = X[M,K] W[N,K]^T in FP8 (E4M3 x E4M3), BF16 out.

@@ -67,7 +67,8 @@ llmq::GemmScratch pieces_of(const WsLayout& l, void* ws, int flags) {
 int check_linear(int64_t M, int64_t N, int64_t K, const void* ws, size_t ws_bytes, int flags) {
     if (!dim_ok(M) || !dim_ok(N) || !dim_ok(K)) return LLMQ_ERR_SHAPE;
     if (M * K >= kMaxElems || N * K >= kMaxElems || M * N >= kMaxElems) return LLMQ_ERR_SHAPE;
-    if (flags & ~(LLMQ_REUSE_X | LLMQ_REUSE_W | LLMQ_REUSE_DY | LLMQ_JIT_X | LLMQ_JIT_W | LLMQ_JIT_DY | LLMQ_NO_TRANSPOSE | LLMQ_SHARE_TILES)) return LLMQ_ERR_FLAGS;
+    if (flags & ~(LLMQ_REUSE_X | LLMQ_REUSE_W | LLMQ_REUSE_DY | LLMQ_JIT_X | LLMQ_JIT_W | LLMQ_JIT_DY | LLMQ_NO_TRANSPOSE | LLMQ_SHARE_TILES | LLMQ_SLAB_COPIES)) return LLMQ_ERR_FLAGS;
+    if ((flags & LLMQ_SLAB_COPIES) && (flags & LLMQ_NO_TRANSPOSE)) return LLMQ_ERR_FLAGS;       // no transposed copies to lay out
     // tiles are shared only by the kernels for contraction-contiguous operands
     if ((flags & LLMQ_SHARE_TILES) && (flags & LLMQ_NO_TRANSPOSE)) return LLMQ_ERR_FLAGS;
     // an operand is either reused or scaled just in time, not both
@@ -90,13 +91,20 @@ int check_swiglu_shape(int64_t M, int64_t I) {
 // found here: the first absmax stage runs over the tensor, the quantize kernel finishes the reduction and
 // stores the scale in d_scale (saving the launch of the second stage).
 int quantize_operand(const void* t, int64_t rows, int64_t cols, float* d_scale, int fmt, uint8_t* q, uint8_t* q_t,
-                     bool jit, unsigned* partial, unsigned* zero, hipStream_t s) {
-    if (!jit) return llmq::launch_quantize(t, rows, cols, d_scale, fmt, q, q_t, zero, s);
+                     bool jit, unsigned* partial, unsigned* zero, hipStream_t s, bool qt_slabs) {
+    if (!jit) return llmq::launch_quantize(t, rows, cols, d_scale, fmt, q, q_t, zero, s, qt_slabs);
     int n_partial = 0;
     int st = llmq::launch_amax_partial(t, (size_t)rows * (size_t)cols, partial, &n_partial, s, num_cus());
     if (st) return st;
     const llmq::ScaleSource src{nullptr, partial, n_partial, fmt == LLMQ_E4M3 ? 448.0f : 57344.0f, d_scale};
-    return llmq::launch_quantize_from(t, rows, cols, src, fmt, q, q_t, zero, s);
+    return llmq::launch_quantize_from(t, rows, cols, src, fmt, q, q_t, zero, s, qt_slabs);
+}
+
+// Under LLMQ_SLAB_COPIES the transposed copy of a tensor [rows, cols] is stored in slabs of 128 contraction bytes
+// whenever the quantizer's tile kernel takes the tensor (a pure function of the shape, so that the call that
+// writes a copy and the calls that reuse it agree); otherwise as the plain transposed tensor.
+bool slab_copy(int flags, int64_t rows, int64_t cols) {
+    return (flags & LLMQ_SLAB_COPIES) && llmq::quantize_can_write_slabs(rows, cols) && rows * cols < (int64_t)0x70000000;
 }
 
 }  // namespace
@@ -148,6 +156,17 @@ int llmq_quantize_fp8(const void* x_bf16, int64_t rows, int64_t cols, const floa
     return llmq::launch_quantize(x_bf16, rows, cols, d_scale, fmt, q, q_t, nullptr, static_cast<hipStream_t>(stream));
 }
 
+int llmq_quantize_fp8_slabs(const void* x_bf16, int64_t rows, int64_t cols, const float* d_scale, int fmt,
+                            uint8_t* q, uint8_t* q_t, void* stream) {
+    if (!x_bf16 || !d_scale || !q || !q_t) return LLMQ_ERR_NULL;
+    if (!dim_ok(rows) || !dim_ok(cols) || rows * cols >= kMaxElems) return LLMQ_ERR_SHAPE;
+    if (rows % 128 != 0 || cols % 256 != 0) return LLMQ_ERR_SHAPE;
+    if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
+    if (!aligned(x_bf16, 16) || !aligned(q, 16) || !aligned(q_t, 16) || !aligned(d_scale, 4)) return LLMQ_ERR_ALIGN;
+    if (!llmq::quantize_can_write_slabs(rows, cols)) return LLMQ_ERR_SHAPE;
+    return llmq::launch_quantize(x_bf16, rows, cols, d_scale, fmt, q, q_t, nullptr, static_cast<hipStream_t>(stream), true);
+}
+
 int llmq_fp8_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64_t R, int64_t C, int64_t T,
                      const float* d_scaleA, const float* d_scaleB, void* c_bf16, int accumulate,
                      float* d_amax_c, void* stream) {
@@ -185,8 +204,11 @@ int llmq_fp8_gemm_with_scratch(const uint8_t* A, int fmtA, int a_t_major, const 
     if (!aligned(A, 16) || !aligned(B, 16) || !aligned(c_bf16, 16) || !aligned(d_scaleA, 4) ||
         !aligned(d_scaleB, 4) || !aligned(d_amax_c, 4) || !aligned(scratch, 256))
         return LLMQ_ERR_ALIGN;
+    // operand layouts: 0 rows, 1 T-major, 2 slabs of 128 contraction bytes
+    if (a_t_major < 0 || a_t_major > LLMQ_LAYOUT_SLABS || b_t_major < 0 || b_t_major > LLMQ_LAYOUT_SLABS) return LLMQ_ERR_FLAGS;
+    if ((a_t_major == LLMQ_LAYOUT_SLABS || b_t_major == LLMQ_LAYOUT_SLABS) && T % 128 != 0) return LLMQ_ERR_SHAPE;
     const llmq::GemmScratch sc{scratch ? static_cast<float*>(scratch) : nullptr, scratch ? scratch_bytes : 0};
-    return llmq::launch_gemm_fp8(A, fmtA, a_t_major != 0, B, fmtB, b_t_major != 0, R, C, T, d_scaleA, d_scaleB, c_bf16,
+    return llmq::launch_gemm_fp8(A, fmtA, a_t_major, B, fmtB, b_t_major, R, C, T, d_scaleA, d_scaleB, c_bf16,
                                  accumulate, d_amax_c, false, static_cast<hipStream_t>(stream), num_cus(), sc);
 }
 
@@ -243,8 +265,8 @@ int llmq_fp8_linear_fwd(const void* X, const void* W, int64_t M, int64_t N, int6
     unsigned* part = reinterpret_cast<unsigned*>(base + l.part);
     constexpr size_t kPartWords = 256 * ((llmq::kAmaxMaxPartials * sizeof(unsigned) + 255) / 256) / sizeof(unsigned);
     const bool nt = (flags & LLMQ_NO_TRANSPOSE) != 0;
-    if (qx && (st = quantize_operand(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, nt ? nullptr : base + l.xqt, (flags & LLMQ_JIT_X) != 0, part, zero, s))) return st;
-    if (qw && (st = quantize_operand(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, nt ? nullptr : base + l.wqt, (flags & LLMQ_JIT_W) != 0, part + kPartWords, qx ? nullptr : zero, s))) return st;
+    if (qx && (st = quantize_operand(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, nt ? nullptr : base + l.xqt, (flags & LLMQ_JIT_X) != 0, part, zero, s, slab_copy(flags, M, K)))) return st;
+    if (qw && (st = quantize_operand(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, nt ? nullptr : base + l.wqt, (flags & LLMQ_JIT_W) != 0, part + kPartWords, qx ? nullptr : zero, s, slab_copy(flags, N, K)))) return st;
     return llmq::launch_gemm_tn(base + l.xq, LLMQ_E4M3, base + l.wq, LLMQ_E4M3, M, N, K, d_scale_x, d_scale_w,
                                 Y, 0, d_amax_y, zeroed, s, num_cus(), pieces_of(l, ws, flags));
 }
@@ -269,10 +291,11 @@ int llmq_fp8_linear_dgrad(const void* dY, const void* W, int64_t M, int64_t N, i
     unsigned* part = reinterpret_cast<unsigned*>(base + l.part);
     constexpr size_t kPartWords = 256 * ((llmq::kAmaxMaxPartials * sizeof(unsigned) + 255) / 256) / sizeof(unsigned);
     const bool nt = (flags & LLMQ_NO_TRANSPOSE) != 0;
-    if (qd && (st = quantize_operand(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, nt ? nullptr : base + l.dyqt, (flags & LLMQ_JIT_DY) != 0, part + 2 * kPartWords, zero, s))) return st;
-    if (qw && (st = quantize_operand(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, nt ? nullptr : base + l.wqt, (flags & LLMQ_JIT_W) != 0, part + kPartWords, qd ? nullptr : zero, s))) return st;
+    if (qd && (st = quantize_operand(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, nt ? nullptr : base + l.dyqt, (flags & LLMQ_JIT_DY) != 0, part + 2 * kPartWords, zero, s, slab_copy(flags, M, N)))) return st;
+    if (qw && (st = quantize_operand(W, N, K, d_scale_w, LLMQ_E4M3, base + l.wq, nt ? nullptr : base + l.wqt, (flags & LLMQ_JIT_W) != 0, part + kPartWords, qd ? nullptr : zero, s, slab_copy(flags, N, K)))) return st;
     // dX[m,k] = sum_n dYq[m,n] * Wq_t[k,n] = sum_n dYq[m,n] * Wq[n,k]
-    return llmq::launch_gemm_fp8(base + l.dyq, fmt_dy, false, nt ? base + l.wq : base + l.wqt, LLMQ_E4M3, nt, M, K, N,
+    const int w_layout = nt ? llmq::kLayoutTMajor : slab_copy(flags, N, K) ? llmq::kLayoutSlabs : llmq::kLayoutRows;
+    return llmq::launch_gemm_fp8(base + l.dyq, fmt_dy, llmq::kLayoutRows, nt ? base + l.wq : base + l.wqt, LLMQ_E4M3, w_layout, M, K, N,
                                  d_scale_dy, d_scale_w, dX, 0, d_amax_dx, zeroed, s, num_cus(), pieces_of(l, ws, flags));
 }
 
@@ -294,10 +317,12 @@ int llmq_fp8_linear_wgrad(const void* dY, const void* X, int64_t M, int64_t N, i
     unsigned* part = reinterpret_cast<unsigned*>(base + l.part);
     constexpr size_t kPartWords = 256 * ((llmq::kAmaxMaxPartials * sizeof(unsigned) + 255) / 256) / sizeof(unsigned);
     const bool nt = (flags & LLMQ_NO_TRANSPOSE) != 0;
-    if (qd && (st = quantize_operand(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, nt ? nullptr : base + l.dyqt, (flags & LLMQ_JIT_DY) != 0, part + 2 * kPartWords, nullptr, s))) return st;
-    if (qx && (st = quantize_operand(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, nt ? nullptr : base + l.xqt, (flags & LLMQ_JIT_X) != 0, part, nullptr, s))) return st;
+    if (qd && (st = quantize_operand(dY, M, N, d_scale_dy, fmt_dy, base + l.dyq, nt ? nullptr : base + l.dyqt, (flags & LLMQ_JIT_DY) != 0, part + 2 * kPartWords, nullptr, s, slab_copy(flags, M, N)))) return st;
+    if (qx && (st = quantize_operand(X, M, K, d_scale_x, LLMQ_E4M3, base + l.xq, nt ? nullptr : base + l.xqt, (flags & LLMQ_JIT_X) != 0, part, nullptr, s, slab_copy(flags, M, K)))) return st;
     // dW[n,k] = sum_m dYq_t[n,m] * Xq_t[k,m] = sum_m dYq[m,n] * Xq[m,k]
-    return llmq::launch_gemm_fp8(nt ? base + l.dyq : base + l.dyqt, fmt_dy, nt, nt ? base + l.xq : base + l.xqt, LLMQ_E4M3, nt,
+    const int dy_layout = nt ? llmq::kLayoutTMajor : slab_copy(flags, M, N) ? llmq::kLayoutSlabs : llmq::kLayoutRows;
+    const int x_layout = nt ? llmq::kLayoutTMajor : slab_copy(flags, M, K) ? llmq::kLayoutSlabs : llmq::kLayoutRows;
+    return llmq::launch_gemm_fp8(nt ? base + l.dyq : base + l.dyqt, fmt_dy, dy_layout, nt ? base + l.xq : base + l.xqt, LLMQ_E4M3, x_layout,
                                  N, K, M, d_scale_dy, d_scale_x, dW, accumulate, nullptr, false, s, num_cus(), pieces_of(l, ws, flags));
 }
 

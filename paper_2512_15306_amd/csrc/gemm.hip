@@ -4,12 +4,12 @@
 
 namespace llmq {
 
-void launch_gemm_generic(const uint8_t* A, int fmtA, bool ta, const uint8_t* B, int fmtB, bool tb, int64_t R, int64_t C,
+void launch_gemm_generic(const uint8_t* A, int fmtA, int layout_a, const uint8_t* B, int fmtB, int layout_b, int64_t R, int64_t C,
                          int64_t T, const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
                          hipStream_t stream);
 
 // ---- generic kernel: one wavefront per 16x16 outputs, v_mfma_f32_16x16x128_f8f6f4, guarded loads.
-// ta / tb: the operand is T-major ([T, R] or [T, Cn]); its bytes are then gathered one by one.
+// ta / tb: the operand's OperandLayout; the bytes of a T-major operand ([T, R] or [T, Cn]) are gathered one by one.
 template <int FA, int FB>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ C,
@@ -25,6 +25,11 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
     auto load32 = [&](const uint8_t* base, bool ok, int64_t row, int64_t k, int tmajor, int64_t ld) -> v8i {
         v8i v = {0, 0, 0, 0, 0, 0, 0, 0};
         if (!ok || k >= T) return v;
+        if (tmajor == kLayoutSlabs) {                 // 32 contiguous bytes of the row's K step (T % 128 == 0)
+            const uint8_t* p = base + (k >> 7) * (ld * 128) + row * 128 + (k & 127);
+            v4i lo = *reinterpret_cast<const v4i*>(p), hi = *reinterpret_cast<const v4i*>(p + 16);
+            return v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        }
         if (tmajor) {
             for (int w = 0; w < 8; ++w) {
                 unsigned word = 0;
@@ -140,8 +145,11 @@ TileChoice choose_tile(int64_t R, int64_t C, int64_t T, int num_cus, size_t scra
 template <int FA, int FB>
 static void launch_one(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
                        const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
-                       hipStream_t stream, int num_cus, GemmScratch scratch) {
-    if (launch_chosen_tile<FA, FB, false, false>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus, scratch)) return;
+                       hipStream_t stream, int num_cus, GemmScratch scratch, bool slabs_a = false, bool slabs_b = false) {
+    // (an operand in slabs is addressed with 32-bit offsets from its first tile row, 0x7FFFFF00 being out of range)
+    const int64_t lim = 0x7FFFFF00ll - ((int64_t)1 << 24);
+    const bool fits = (!slabs_a || (T + 256) * R < lim) && (!slabs_b || (T + 256) * C < lim);
+    if (fits && launch_chosen_tile<FA, FB, false, false>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus, scratch, slabs_a, slabs_b)) return;
     if constexpr (FA == kFmtBf16) {
         const int64_t n = R * C;
         int64_t blocks = (n + 255) / 256;
@@ -150,11 +158,12 @@ static void launch_one(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C,
                            reinterpret_cast<const uint16_t*>(A), reinterpret_cast<const uint16_t*>(B),
                            reinterpret_cast<uint16_t*>(c), R, C, T / 2, accumulate);
     } else {
-        launch_gemm_generic(A, FA, false, B, FB, false, R, C, T, sA, sB, c, accumulate, amax, stream);
+        launch_gemm_generic(A, FA, slabs_a ? kLayoutSlabs : kLayoutRows, B, FB, slabs_b ? kLayoutSlabs : kLayoutRows, R, C, T, sA, sB, c,
+                            accumulate, amax, stream);
     }
 }
 
-void launch_gemm_generic(const uint8_t* A, int fmtA, bool ta, const uint8_t* B, int fmtB, bool tb, int64_t R, int64_t C,
+void launch_gemm_generic(const uint8_t* A, int fmtA, int ta, const uint8_t* B, int fmtB, int tb, int64_t R, int64_t C,
                          int64_t T, const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
                          hipStream_t stream) {
     dim3 grid((unsigned)((C + 31) / 32), (unsigned)((R + 31) / 32));
@@ -171,13 +180,14 @@ void launch_gemm_amax_reset(unsigned* amax, hipStream_t stream) {
 
 int launch_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64_t R, int64_t C,
                    int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16,
-                   int accumulate, float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus, GemmScratch scratch) {
+                   int accumulate, float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus, GemmScratch scratch,
+                   bool slabs_a, bool slabs_b) {
     unsigned* amax = reinterpret_cast<unsigned*>(d_amax_c);
     if (amax && !amax_is_zeroed) hipLaunchKernelGGL(gemm_amax_reset_kernel, dim3(1), dim3(64), 0, stream, amax);
-    if (fmtA == 0 && fmtB == 0) launch_one<0, 0>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus, scratch);
-    else if (fmtA == 1 && fmtB == 0) launch_one<1, 0>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus, scratch);
-    else if (fmtA == 0 && fmtB == 1) launch_one<0, 1>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus, scratch);
-    else launch_one<1, 1>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus, scratch);
+    if (fmtA == 0 && fmtB == 0) launch_one<0, 0>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus, scratch, slabs_a, slabs_b);
+    else if (fmtA == 1 && fmtB == 0) launch_one<1, 0>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus, scratch, slabs_a, slabs_b);
+    else if (fmtA == 0 && fmtB == 1) launch_one<0, 1>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus, scratch, slabs_a, slabs_b);
+    else launch_one<1, 1>(A, B, R, C, T, d_scaleA, d_scaleB, c_bf16, accumulate, amax, stream, num_cus, scratch, slabs_a, slabs_b);
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 
@@ -221,8 +231,8 @@ int launch_gemm_phase_stamps(const uint8_t* A, const uint8_t* B, int64_t R, int6
     hipLaunchKernelGGL(gemm_amax_reset_kernel, dim3(1), dim3(64), 0, stream, amax);
     auto launch = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, dim3(grid), dim3(kGemmThreads), 0, stream, A, B, reinterpret_cast<uint16_t*>(c_bf16),
-                           (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c, touch_ahead(), band, next_stride, (int)R, (int)C,
-                           share_a, share_b, plan);
+                           (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c, touch_ahead(), band, next_stride, (int)T, (int)T,
+                           BK, BK, share_a, share_b, plan);
     };
     if (ieee_maximum) launch(gemm_tile_kernel<0, 0, 4, 4, false, GemmPhaseTuning<true>>);
     else launch(gemm_tile_kernel<0, 0, 4, 4, false, GemmPhaseTuning<false>>);

@@ -223,6 +223,13 @@ __device__ inline void mma_quadrant(BlockAcc<MI, MJ>& acc, const v8i (&a)[HI], c
 // the same with 4 or 8 cycles per read (the LDS is a quarter or half busy), within 1 %.
 __device__ constexpr int row_swizzle(int row) { return (((row >> 1) & 3) << 1) | ((row >> 3) & 1); }
 
+// How an operand [rows, T] may sit in memory (OperandLayout of the launchers):
+//   rows    : row r at r T, its T contraction bytes contiguous;
+//   t_major : the transposed tensor [T, rows] (see TMAJOR below);
+//   slabs   : K step by K step, byte (r, t) at (t / 128) rows 128 + r 128 + t % 128: each K step of all rows is one
+//             contiguous piece (T a multiple of 128).  The kernel reads it like `rows` with a row pitch of 128 bytes
+//             and rows x 128 bytes from one K step to the next; the tile kernel of the quantizer writes its transposed
+//             copy that way, a whole tile's transposed bytes as one contiguous 32 KB piece.
 // How one operand slab sits in memory and in LDS, and how its MFMA fragments are read.
 //   TMAJOR = false: the operand is [rows, T], a slab is 64 NX rows of 128 B; LDS keeps the rows, 128 B
 //     each, the 16-byte chunk index XOR-ed with row_swizzle(row); a lane reads the 32 contiguous
@@ -262,8 +269,11 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ C,
     int Cn, int T, const float* __restrict__ d_sA, const float* __restrict__ d_sB,
     unsigned* __restrict__ amax_bits, int tiles_r, int tiles_c, int touch_ahead, int band_rows, int next_stride,
-    int ldA, int ldB, int share_a, int share_b, const SplitPlan plan) {
+    int ldA, int ldB, int ks_a, int ks_b, int share_a, int share_b, const SplitPlan plan) {
     static_assert(!(TA || TB) || (FA != kFmtBf16 && FB != kFmtBf16), "the transposing reads move single bytes");
+    // Bytes from one K step of an operand to the next: 128 rows of a T-major operand, else what the host says
+    // (128 for rows of T contiguous bytes; rows x 128 when the operand is stored slab by slab, see OperandLayout).
+    const int ksA = TA ? BK * ldA : ks_a, ksB = TB ? BK * ldB : ks_b;
     constexpr int BM = 64 * NI, BN = 64 * NJ;
     typedef SlabShape<NI, TA> SA;
     typedef SlabShape<NJ, TB> SB;
@@ -334,12 +344,13 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     // rows (64 NX bytes each); wave w moves slab rows [32 w, 32 w + 32), again 2 NX instructions, whose
     // lane pattern repeats every kPeriod instructions (kPeriodRows slab rows).
     const __amdgpu_buffer_rsrc_t rsA = TA ? make_rsrc(A + (size_t)tr * BM, (unsigned)((size_t)T * ldA - (size_t)tr * BM))
-                                          : make_rsrc(A + (size_t)tr * BM * T, (unsigned)((size_t)BM * T));
+                                          : make_rsrc(A + (size_t)tr * BM * ldA, (unsigned)((size_t)(T / BK - 1) * ksA + (size_t)(BM - 1) * ldA + BK));
     const __amdgpu_buffer_rsrc_t rsB = TB ? make_rsrc(B + (size_t)tc * BN, (unsigned)((size_t)T * ldB - (size_t)tc * BN))
-                                          : make_rsrc(B + (size_t)tc * BN * T, (unsigned)((size_t)BN * T));
+                                          : make_rsrc(B + (size_t)tc * BN * ldB, (unsigned)((size_t)(T / BK - 1) * ksB + (size_t)(BN - 1) * ldB + BK));
     const int ld_row = lane >> 3;                                   // row inside the group of 8
-    const int ld_voff0 = ld_row * T + (((lane & 7) ^ row_swizzle(ld_row)) << 4);
-    const int ld_voff1 = ld_row * T + (((lane & 7) ^ row_swizzle(8 + ld_row)) << 4);
+    auto rows_voff = [&](int m, int ld) {                           // rows 8 m + ld_row of a row-wise operand, `ld` bytes apart
+        return ld_row * ld + (((lane & 7) ^ row_swizzle(8 * m + ld_row)) << 4);
+    };
     auto tmajor_voff = [&](auto shape, int m, int ld) {             // pattern m of a T-major operand
         typedef decltype(shape) S;
         const int unit = 64 * m + lane, row = unit / S::kUnits, col = unit % S::kUnits;
@@ -348,35 +359,35 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     int ld_voffA[3], ld_voffB[3];
 #pragma unroll
     for (int m = 0; m < 3; ++m) {
-        ld_voffA[m] = TA ? (m < SA::kPeriod ? tmajor_voff(SA{}, m, ldA) : 0) : (m & 1) ? ld_voff1 : ld_voff0;
-        ld_voffB[m] = TB ? (m < SB::kPeriod ? tmajor_voff(SB{}, m, ldB) : 0) : (m & 1) ? ld_voff1 : ld_voff0;
+        ld_voffA[m] = TA ? (m < SA::kPeriod ? tmajor_voff(SA{}, m, ldA) : 0) : rows_voff(m & 1, ldA);
+        ld_voffB[m] = TB ? (m < SB::kPeriod ? tmajor_voff(SB{}, m, ldB) : 0) : rows_voff(m & 1, ldB);
     }
-    const int ld_soffA = TA ? wave * 32 * ldA : wave * 16 * NI * T, ld_soffB = TB ? wave * 32 * ldB : wave * 16 * NJ * T;
+    const int ld_soffA = TA ? wave * 32 * ldA : wave * 16 * NI * ldA, ld_soffB = TB ? wave * 32 * ldB : wave * 16 * NJ * ldB;
     // The direct-to-LDS loads of one slab pair: pieces 0 .. 2 NI - 1 fill the wave's share of the A slab, the
-    // next 2 NJ that of the B slab.  k0: first contraction index of the slab, or a negative value for "no slab"
+    // next 2 NJ that of the B slab.  step: K step of the slab, or a negative value for "no slab"
     // (nothing is fetched).
-    auto load_base = [&](int k0, int& baseA, int& baseB) {
-        baseA = k0 < 0 ? kOutOfRange : ld_soffA + (TA ? k0 * ldA : k0);
-        baseB = k0 < 0 ? kOutOfRange : ld_soffB + (TB ? k0 * ldB : k0);
+    auto load_base = [&](int step, int& baseA, int& baseB) {
+        baseA = step < 0 ? kOutOfRange : ld_soffA + step * ksA;
+        baseB = step < 0 ? kOutOfRange : ld_soffB + step * ksB;
     };
     auto issue_load = [&](uint8_t* slabA, uint8_t* slabB, int baseA, int baseB, auto piece) {
         constexpr int p = decltype(piece)::value;
         if constexpr (p < 2 * NI) {
             constexpr int j = p;
             const int voff = TA ? ld_voffA[j % SA::kPeriod] : ld_voffA[j & 1];
-            const int soff = TA ? (j / SA::kPeriod) * SA::kPeriodRows * ldA : j * 8 * T;
+            const int soff = TA ? (j / SA::kPeriod) * SA::kPeriodRows * ldA : j * 8 * ldA;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_void*)(slabA + wave * 16 * NI * BK + j * 8 * BK), 16, voff, baseA + soff, 0, 0);
         } else {
             constexpr int j = p - 2 * NI;
             const int voff = TB ? ld_voffB[j % SB::kPeriod] : ld_voffB[j & 1];
-            const int soff = TB ? (j / SB::kPeriod) * SB::kPeriodRows * ldB : j * 8 * T;
+            const int soff = TB ? (j / SB::kPeriod) * SB::kPeriodRows * ldB : j * 8 * ldB;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_void*)(slabB + wave * 16 * NJ * BK + j * 8 * BK), 16, voff, baseB + soff, 0, 0);
         }
     };
     constexpr int kLoadsPerStep = 2 * (NI + NJ);
-    auto issue_loads = [&](uint8_t* slabA, uint8_t* slabB, int k0) {
+    auto issue_loads = [&](uint8_t* slabA, uint8_t* slabB, int step) {
         int baseA, baseB;
-        load_base(k0, baseA, baseB);
+        load_base(step, baseA, baseB);
         static_for<kLoadsPerStep>([&](auto piece) { issue_load(slabA, slabB, baseA, baseB, piece); });
     };
     // The wave tile as 16 x 16 blocks: MI x MJ of them, handled in halves of HI block rows / HJ block columns.
@@ -459,9 +470,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
     const int per_wave_a = (kLinesOfA + share_a * 4 - 1) / (share_a * 4), per_wave_b = (kLinesOfB + share_b * 4 - 1) / (share_b * 4);
     const int touch_lineA = ((tc % share_a) * 4 + wave) * per_wave_a + lane, touch_lineB = ((tr % share_b) * 4 + wave) * per_wave_b + lane;
     const int touch_voffA = (lane >= per_wave_a || touch_lineA >= kLinesOfA) ? kOutOfRange
-                            : TA ? (touch_lineA / SA::kLines) * ldA + (touch_lineA % SA::kLines) * 128 : touch_lineA * T;
+                            : TA ? (touch_lineA / SA::kLines) * ldA + (touch_lineA % SA::kLines) * 128 : touch_lineA * ldA;
     const int touch_voffB = (lane >= per_wave_b || touch_lineB >= kLinesOfB) ? kOutOfRange
-                            : TB ? (touch_lineB / SB::kLines) * ldB + (touch_lineB % SB::kLines) * 128 : touch_lineB * T;
+                            : TB ? (touch_lineB / SB::kLines) * ldB + (touch_lineB % SB::kLines) * 128 : touch_lineB * ldB;
     int touchA[2] = {0, 0}, touchB[2] = {0, 0};   // results are only kept so that the loads stay tracked
     int touch_sink = 0;
 
@@ -516,7 +527,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
         lds_barrier();
         __builtin_amdgcn_sched_barrier(0);
         int baseA, baseB;
-        load_base(kt + 2 < nk ? (kb + kt + 2) * BK : -1, baseA, baseB);
+        load_base(kt + 2 < nk ? kb + kt + 2 : -1, baseA, baseB);
         mma_quadrant<FA, FB, Y0, HJ, true>(acc, aY, bH, [&](auto m) {
             readsB_of_slot(nxtB, IntTag<0>{}, bL, m);     // past the last slab this reads bytes that are never used
             loads_of_slot(curA, curB, baseA, baseB, m);
@@ -529,20 +540,20 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
             const int kp = kt + 2 + touch_ahead;
             const bool on = touch_ahead > 0 && kp < nk;
             touch_sink ^= touchA[parity] ^ touchB[parity];          // issued two steps ago: long landed
-            touchA[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, on ? (TA ? (kb + kp) * BK * ldA : (kb + kp) * BK) : kOutOfRange, 0);
-            touchB[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, on ? (TB ? (kb + kp) * BK * ldB : (kb + kp) * BK) : kOutOfRange, 0);
+            touchA[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, on ? (kb + kp) * ksA : kOutOfRange, 0);
+            touchB[parity] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, on ? (kb + kp) * ksB : kOutOfRange, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
     if constexpr (!fixup) {
     // both stages are requested at once; only the first has to have landed before the first fragments
-    issue_loads(ldsA0, ldsB0, kb * BK);
-    issue_loads(ldsA1, ldsB1, nk > 1 ? (kb + 1) * BK : -1);
+    issue_loads(ldsA0, ldsB0, kb);
+    issue_loads(ldsA1, ldsB1, nk > 1 ? kb + 1 : -1);
     if constexpr (kTouch) {                       // keep "two touch loads are the newest" true from the start
         const bool on = touch_ahead > 0 && 2 < nk;
-        touchA[1] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, on ? (TA ? (kb + 2) * BK * ldA : (kb + 2) * BK) : kOutOfRange, 0);
-        touchB[1] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, on ? (TB ? (kb + 2) * BK * ldB : (kb + 2) * BK) : kOutOfRange, 0);
+        touchA[1] = __builtin_amdgcn_raw_buffer_load_b32(rsA, touch_voffA, on ? (kb + 2) * ksA : kOutOfRange, 0);
+        touchB[1] = __builtin_amdgcn_raw_buffer_load_b32(rsB, touch_voffB, on ? (kb + 2) * ksB : kOutOfRange, 0);
     }
     wait_vmcnt<kLoadsPerStep + (kTouch ? 2 : 0)>();
     lds_barrier();
@@ -624,10 +635,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
                 next_touch[0] = *reinterpret_cast<const int*>(na);
                 if (SA::kLines > 1) next_touch[1] = *reinterpret_cast<const int*>(na + 128);
             } else {
-                const uint8_t* na = A + ((size_t)ntr * BM + wave * (BM / 4) + lane) * T;
+                const uint8_t* na = A + ((size_t)ntr * BM + wave * (BM / 4) + lane) * ldA;
                 if (lane < BM / 4) {
                     next_touch[0] = *reinterpret_cast<const int*>(na);
-                    next_touch[1] = *reinterpret_cast<const int*>(na + BK);
+                    next_touch[1] = *reinterpret_cast<const int*>(na + ksA);
                 }
             }
             if constexpr (TB) {
@@ -635,10 +646,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
                 next_touch[2] = *reinterpret_cast<const int*>(nb);
                 if (SB::kLines > 1) next_touch[3] = *reinterpret_cast<const int*>(nb + 128);
             } else {
-                const uint8_t* nb = B + ((size_t)ntc * BN + wave * (BN / 4) + lane) * T;
+                const uint8_t* nb = B + ((size_t)ntc * BN + wave * (BN / 4) + lane) * ldB;
                 if (lane < BN / 4) {
                     next_touch[2] = *reinterpret_cast<const int*>(nb);
-                    next_touch[3] = *reinterpret_cast<const int*>(nb + BK);
+                    next_touch[3] = *reinterpret_cast<const int*>(nb + ksB);
                 }
             }
         }
@@ -896,7 +907,10 @@ inline SplitChoice choose_split(int nt, int nk, int slots, int ni, int nj, size_
 template <int FA, int FB, int NI, int NJ, bool TA = false, bool TB = false>
 static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C, int64_t T,
                         const float* sA, const float* sB, void* c, int accumulate, unsigned* amax,
-                        hipStream_t stream, int num_cus, GemmScratch scratch) {
+                        hipStream_t stream, int num_cus, GemmScratch scratch, bool slabs_a, bool slabs_b) {
+    // row pitch and K-step stride of the operands (OperandLayout)
+    const int ldA = TA ? (int)R : slabs_a ? BK : (int)T, ldB = TB ? (int)C : slabs_b ? BK : (int)T;
+    const int ksA = slabs_a ? (int)(R * BK) : BK, ksB = slabs_b ? (int)(C * BK) : BK;
     const int tiles_r = (int)(R / (64 * NI)), tiles_c = (int)(C / (64 * NJ));
     const int nt = tiles_r * tiles_c;
     const int touch = (NI == 2 && NJ == 2) ? touch_ahead_pair() : touch_ahead();
@@ -924,7 +938,7 @@ static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C
     auto launch = [&](auto kernel, int blocks, const SplitPlan& pl) {
         hipLaunchKernelGGL(kernel, dim3(blocks), dim3(kGemmThreads), 0, stream,
                            A, B, reinterpret_cast<uint16_t*>(c), (int)C, (int)T, sA, sB, amax, tiles_r, tiles_c,
-                           touch, band, next_stride, (int)R, (int)C, share_a, share_b, pl);
+                           touch, band, next_stride, ldA, ldB, ksA, ksB, share_a, share_b, pl);
     };
     // The pieces first (all CUs start and end them together), their sums next, the whole rounds last.
     if constexpr (split_supported(NI, NJ) && FA != kFmtBf16 && !TA && !TB) {
@@ -945,13 +959,13 @@ static void launch_tile(const uint8_t* A, const uint8_t* B, int64_t R, int64_t C
 // compile side by side); everybody else sees the declarations below.
 #define LLMQ_TILE_LAUNCH_PARAMS                                                                                   \
     const uint8_t *A, const uint8_t *B, int64_t R, int64_t C, int64_t T, const float *sA, const float *sB, void *c, \
-        int accumulate, unsigned *amax, hipStream_t stream, int num_cus, GemmScratch scratch
+        int accumulate, unsigned *amax, hipStream_t stream, int num_cus, GemmScratch scratch, bool slabs_a, bool slabs_b
 template <int FA, int FB, bool TA, bool TB>
 bool launch_chosen_tile(LLMQ_TILE_LAUNCH_PARAMS) {
     const TileChoice tc = choose_tile(R, C, T, num_cus, (scratch.ptr && !TA && !TB && FA != kFmtBf16) ? scratch.bytes : 0);
 #define LLMQ_TILE_CASE(I, J)                                                                              \
     case I * 8 + J:                                                                                       \
-        launch_tile<FA, FB, I, J, TA, TB>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus, scratch); \
+        launch_tile<FA, FB, I, J, TA, TB>(A, B, R, C, T, sA, sB, c, accumulate, amax, stream, num_cus, scratch, slabs_a, slabs_b); \
         return true;
     switch (tc.ni * 8 + tc.nj) {
         LLMQ_TILE_CASE(4, 4) LLMQ_TILE_CASE(4, 3) LLMQ_TILE_CASE(4, 2)

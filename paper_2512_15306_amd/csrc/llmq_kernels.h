@@ -32,8 +32,12 @@ int launch_gemm_bf16_tn(const void* A, const void* B, int64_t R, int64_t C, int6
 int launch_scale_from_amax(const float* d_amax, int fmt, float* d_scale, hipStream_t stream);
 // zero_word: if not NULL, one 32-bit word the kernel also clears (the absmax accumulator of the GEMM
 // that follows in the same call, which saves a launch).
+// qt_slabs: the transposed copy is written in slabs of 128 contraction bytes (kLayoutSlabs of the contraction that
+// reads it: [cols, rows] with rows the contraction index), which only the tile kernel does: ask
+// quantize_can_write_slabs() first (else -2).
 int launch_quantize(const void* x, int64_t rows, int64_t cols, const float* d_scale, int fmt,
-                    uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream);
+                    uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream, bool qt_slabs = false);
+bool quantize_can_write_slabs(int64_t rows, int64_t cols);
 // Where a quantizing kernel gets its scale from: a scale on the device, or the per-workgroup results of
 // the first stage of an absmax reduction over the same tensor, in which case every workgroup finishes the
 // reduction itself (at most 1024 words) and the first one also stores the scale: the second-stage launch of
@@ -48,7 +52,7 @@ struct ScaleSource {
 
 // The same with the scale taken from a ScaleSource (a given scale, or the first-stage results of an absmax).
 int launch_quantize_from(const void* x, int64_t rows, int64_t cols, const ScaleSource& src, int fmt,
-                         uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream);
+                         uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream, bool qt_slabs = false);
 // First stage of the absmax only: one BF16 magnitude pattern per workgroup into partial; returns the number
 // of workgroups (<= kAmaxMaxPartials) through n_partial.
 int launch_amax_partial(const void* x, size_t n, unsigned* partial, int* n_partial, hipStream_t stream, int num_cus);
@@ -60,10 +64,15 @@ struct GemmScratch {
 };
 // What a contraction of this shape would use of it (0: nothing).
 size_t gemm_scratch_bytes(int64_t R, int64_t C, int64_t T, int num_cus);
+// How an operand [rows, T] of a contraction sits in memory: its rows of T contiguous bytes one after the other;
+// the transposed tensor [T, rows]; or K step by K step ("slabs": byte (r, t) at (t / 128) rows 128 + r 128 + t % 128,
+// T a multiple of 128), which is how the quantizer's tile kernel can write a transposed copy in contiguous pieces.
+enum OperandLayout { kLayoutRows = 0, kLayoutTMajor = 1, kLayoutSlabs = 2 };
+// Both operands kLayoutRows or kLayoutSlabs (slabs_a, slabs_b).
 int launch_gemm_tn(const uint8_t* A, int fmtA, const uint8_t* B, int fmtB, int64_t R, int64_t C,
                    int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16,
                    int accumulate, float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus,
-                   GemmScratch scratch);
+                   GemmScratch scratch, bool slabs_a = false, bool slabs_b = false);
 
 // The 256 x 256 tile kernel with phase stamps: 16 words of 64 bits per workgroup id, gemm_phase_stamp_blocks() ids.
 int gemm_phase_stamp_blocks(int64_t R, int64_t C);
@@ -71,9 +80,9 @@ int launch_gemm_phase_stamps(const uint8_t* A, const uint8_t* B, int64_t R, int6
                              const float* sB, void* c_bf16, float* d_amax_c, long long* stamps, int ieee_maximum,
                              hipStream_t stream, int num_cus);
 
-// The same contraction with either operand optionally T-major: ta: A is [T, R], tb: B is [T, C] (the
+// The same contraction with either operand in any OperandLayout: kLayoutTMajor: A is [T, R], B is [T, C] (the
 // contraction index runs down the rows), so the backward GEMMs can read the untransposed quantized tensors.
-int launch_gemm_fp8(const uint8_t* A, int fmtA, bool ta, const uint8_t* B, int fmtB, bool tb, int64_t R, int64_t C,
+int launch_gemm_fp8(const uint8_t* A, int fmtA, int layout_a, const uint8_t* B, int fmtB, int layout_b, int64_t R, int64_t C,
                     int64_t T, const float* d_scaleA, const float* d_scaleB, void* c_bf16, int accumulate,
                     float* d_amax_c, bool amax_is_zeroed, hipStream_t stream, int num_cus, GemmScratch scratch);
 

@@ -125,7 +125,8 @@ constexpr int kTileRows = 128, kTileCols = 256, kTilePitch = kTileRows + 16;
 template <int FMT>
 __global__ __launch_bounds__(kQThreads) void quantize_tile_kernel(
     const uint16_t* __restrict__ x, int64_t rows, int64_t cols, const ScaleSource scale_src,
-    uint8_t* __restrict__ q, uint8_t* __restrict__ qt, unsigned* __restrict__ zero_word, unsigned grid_cols) {
+    uint8_t* __restrict__ q, uint8_t* __restrict__ qt, unsigned* __restrict__ zero_word, unsigned grid_cols,
+    int64_t qt_row_stride, int64_t qt_band_stride) {
     __shared__ unsigned s_part[kQThreads / kWave];
     __shared__ __attribute__((aligned(16))) uint8_t s_t[kTileCols * kTilePitch];
     if (zero_word && blockIdx.x == 0 && threadIdx.x == 0) *zero_word = 0u;
@@ -164,13 +165,16 @@ __global__ __launch_bounds__(kQThreads) void quantize_tile_kernel(
             *reinterpret_cast<v4u*>(s_t + (tc + 4 * k + c) * kTilePitch + tr) = v4u{col[c][0], col[c][1], col[c][2], col[c][3]};
     }
     __syncthreads();
-    uint8_t* dt = qt + (int64_t)bcol * kTileCols * rows + (int64_t)brow * kTileRows;
+    // Transposed row c of the tile starts qt_row_stride bytes after row c - 1, the tile of the next 128 rows of x
+    // qt_band_stride bytes further on: (rows, 128) for the transposed tensor as such, (128, cols x 128) when it is
+    // stored in slabs of 128 contraction bytes (OperandLayout), where the tile's 32 KB are one contiguous piece.
+    uint8_t* dt = qt + (int64_t)bcol * kTileCols * qt_row_stride + (int64_t)brow * qt_band_stride;
 #pragma unroll
     for (int m = 0; m < kTileCols * (kTileRows / 16) / kQThreads; ++m) {
         const int p = threadIdx.x + m * kQThreads;          // 16-byte piece: column p / 8, rows 16 (p % 8) ..
         const int c = p >> 3, ch = p & 7;
         const v4u v = *reinterpret_cast<const v4u*>(s_t + c * kTilePitch + ch * 16);
-        *reinterpret_cast<v4u*>(dt + (int64_t)c * rows + ch * 16) = v;
+        *reinterpret_cast<v4u*>(dt + (int64_t)c * qt_row_stride + ch * 16) = v;
     }
 }
 
@@ -252,14 +256,19 @@ static bool use_tile_kernel() {
 }
 
 int launch_quantize(const void* x, int64_t rows, int64_t cols, const float* d_scale, int fmt,
-                    uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream) {
+                    uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream, bool qt_slabs) {
     const ScaleSource src{d_scale, nullptr, 0, fp8_max(fmt), nullptr};
-    return launch_quantize_from(x, rows, cols, src, fmt, q, q_t, zero_word, stream);
+    return launch_quantize_from(x, rows, cols, src, fmt, q, q_t, zero_word, stream, qt_slabs);
+}
+
+bool quantize_can_write_slabs(int64_t rows, int64_t cols) {
+    return rows % kTileRows == 0 && cols % kTileCols == 0 && use_tile_kernel();
 }
 
 int launch_quantize_from(const void* x, int64_t rows, int64_t cols, const ScaleSource& d_scale, int fmt,
-                         uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream) {
+                         uint8_t* q, uint8_t* q_t, unsigned* zero_word, hipStream_t stream, bool qt_slabs) {
     const uint16_t* xb = reinterpret_cast<const uint16_t*>(x);
+    if (qt_slabs && !(q_t && quantize_can_write_slabs(rows, cols))) return -2;       // the caller asks first
     if (!q_t && (rows * cols) % 8 == 0) {
         const int64_t n8 = rows * cols / 8;
         const dim3 grid((unsigned)((n8 + kQThreads * kFlatUnits - 1) / (kQThreads * kFlatUnits)));
@@ -267,8 +276,9 @@ int launch_quantize_from(const void* x, int64_t rows, int64_t cols, const ScaleS
         else hipLaunchKernelGGL((quantize_flat_kernel<1>), grid, dim3(kQThreads), 0, stream, xb, n8, d_scale, q, zero_word);
     } else if (q_t && rows % kTileRows == 0 && cols % kTileCols == 0 && use_tile_kernel()) {
         const unsigned gc = (unsigned)(cols / kTileCols), gr = (unsigned)(rows / kTileRows);
-        if (fmt == 0) hipLaunchKernelGGL((quantize_tile_kernel<0>), dim3(gr * gc), dim3(kQThreads), 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word, gc);
-        else hipLaunchKernelGGL((quantize_tile_kernel<1>), dim3(gr * gc), dim3(kQThreads), 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word, gc);
+        const int64_t row_stride = qt_slabs ? kTileRows : rows, band_stride = qt_slabs ? cols * kTileRows : kTileRows;
+        if (fmt == 0) hipLaunchKernelGGL((quantize_tile_kernel<0>), dim3(gr * gc), dim3(kQThreads), 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word, gc, row_stride, band_stride);
+        else hipLaunchKernelGGL((quantize_tile_kernel<1>), dim3(gr * gc), dim3(kQThreads), 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word, gc, row_stride, band_stride);
     } else if (rows % kPatchRows == 0 && cols % QuantTuning::kPatchCols == 0) {
         launch_patch<QuantTuning>(xb, rows, cols, d_scale, fmt, q, q_t, zero_word, stream);
     } else {

@@ -21,12 +21,14 @@ JIT_W = 16
 JIT_DY = 32
 NO_TRANSPOSE = 64
 SHARE_TILES = 128
+SLAB_COPIES = 256
+LAYOUT_ROWS, LAYOUT_T_MAJOR, LAYOUT_SLABS = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libllmq.so")
 _lib = None
 
-EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "llmq_amax", "llmq_amax_static", "llmq_quantize_fp8", "llmq_fp8_gemm_tn", "llmq_fp8_gemm", "llmq_fp8_gemm_scratch_bytes", "llmq_fp8_gemm_with_scratch", "llmq_bf16_gemm_tn",
+EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "llmq_amax", "llmq_amax_static", "llmq_quantize_fp8", "llmq_quantize_fp8_slabs", "llmq_fp8_gemm_tn", "llmq_fp8_gemm", "llmq_fp8_gemm_scratch_bytes", "llmq_fp8_gemm_with_scratch", "llmq_bf16_gemm_tn",
            "llmq_fp8_linear_workspace_bytes", "llmq_fp8_linear_workspace_bytes_no_transpose", "llmq_fp8_linear_workspace_bytes_shared", "llmq_fp8_linear_workspace_offsets",
            "llmq_fp8_linear_fwd", "llmq_fp8_linear_dgrad", "llmq_fp8_linear_wgrad",
            "llmq_scale_from_amax", "llmq_swiglu_workspace_bytes", "llmq_swiglu_fwd", "llmq_swiglu_fwd_fp8",
@@ -63,6 +65,8 @@ def lib() -> ctypes.CDLL:
     L.llmq_amax_static.argtypes = [vp, sz, i32, vp, vp, vp]
     L.llmq_quantize_fp8.restype = i32
     L.llmq_quantize_fp8.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp]
+    L.llmq_quantize_fp8_slabs.restype = i32
+    L.llmq_quantize_fp8_slabs.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp]
     L.llmq_fp8_gemm_tn.restype = i32
     L.llmq_fp8_gemm_tn.argtypes = [vp, i32, vp, i32, i64, i64, i64, vp, vp, vp, i32, vp, vp]
     L.llmq_fp8_gemm.restype = i32
@@ -171,6 +175,16 @@ def llmq_quantize_fp8(x: torch.Tensor, d_scale: torch.Tensor, fmt: int, q: torch
            "llmq_quantize_fp8")
 
 
+def llmq_quantize_fp8_slabs(x: torch.Tensor, d_scale: torch.Tensor, fmt: int, q: torch.Tensor, q_t: torch.Tensor) -> None:
+    """q_t: rows * cols bytes, the transposed copy as [rows / 128, cols, 128]."""
+    rows, cols = x.shape
+    if q.numel() != rows * cols or q_t.numel() != rows * cols:
+        raise ValueError("output size does not match the input")
+    _check(lib().llmq_quantize_fp8_slabs(_dev(x, torch.bfloat16, "x"), rows, cols, _dev(d_scale, torch.float32, "d_scale"),
+                                         fmt, _dev(q, torch.uint8, "q"), _dev(q_t, torch.uint8, "q_t"), _stream()),
+           "llmq_quantize_fp8_slabs")
+
+
 def llmq_fp8_gemm_tn(A: torch.Tensor, fmtA: int, B: torch.Tensor, fmtB: int, d_scaleA: torch.Tensor,
                      d_scaleB: torch.Tensor, c: torch.Tensor, accumulate: bool = False,
                      d_amax_c: Optional[torch.Tensor] = None) -> None:
@@ -184,16 +198,29 @@ def llmq_fp8_gemm_tn(A: torch.Tensor, fmtA: int, B: torch.Tensor, fmtB: int, d_s
                                   _dev(d_amax_c, torch.float32), _stream()), "llmq_fp8_gemm_tn")
 
 
+def _operand_dims(t: torch.Tensor, layout: int):
+    """(T, rows) of a contraction operand given as [rows, T], [T, rows] or [T / 128, rows, 128]."""
+    if layout == LAYOUT_SLABS:
+        if t.dim() != 3 or t.shape[2] != 128:
+            raise ValueError("an operand in slabs is [T / 128, rows, 128], got %s" % (tuple(t.shape),))
+        return t.shape[0] * 128, t.shape[1]
+    if t.dim() != 2:
+        raise ValueError("operand must be 2-D, got %s" % (tuple(t.shape),))
+    return tuple(t.shape) if layout == LAYOUT_T_MAJOR else tuple(t.shape[::-1])
+
+
 def llmq_fp8_gemm(A: torch.Tensor, fmtA: int, a_t_major: bool, B: torch.Tensor, fmtB: int, b_t_major: bool,
                   d_scaleA: torch.Tensor, d_scaleB: torch.Tensor, c: torch.Tensor, accumulate: bool = False,
                   d_amax_c: Optional[torch.Tensor] = None) -> None:
-    """A is [R, T], or [T, R] when a_t_major; B is [C, T], or [T, C] when b_t_major."""
-    T, R = A.shape if a_t_major else A.shape[::-1]
-    T2, C = B.shape if b_t_major else B.shape[::-1]
+    """A is [R, T], [T, R] when a_t_major is True / LAYOUT_T_MAJOR, [T / 128, R, 128] when it is LAYOUT_SLABS;
+    B likewise."""
+    la, lb = int(a_t_major), int(b_t_major)
+    T, R = _operand_dims(A, la)
+    T2, C = _operand_dims(B, lb)
     if T != T2 or tuple(c.shape) != (R, C):
         raise ValueError("shape mismatch: A %s, B %s, c %s" % (tuple(A.shape), tuple(B.shape), tuple(c.shape)))
-    _check(lib().llmq_fp8_gemm(_dev(A, torch.uint8, "A"), fmtA, int(bool(a_t_major)), _dev(B, torch.uint8, "B"), fmtB,
-                               int(bool(b_t_major)), R, C, T, _dev(d_scaleA, torch.float32),
+    _check(lib().llmq_fp8_gemm(_dev(A, torch.uint8, "A"), fmtA, la, _dev(B, torch.uint8, "B"), fmtB,
+                               lb, R, C, T, _dev(d_scaleA, torch.float32),
                                _dev(d_scaleB, torch.float32), _dev(c, torch.bfloat16, "c"), int(bool(accumulate)),
                                _dev(d_amax_c, torch.float32), _stream()), "llmq_fp8_gemm")
 
@@ -206,12 +233,13 @@ def llmq_fp8_gemm_with_scratch(A: torch.Tensor, fmtA: int, a_t_major: bool, B: t
                                d_scaleA: torch.Tensor, d_scaleB: torch.Tensor, c: torch.Tensor, accumulate: bool,
                                d_amax_c: Optional[torch.Tensor], scratch: Optional[torch.Tensor]) -> None:
     """llmq_fp8_gemm with scratch (a uint8 tensor or None) for sharing out a ragged last round of tiles."""
-    T, R = A.shape if a_t_major else A.shape[::-1]
-    T2, C = B.shape if b_t_major else B.shape[::-1]
+    la, lb = int(a_t_major), int(b_t_major)
+    T, R = _operand_dims(A, la)
+    T2, C = _operand_dims(B, lb)
     if T != T2 or tuple(c.shape) != (R, C):
         raise ValueError("shape mismatch: A %s, B %s, c %s" % (tuple(A.shape), tuple(B.shape), tuple(c.shape)))
-    _check(lib().llmq_fp8_gemm_with_scratch(_dev(A, torch.uint8, "A"), fmtA, int(bool(a_t_major)), _dev(B, torch.uint8, "B"),
-                                            fmtB, int(bool(b_t_major)), R, C, T, _dev(d_scaleA, torch.float32),
+    _check(lib().llmq_fp8_gemm_with_scratch(_dev(A, torch.uint8, "A"), fmtA, la, _dev(B, torch.uint8, "B"),
+                                            fmtB, lb, R, C, T, _dev(d_scaleA, torch.float32),
                                             _dev(d_scaleB, torch.float32), _dev(c, torch.bfloat16, "c"),
                                             int(bool(accumulate)), _dev(d_amax_c, torch.float32),
                                             _dev(scratch, torch.uint8, "scratch"),

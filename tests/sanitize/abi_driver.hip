@@ -17,12 +17,13 @@ int launch_amax_static(const void*, size_t, int, float*, float*, hipStream_t, in
 int launch_amax_final(const unsigned*, int, int, float*, float*, hipStream_t) { ++g_launches; return 0; }
 int launch_gemm_bf16_tn(const void*, const void*, int64_t, int64_t, int64_t, void*, int, hipStream_t, int) { ++g_launches; return 0; }
 int launch_scale_from_amax(const float*, int, float*, hipStream_t) { ++g_launches; return 0; }
-int launch_quantize(const void*, int64_t, int64_t, const float*, int, uint8_t*, uint8_t*, unsigned*, hipStream_t) { ++g_launches; return 0; }
-int launch_quantize_from(const void*, int64_t, int64_t, const ScaleSource&, int, uint8_t*, uint8_t*, unsigned*, hipStream_t) { ++g_launches; return 0; }
+int launch_quantize(const void*, int64_t, int64_t, const float*, int, uint8_t*, uint8_t*, unsigned*, hipStream_t, bool) { ++g_launches; return 0; }
+bool quantize_can_write_slabs(int64_t rows, int64_t cols) { return rows % 128 == 0 && cols % 256 == 0; }
+int launch_quantize_from(const void*, int64_t, int64_t, const ScaleSource&, int, uint8_t*, uint8_t*, unsigned*, hipStream_t, bool) { ++g_launches; return 0; }
 int launch_amax_partial(const void*, size_t, unsigned*, int* n_partial, hipStream_t, int) { ++g_launches; *n_partial = 7; return 0; }
 size_t gemm_scratch_bytes(int64_t R, int64_t C, int64_t, int) { return (size_t)((R / 256) * (C / 256) % 7) * 262144; }
-int launch_gemm_tn(const uint8_t*, int, const uint8_t*, int, int64_t, int64_t, int64_t, const float*, const float*, void*, int, float*, bool, hipStream_t, int, GemmScratch sc) { ++g_launches; g_scratch_seen = sc.ptr ? sc.bytes : 0; return 0; }
-int launch_gemm_fp8(const uint8_t*, int, bool, const uint8_t*, int, bool, int64_t, int64_t, int64_t, const float*, const float*, void*, int, float*, bool, hipStream_t, int, GemmScratch sc) { ++g_launches; g_scratch_seen = sc.ptr ? sc.bytes : 0; return 0; }
+int launch_gemm_tn(const uint8_t*, int, const uint8_t*, int, int64_t, int64_t, int64_t, const float*, const float*, void*, int, float*, bool, hipStream_t, int, GemmScratch sc, bool, bool) { ++g_launches; g_scratch_seen = sc.ptr ? sc.bytes : 0; return 0; }
+int launch_gemm_fp8(const uint8_t*, int, int, const uint8_t*, int, int, int64_t, int64_t, int64_t, const float*, const float*, void*, int, float*, bool, hipStream_t, int, GemmScratch sc) { ++g_launches; g_scratch_seen = sc.ptr ? sc.bytes : 0; return 0; }
 int gemm_phase_stamp_blocks(int64_t R, int64_t C) { return (int)((R / 256) * (C / 256)); }
 int launch_gemm_phase_stamps(const uint8_t*, const uint8_t*, int64_t, int64_t, int64_t, const float*, const float*, void*, float*, long long*, int, hipStream_t, int) { ++g_launches; return 0; }
 int64_t swiglu_blocks(int64_t M, int64_t I) { return (M + 31) / 32 * ((I + 255) / 256); }

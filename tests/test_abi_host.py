@@ -88,12 +88,16 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.llmq_fp8_gemm(ok_ptr, 0, 1, ok_ptr, 0, 1, 16, 0, 16, ok_ptr, ok_ptr, ok_ptr, 0, None, None) == -2
     assert L.llmq_fp8_gemm(ok_ptr, 0, 1, ok_ptr, 5, 0, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, 0, None, None) == -4
     assert L.llmq_fp8_gemm(odd_ptr, 0, 0, ok_ptr, 0, 1, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, 0, None, None) == -3
+    assert L.llmq_fp8_gemm(ok_ptr, 0, 3, ok_ptr, 0, 0, 16, 16, 128, ok_ptr, ok_ptr, ok_ptr, 0, None, None) == -7              # no such layout
+    assert L.llmq_fp8_gemm(ok_ptr, 0, 0, ok_ptr, 0, -1, 16, 16, 128, ok_ptr, ok_ptr, ok_ptr, 0, None, None) == -7
+    assert L.llmq_fp8_gemm(ok_ptr, 0, 2, ok_ptr, 0, 0, 16, 16, 192, ok_ptr, ok_ptr, ok_ptr, 0, None, None) == -2              # slabs are 128 contraction bytes
     ws = 0x100000
     need = llmq.llmq_fp8_linear_workspace_bytes(16, 16, 16)
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, None, n(need), 0, None) == -1
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need - 1), 0, None) == -5
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws + 16, n(need), 0, None) == -3
-    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 256, None) == -7
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 512, None) == -7
+    assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 256 | 64, None) == -7  # slabs are a layout of the transposed copies
     assert L.llmq_fp8_linear_fwd(ok_ptr, ok_ptr, 16, 16, 16, ok_ptr, ok_ptr, ok_ptr, None, ws, n(need), 128 | 64, None) == -7  # shared tiles need the transposed copies
     big = (16384, 5120, 7168)                                   # a shape whose weight gradient shares tiles
     shared, plain = llmq.llmq_fp8_linear_workspace_bytes_shared(*big), llmq.llmq_fp8_linear_workspace_bytes(*big)
