@@ -226,8 +226,8 @@ def measure_bf16_baseline(cfg, dev, reps):
 
 def measure_swiglu(cfg, dev, reps):
     """The block's SwiGLU with its fused outputs (next to the linears, not part of the step's FLOP count):
-    forward writing h + absmax, recompute mode writing FP8 bytes (both layouts) instead of h, backward
-    writing dGU + absmax.  GB/s on algorithmic bytes: 6, 6 and 10 per element of h."""
+    forward writing h + absmax, recompute mode writing FP8 bytes (both layouts; the transposed copy plain or in
+    slabs of 128 contraction bytes) instead of h, backward writing dGU + absmax.  GB/s on algorithmic bytes: 6, 6 and 10 per element of h."""
     import torch
     from paper_2512_15306_amd import llmq, synth
     M, I = synth.swiglu_dims(cfg)
@@ -243,6 +243,7 @@ def measure_swiglu(cfg, dev, reps):
     legs = {
         "fwd_h_absmax": (6.0, lambda: llmq.llmq_swiglu_fwd(gu, h, llmq.E4M3, f[0:1], f[1:2], ws)),
         "fwd_fp8_both_layouts": (6.0, lambda: llmq.llmq_swiglu_fwd_fp8(gu, f[1:2], llmq.E4M3, q, qt, None)),
+        "fwd_fp8_slab_copy": (6.0, lambda: llmq.llmq_swiglu_fwd_fp8_slabs(gu, f[1:2], llmq.E4M3, q, qt, None)),
         "bwd_dgu_absmax": (10.0, lambda: llmq.llmq_swiglu_bwd(dh, gu, dgu, llmq.E5M2, f[2:3], f[3:4], ws)),
         "separate_absmax_of_h": (2.0, lambda: llmq.llmq_amax(h, llmq.E4M3, f[0:1], f[1:2], aws)),
         "separate_quantize_of_h": (4.0, lambda: llmq.llmq_quantize_fp8(h, f[1:2], llmq.E4M3, q, qt)),
@@ -274,6 +275,7 @@ def measure_rmsnorm(cfg, dev, reps):
     legs = {
         "fwd_add_norm_absmax": (8.0, lambda: llmq.llmq_rmsnorm_fwd(res, x, w, 1e-6, res_out, y, rstd, llmq.E4M3, f[0:1], f[1:2], ws)),
         "recompute_fp8_both_layouts": (4.0, lambda: llmq.llmq_rmsnorm_apply_fp8(res_out, w, rstd, f[1:2], llmq.E4M3, q, qt, None)),
+        "recompute_fp8_slab_copy": (4.0, lambda: llmq.llmq_rmsnorm_apply_fp8_slabs(res_out, w, rstd, f[1:2], llmq.E4M3, q, qt, None)),
     }
     out = {"M": M, "C": C}
     for name, (bpe, fn) in legs.items():

@@ -251,8 +251,9 @@ int llmq_fp8_linear_workspace_offsets(int64_t M, int64_t N, int64_t K, size_t of
  * tensors keep the plain form): a 128 x 256 tile of a tensor then lands as one contiguous 32 KB piece of its
  * transposed copy instead of 256 pieces of 128 bytes, and every K step of a backward contraction reads one
  * contiguous piece per operand.  Results are the same bytes as without the flag.  Copies made under this flag can
- * only be reused (LLMQ_REUSE_*) by calls that carry it too, and copies made without it (or by the producers that
- * write FP8 directly, llmq_swiglu_fwd_fp8 and llmq_rmsnorm_apply_fp8) only by calls without it.  Not together with
+ * only be reused (LLMQ_REUSE_*) by calls that carry it too (the producers that write FP8 directly make such
+ * copies with llmq_swiglu_fwd_fp8_slabs and llmq_rmsnorm_apply_fp8_slabs), and copies made without it (or by
+ * llmq_swiglu_fwd_fp8 and llmq_rmsnorm_apply_fp8) only by calls without it.  Not together with
  * LLMQ_NO_TRANSPOSE (LLMQ_ERR_FLAGS). */
 #define LLMQ_SLAB_COPIES 256
 
@@ -313,17 +314,24 @@ int llmq_scale_from_amax(const float* d_amax, int fmt, float* d_scale, void* str
  *   llmq_quantize_fp8 would produce from h with *d_scale_h, q_t [I, M] their transposed copy if not NULL,
  *   and h itself only if h_bf16 is not NULL.  With q and q_t pointing at the Xq / Xq_t sections of a linear
  *   workspace, the down projection then runs with LLMQ_REUSE_X.
+ * llmq_swiglu_fwd_fp8_slabs: the same with q_t (required) in slabs of 128 contraction bytes, exactly what
+ *   llmq_quantize_fp8_slabs writes from h (byte (i, m) of the transposed tensor at (m / 128) I 128 + i 128 + m % 128),
+ *   for a down projection that runs with LLMQ_REUSE_X | LLMQ_SLAB_COPIES.  M % 128 == 0, I % 256 == 0 and
+ *   M I < 0x70000000 (the tensors such a linear call keeps in slabs), else LLMQ_ERR_SHAPE.
  * llmq_swiglu_bwd: dh [M, I], GU [M, 2I] -> dGU [M, 2I] (same column layout):
  *     dGU[m, I+i] = bf16( dh * (g * sg) ),   dGU[m, i] = bf16( ((dh * u) * sg) * fma(g, 1 - sg, 1) ),
  *   plus absmax and, if wanted, scale (format fmt) of dGU, which is the dY of the gate+up projection.
  * M, I >= 1, I < 2^24; GU, h, dh, dGU 16-byte aligned and I % 8 == 0 for that to hold for every row (other
- * I, and M not a multiple of 4, or of 16 with q_t, take a slower generic kernel).
+ * I, and M not a multiple of 4, or of 16 with q_t, take a slower generic kernel; with q_t, M % 128 == 0 and
+ * I % 256 == 0 take the fastest one).
  */
 size_t llmq_swiglu_workspace_bytes(int64_t M, int64_t I);
 int llmq_swiglu_fwd(const void* gu_bf16, int64_t M, int64_t I, void* h_bf16, int fmt,
                     float* d_amax_h, float* d_scale_h, void* ws, size_t ws_bytes, void* stream);
 int llmq_swiglu_fwd_fp8(const void* gu_bf16, int64_t M, int64_t I, const float* d_scale_h, int fmt,
                         uint8_t* q, uint8_t* q_t, void* h_bf16, void* stream);
+int llmq_swiglu_fwd_fp8_slabs(const void* gu_bf16, int64_t M, int64_t I, const float* d_scale_h, int fmt,
+                              uint8_t* q, uint8_t* q_t, void* h_bf16, void* stream);
 int llmq_swiglu_bwd(const void* dh_bf16, const void* gu_bf16, int64_t M, int64_t I, void* dgu_bf16, int fmt,
                     float* d_amax_dgu, float* d_scale_dgu, void* ws, size_t ws_bytes, void* stream);
 
@@ -349,8 +357,12 @@ int llmq_swiglu_bwd(const void* dh_bf16, const void* gu_bf16, int64_t M, int64_t
  *   given; writes q [M, C] = the FP8 codes llmq_quantize_fp8 would produce from y with *d_scale_y, their
  *   transposed copy q_t [C, M] if not NULL, and y itself only if y_bf16 is not NULL.  Element-wise, hence
  *   reproducible bit for bit from its inputs.  rstd must be 16-byte aligned.
+ * llmq_rmsnorm_apply_fp8_slabs: the same with q_t (required) in slabs of 128 contraction bytes, as
+ *   llmq_quantize_fp8_slabs writes it from y, for a linear call with LLMQ_REUSE_X | LLMQ_SLAB_COPIES.
+ *   M % 128 == 0, C % 256 == 0 and M C < 0x70000000, else LLMQ_ERR_SHAPE.
  * M, C >= 1, C < 2^24.  C % 8 == 0 and C <= 8192 take the single-pass forward kernel; M % 16 == 0 (M % 4
- * without q_t) and C % 8 == 0 the tuned recompute kernel; other shapes slower generic ones.
+ * without q_t) and C % 8 == 0 the tuned recompute kernels (with q_t, M % 128 == 0 and C % 256 == 0 the fastest
+ * one); other shapes slower generic ones.
  */
 size_t llmq_rmsnorm_workspace_bytes(int64_t M);
 int llmq_rmsnorm_fwd(const void* res_bf16, const void* x_bf16, const void* w_bf16, int64_t M, int64_t C,
@@ -359,6 +371,9 @@ int llmq_rmsnorm_fwd(const void* res_bf16, const void* x_bf16, const void* w_bf1
 int llmq_rmsnorm_apply_fp8(const void* res_bf16, const void* w_bf16, const float* rstd, int64_t M, int64_t C,
                            const float* d_scale_y, int fmt, uint8_t* q, uint8_t* q_t, void* y_bf16,
                            void* stream);
+int llmq_rmsnorm_apply_fp8_slabs(const void* res_bf16, const void* w_bf16, const float* rstd, int64_t M,
+                                 int64_t C, const float* d_scale_y, int fmt, uint8_t* q, uint8_t* q_t,
+                                 void* y_bf16, void* stream);
 
 /*
  * Peak calibration (the paper's appendix "A note on MFU" measures the attainable peak with a large-matmul

@@ -103,8 +103,10 @@ int quantize_operand(const void* t, int64_t rows, int64_t cols, float* d_scale, 
 // Under LLMQ_SLAB_COPIES the transposed copy of a tensor [rows, cols] is stored in slabs of 128 contraction bytes
 // whenever the quantizer's tile kernel takes the tensor (a pure function of the shape, so that the call that
 // writes a copy and the calls that reuse it agree); otherwise as the plain transposed tensor.
+constexpr int64_t kMaxSlabElems = 0x70000000;      // tensors kept in slabs stay below this many elements
+
 bool slab_copy(int flags, int64_t rows, int64_t cols) {
-    return (flags & LLMQ_SLAB_COPIES) && llmq::quantize_can_write_slabs(rows, cols) && rows * cols < (int64_t)0x70000000;
+    return (flags & LLMQ_SLAB_COPIES) && llmq::quantize_can_write_slabs(rows, cols) && rows * cols < kMaxSlabElems;
 }
 
 }  // namespace
@@ -125,7 +127,7 @@ const char* llmq_status_string(int status) {
     }
 }
 
-int llmq_version(void) { return 210; }
+int llmq_version(void) { return 211; }
 
 size_t llmq_amax_workspace_bytes(void) { return (size_t)llmq::kAmaxMaxPartials * sizeof(unsigned); }
 
@@ -364,6 +366,19 @@ int llmq_swiglu_fwd_fp8(const void* gu_bf16, int64_t M, int64_t I, const float* 
                                    static_cast<hipStream_t>(stream));
 }
 
+int llmq_swiglu_fwd_fp8_slabs(const void* gu_bf16, int64_t M, int64_t I, const float* d_scale_h, int fmt, uint8_t* q,
+                              uint8_t* q_t, void* h_bf16, void* stream) {
+    if (!gu_bf16 || !d_scale_h || !q || !q_t) return LLMQ_ERR_NULL;
+    int st = check_swiglu_shape(M, I);
+    if (st != LLMQ_OK) return st;
+    if (!llmq::tile_shape_ok(M, I) || M * I >= kMaxSlabElems) return LLMQ_ERR_SHAPE;
+    if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
+    if (!aligned(gu_bf16, 16) || !aligned(h_bf16, 16) || !aligned(q, 16) || !aligned(q_t, 16) || !aligned(d_scale_h, 4))
+        return LLMQ_ERR_ALIGN;
+    return llmq::launch_swiglu_fwd(gu_bf16, M, I, h_bf16, nullptr, fmt, nullptr, nullptr, d_scale_h, fmt, q, q_t,
+                                   static_cast<hipStream_t>(stream), true);
+}
+
 int llmq_swiglu_bwd(const void* dh_bf16, const void* gu_bf16, int64_t M, int64_t I, void* dgu_bf16, int fmt,
                     float* d_amax_dgu, float* d_scale_dgu, void* ws, size_t ws_bytes, void* stream) {
     if (!dh_bf16 || !gu_bf16 || !dgu_bf16 || !d_amax_dgu || !ws) return LLMQ_ERR_NULL;
@@ -412,13 +427,27 @@ int llmq_rmsnorm_apply_fp8(const void* res_bf16, const void* w_bf16, const float
                                           static_cast<hipStream_t>(stream));
 }
 
+int llmq_rmsnorm_apply_fp8_slabs(const void* res_bf16, const void* w_bf16, const float* rstd, int64_t M, int64_t C,
+                                 const float* d_scale_y, int fmt, uint8_t* q, uint8_t* q_t, void* y_bf16,
+                                 void* stream) {
+    if (!res_bf16 || !w_bf16 || !rstd || !d_scale_y || !q || !q_t) return LLMQ_ERR_NULL;
+    if (!dim_ok(M) || !dim_ok(C) || C >= ((int64_t)1 << 24) || M * C >= kMaxElems) return LLMQ_ERR_SHAPE;
+    if (!llmq::tile_shape_ok(M, C) || M * C >= kMaxSlabElems) return LLMQ_ERR_SHAPE;
+    if (!fmt_ok(fmt)) return LLMQ_ERR_FORMAT;
+    if (!aligned(res_bf16, 16) || !aligned(w_bf16, 16) || !aligned(rstd, 16) || !aligned(d_scale_y, 4) ||
+        !aligned(q, 16) || !aligned(q_t, 16) || !aligned(y_bf16, 16))
+        return LLMQ_ERR_ALIGN;
+    return llmq::launch_rmsnorm_apply_fp8(res_bf16, w_bf16, rstd, M, C, d_scale_y, fmt, q, q_t, y_bf16,
+                                          static_cast<hipStream_t>(stream), true);
+}
+
 int llmq_calibrate_mfma(int fmtA, int fmtB, int random_bits, int iters, float* d_sink, double* flops,
                         void* stream) {
     if (!d_sink) return LLMQ_ERR_NULL;
     if (!fmt_ok(fmtA) || !fmt_ok(fmtB)) return LLMQ_ERR_FORMAT;
     if (iters < 1 || iters > (1 << 24)) return LLMQ_ERR_SHAPE;
     if (!aligned(d_sink, 4)) return LLMQ_ERR_ALIGN;
-    // workgroups x waves x iterations x 16 MFMAs x 2 * 32 * 32 * 64 FLOP
+    // workgroups x waves x iterations x 64 MFMAs x 2 * 16 * 16 * 128 FLOP
     if (flops) *flops = (double)num_cus() * 4.0 * iters * 64.0 * 2.0 * 16 * 16 * 128;
     return llmq::launch_calibrate_mfma(fmtA, fmtB, random_bits != 0, iters, d_sink, static_cast<hipStream_t>(stream),
                                        num_cus());

@@ -140,4 +140,58 @@ __device__ inline void transpose4x4_bytes(const unsigned w[4], unsigned o[4]) {
     o[3] = __builtin_amdgcn_perm(t23h, t01h, 0x07060302u);
 }
 
+// ---- The 128-row x 256-column workgroup tile of the kernels that write FP8 codes in both layouts ----
+//
+// 256 lanes; a lane owns a patch of 16 rows x 8 columns, a wave is 4 lanes stacked x 16 side by side (64 rows x 128
+// columns: its loads of BF16 input cover 256 contiguous bytes of a row, its stores of codes a whole 128-byte line),
+// the four waves tile 128 x 256.  The transposed patches (16-byte column pieces after the register transpose)
+// go through a [256 columns][128 rows] byte tile in LDS (rows padded to 144 bytes against bank conflicts) and
+// leave, after one barrier, as 128-byte lines of the transposed tensor, 8 lanes per transposed row.
+constexpr int kTilePitch = kTileRows + 16;        // kTileRows = 128, kTileCols = 256
+constexpr int kTileThreads = 256, kPatchRows = 16;
+constexpr int kTileLdsBytes = kTileCols * kTilePitch;
+
+// Origin of this lane's patch inside the tile
+__device__ inline void tile_patch_origin(int& tr, int& tc) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    tr = (wave >> 1) * 64 + (lane & 3) * kPatchRows;
+    tc = (wave & 1) * 128 + (lane >> 2) * 8;
+}
+
+// The patch as FP8 bytes, w[row][k] = columns 4k .. 4k+3: column j of the patch becomes 16 consecutive bytes of
+// row (tc + j) of the LDS tile, at byte tr.
+__device__ inline void tile_stage_transposed(const unsigned (&w)[kPatchRows][2], int tr, int tc, uint8_t* s_t) {
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        unsigned col[4][4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            unsigned blk[4] = {w[4 * t][k], w[4 * t + 1][k], w[4 * t + 2][k], w[4 * t + 3][k]};
+            unsigned o[4];
+            transpose4x4_bytes(blk, o);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) col[c][t] = o[c];
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            *reinterpret_cast<v4u*>(s_t + (tc + 4 * k + c) * kTilePitch + tr) = v4u{col[c][0], col[c][1], col[c][2], col[c][3]};
+    }
+}
+
+// After the barrier that follows the staging: the whole tile to memory.  dt = where transposed row 0 of this tile
+// starts; transposed row c starts row_stride bytes after row c - 1.  The transposed tensor [cols, rows] as such:
+// dt = qt + (first column) rows + (first row), row_stride = rows.  In slabs of 128 contraction bytes
+// (OperandLayout): dt = qt + (first row / 128) cols 128 + (first column) 128, row_stride = 128, and the tile's
+// 32 KB are one contiguous piece.
+__device__ inline void tile_write_transposed(const uint8_t* s_t, uint8_t* dt, int64_t row_stride) {
+#pragma unroll
+    for (int m = 0; m < kTileCols * (kTileRows / 16) / kTileThreads; ++m) {
+        const int p = threadIdx.x + m * kTileThreads;       // 16-byte piece: column p / 8, rows 16 (p % 8) ..
+        const int c = p >> 3, ch = p & 7;
+        const v4u v = *reinterpret_cast<const v4u*>(s_t + c * kTilePitch + ch * 16);
+        *reinterpret_cast<v4u*>(dt + (int64_t)c * row_stride + ch * 16) = v;
+    }
+}
+
 }  // namespace llmq

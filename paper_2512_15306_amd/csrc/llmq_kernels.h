@@ -15,6 +15,12 @@ inline const char* tuning_env(const char* name) {
     return enabled ? getenv(name) : nullptr;
 }
 
+// The workgroup tile of the kernels that write FP8 codes in both layouts (quantize, and the SwiGLU and RMSNorm
+// kernels that emit FP8 directly): tensors made of whole tiles take the tile kernels, and only those can write
+// the transposed copy in slabs.
+constexpr int kTileRows = 128, kTileCols = 256;
+inline bool tile_shape_ok(int64_t rows, int64_t cols) { return rows % kTileRows == 0 && cols % kTileCols == 0; }
+
 // Each returns 0 or LLMQ_ERR_DEVICE (-6).  Arguments are validated by the callers in api.hip.
 constexpr int kAmaxMaxPartials = 1024;      // the absmax workspace holds one 32-bit word per block
 int launch_amax(const void* x, size_t n, int fmt, float* d_amax, float* d_scale, void* ws,
@@ -88,10 +94,12 @@ int launch_gemm_fp8(const uint8_t* A, int fmtA, int layout_a, const uint8_t* B, 
 
 // SwiGLU with its extra outputs.  h, d_amax (with partial, the per-workgroup scratch), q and q_t are
 // optional; q_fmt is only read when q is given.  swiglu_blocks() is the number of scratch words.
+// qt_slabs (here and in the RMSNorm recompute launch): q_t in slabs of 128 contraction bytes, as in
+// launch_quantize; needs q_t and tile_shape_ok(M, columns), else -2.
 int64_t swiglu_blocks(int64_t M, int64_t I);
 int launch_swiglu_fwd(const void* gu, int64_t M, int64_t I, void* h, unsigned* partial, int amax_fmt,
                       float* d_amax, float* d_scale, const float* d_qscale, int q_fmt, uint8_t* q, uint8_t* q_t,
-                      hipStream_t stream);
+                      hipStream_t stream, bool qt_slabs = false);
 int launch_swiglu_bwd(const void* dh, const void* gu, int64_t M, int64_t I, void* dgu, unsigned* partial,
                       int amax_fmt, float* d_amax, float* d_scale, hipStream_t stream);
 
@@ -103,7 +111,8 @@ int launch_rmsnorm_fwd(const void* res, const void* x, const void* w, int64_t M,
                        void* res_out, void* y, float* rstd, unsigned* partial, int fmt, float* d_amax,
                        float* d_scale, hipStream_t stream);
 int launch_rmsnorm_apply_fp8(const void* res, const void* w, const float* rstd, int64_t M, int64_t C,
-                             const float* d_qscale, int fmt, uint8_t* q, uint8_t* q_t, void* y, hipStream_t stream);
+                             const float* d_qscale, int fmt, uint8_t* q, uint8_t* q_t, void* y, hipStream_t stream,
+                             bool qt_slabs = false);
 
 int launch_calibrate_mfma(int fmtA, int fmtB, int random_bits, int iters, float* d_sink, hipStream_t stream,
                           int num_cus);

@@ -17,7 +17,6 @@
 namespace llmq {
 
 constexpr int kQThreads = 256;
-constexpr int kPatchRows = 16;
 
 // Shape of the work of one wavefront: every lane owns a patch of 16 rows x kPatchCols columns,
 // kLanesR lanes are stacked along rows (16 * kLanesR rows per wave, which is also the length in
@@ -114,28 +113,21 @@ __global__ __launch_bounds__(kQThreads) void quantize_patch_kernel(
 
 // Workgroup-tile variant for tensors whose rows are a multiple of 128 and whose columns a multiple of 256 (every
 // benchmark tensor): full 128-byte lines on all three streams.  A lane owns the same 16 x 8 patch, but a wave is
-// 4 lanes stacked x 16 side by side (64 rows x 128 columns), so that its loads cover 256 contiguous bytes of a
-// row and its row-major stores a whole 128-byte line; the four waves tile 128 rows x 256 columns.  The transposed
-// copy cannot be written that way from registers (4 stacked lanes hold 64 contiguous bytes of a transposed row),
-// so the transposed patches go through LDS: every lane writes its eight 16-byte column pieces into a
-// [256 columns][128 rows] byte tile (rows padded to 144 bytes against bank conflicts), and after one barrier the
-// workgroup writes the tile out, 8 lanes per transposed row = one 128-byte line per group of 8 lanes.
-constexpr int kTileRows = 128, kTileCols = 256, kTilePitch = kTileRows + 16;
-
+// 4 lanes stacked x 16 side by side, and the transposed copy cannot be written that way from registers (4 stacked
+// lanes hold 64 contiguous bytes of a transposed row), so the transposed patches go through LDS (the tile_*
+// helpers).
 template <int FMT>
-__global__ __launch_bounds__(kQThreads) void quantize_tile_kernel(
+__global__ __launch_bounds__(kTileThreads) void quantize_tile_kernel(
     const uint16_t* __restrict__ x, int64_t rows, int64_t cols, const ScaleSource scale_src,
     uint8_t* __restrict__ q, uint8_t* __restrict__ qt, unsigned* __restrict__ zero_word, unsigned grid_cols,
     int64_t qt_row_stride, int64_t qt_band_stride) {
-    __shared__ unsigned s_part[kQThreads / kWave];
-    __shared__ __attribute__((aligned(16))) uint8_t s_t[kTileCols * kTilePitch];
+    __shared__ unsigned s_part[kTileThreads / kWave];
+    __shared__ __attribute__((aligned(16))) uint8_t s_t[kTileLdsBytes];
     if (zero_word && blockIdx.x == 0 && threadIdx.x == 0) *zero_word = 0u;
     const float s = resolve_scale(scale_src, blockIdx.x == 0, s_part);
     const unsigned brow = blockIdx.x / grid_cols, bcol = blockIdx.x - brow * grid_cols;   // along the columns first
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
-    const int tr = (wave >> 1) * 64 + (lane & 3) * kPatchRows;      // patch origin inside the tile
-    const int tc = (wave & 1) * 128 + (lane >> 2) * 8;
+    int tr, tc;
+    tile_patch_origin(tr, tc);
     const int64_t r0 = (int64_t)brow * kTileRows + tr, c0 = (int64_t)bcol * kTileCols + tc;
     v4u in[kPatchRows];
     const uint16_t* src = x + r0 * cols + c0;
@@ -148,34 +140,10 @@ __global__ __launch_bounds__(kQThreads) void quantize_tile_kernel(
     uint8_t* dst = q + r0 * cols + c0;
 #pragma unroll
     for (int i = 0; i < kPatchRows; ++i) *reinterpret_cast<v2u*>(dst + (int64_t)i * cols) = v2u{w[i][0], w[i][1]};
-    // column j of the patch -> 16 consecutive bytes of row (tc + j) of the LDS tile, at byte tr
-#pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        unsigned col[4][4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            unsigned blk[4] = {w[4 * t][k], w[4 * t + 1][k], w[4 * t + 2][k], w[4 * t + 3][k]};
-            unsigned o[4];
-            transpose4x4_bytes(blk, o);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) col[c][t] = o[c];
-        }
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-            *reinterpret_cast<v4u*>(s_t + (tc + 4 * k + c) * kTilePitch + tr) = v4u{col[c][0], col[c][1], col[c][2], col[c][3]};
-    }
+    tile_stage_transposed(w, tr, tc, s_t);
     __syncthreads();
-    // Transposed row c of the tile starts qt_row_stride bytes after row c - 1, the tile of the next 128 rows of x
-    // qt_band_stride bytes further on: (rows, 128) for the transposed tensor as such, (128, cols x 128) when it is
-    // stored in slabs of 128 contraction bytes (OperandLayout), where the tile's 32 KB are one contiguous piece.
-    uint8_t* dt = qt + (int64_t)bcol * kTileCols * qt_row_stride + (int64_t)brow * qt_band_stride;
-#pragma unroll
-    for (int m = 0; m < kTileCols * (kTileRows / 16) / kQThreads; ++m) {
-        const int p = threadIdx.x + m * kQThreads;          // 16-byte piece: column p / 8, rows 16 (p % 8) ..
-        const int c = p >> 3, ch = p & 7;
-        const v4u v = *reinterpret_cast<const v4u*>(s_t + c * kTilePitch + ch * 16);
-        *reinterpret_cast<v4u*>(dt + (int64_t)c * qt_row_stride + ch * 16) = v;
-    }
+    // (qt_row_stride, qt_band_stride) = (rows, 128) for the transposed tensor as such, (128, cols x 128) in slabs
+    tile_write_transposed(s_t, qt + (int64_t)bcol * kTileCols * qt_row_stride + (int64_t)brow * qt_band_stride, qt_row_stride);
 }
 
 // No transposed copy wanted: the conversion is element-wise and the tensor can be taken as a flat array.  A
@@ -262,7 +230,7 @@ int launch_quantize(const void* x, int64_t rows, int64_t cols, const float* d_sc
 }
 
 bool quantize_can_write_slabs(int64_t rows, int64_t cols) {
-    return rows % kTileRows == 0 && cols % kTileCols == 0 && use_tile_kernel();
+    return tile_shape_ok(rows, cols) && use_tile_kernel();
 }
 
 int launch_quantize_from(const void* x, int64_t rows, int64_t cols, const ScaleSource& d_scale, int fmt,
@@ -274,7 +242,7 @@ int launch_quantize_from(const void* x, int64_t rows, int64_t cols, const ScaleS
         const dim3 grid((unsigned)((n8 + kQThreads * kFlatUnits - 1) / (kQThreads * kFlatUnits)));
         if (fmt == 0) hipLaunchKernelGGL((quantize_flat_kernel<0>), grid, dim3(kQThreads), 0, stream, xb, n8, d_scale, q, zero_word);
         else hipLaunchKernelGGL((quantize_flat_kernel<1>), grid, dim3(kQThreads), 0, stream, xb, n8, d_scale, q, zero_word);
-    } else if (q_t && rows % kTileRows == 0 && cols % kTileCols == 0 && use_tile_kernel()) {
+    } else if (q_t && tile_shape_ok(rows, cols) && use_tile_kernel()) {
         const unsigned gc = (unsigned)(cols / kTileCols), gr = (unsigned)(rows / kTileRows);
         const int64_t row_stride = qt_slabs ? kTileRows : rows, band_stride = qt_slabs ? cols * kTileRows : kTileRows;
         if (fmt == 0) hipLaunchKernelGGL((quantize_tile_kernel<0>), dim3(gr * gc), dim3(kQThreads), 0, stream, xb, rows, cols, d_scale, q, q_t, zero_word, gc, row_stride, band_stride);

@@ -13,6 +13,8 @@
 // Recompute kernel: rstd and the scale are inputs, so the operation is element-wise; it has the
 // lane geometry of the quantize kernel (16 rows x 8 columns per lane) and reuses its register
 // transpose to write the FP8 codes in both layouts (2 B read, 1 + 1 B written per element).
+#include <stdlib.h>
+
 #include "llmq_device.h"
 #include "llmq_kernels.h"
 
@@ -227,6 +229,47 @@ __global__ __launch_bounds__(kRnThreads) void rmsnorm_apply_fp8_patch_kernel(
     }
 }
 
+// The same for tensors made of whole 128 x 256 tiles: lane geometry and LDS transpose of the quantize kernel's tile
+// variant (full 128-byte lines on every stream; the transposed copy optionally in slabs).
+template <int QFMT, bool WRITE_Y>
+__global__ __launch_bounds__(kTileThreads) void rmsnorm_apply_fp8_tile_kernel(
+    const uint16_t* __restrict__ res, const uint16_t* __restrict__ w, const float* __restrict__ rstd,
+    int64_t M, int64_t C, const float* __restrict__ d_qscale, uint8_t* __restrict__ q,
+    uint8_t* __restrict__ qt, uint16_t* __restrict__ y, unsigned grid_cols, int64_t qt_row_stride,
+    int64_t qt_band_stride) {
+    __shared__ __attribute__((aligned(16))) uint8_t s_t[kTileLdsBytes];
+    const unsigned brow = blockIdx.x / grid_cols, bcol = blockIdx.x - brow * grid_cols;   // along the columns first
+    int tr, tc;
+    tile_patch_origin(tr, tc);
+    const int64_t r0 = (int64_t)brow * kTileRows + tr, c0 = (int64_t)bcol * kTileCols + tc;
+    const uint16_t* src = res + r0 * C + c0;
+    v4u in[kPatchRows];
+#pragma unroll
+    for (int i = 0; i < kPatchRows; ++i) in[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(src + (int64_t)i * C));
+    const v4u wv = *reinterpret_cast<const v4u*>(w + c0);
+    float rs[kPatchRows];
+#pragma unroll
+    for (int i = 0; i < kPatchRows / 4; ++i) {
+        const v4f t = *reinterpret_cast<const v4f*>(rstd + r0 + 4 * i);
+        rs[4 * i] = t[0]; rs[4 * i + 1] = t[1]; rs[4 * i + 2] = t[2]; rs[4 * i + 3] = t[3];
+    }
+    const float s = *d_qscale;
+    __builtin_amdgcn_sched_barrier(0);
+    unsigned wq[kPatchRows][2];
+#pragma unroll
+    for (int i = 0; i < kPatchRows; ++i) {
+        const v4u o = normalize8(in[i], rs[i], wv);
+        if constexpr (WRITE_Y) *reinterpret_cast<v4u*>(y + (r0 + i) * C + c0) = o;
+        quantize8<QFMT>(o, s, wq[i][0], wq[i][1]);
+    }
+    uint8_t* dq = q + r0 * C + c0;
+#pragma unroll
+    for (int i = 0; i < kPatchRows; ++i) *reinterpret_cast<v2u*>(dq + (int64_t)i * C) = v2u{wq[i][0], wq[i][1]};
+    tile_stage_transposed(wq, tr, tc, s_t);
+    __syncthreads();
+    tile_write_transposed(s_t, qt + (int64_t)bcol * kTileCols * qt_row_stride + (int64_t)brow * qt_band_stride, qt_row_stride);
+}
+
 template <int QFMT>
 __global__ __launch_bounds__(kRnThreads) void rmsnorm_apply_fp8_generic_kernel(
     const uint16_t* __restrict__ res, const uint16_t* __restrict__ w, const float* __restrict__ rstd,
@@ -267,12 +310,23 @@ int launch_rmsnorm_fwd(const void* res_, const void* x_, const void* w_, int64_t
     return launch_amax_final(partial, (int)rmsnorm_blocks(M), fmt, d_amax, d_scale, stream);
 }
 
+static bool use_tile_kernel() {       // LLMQ_FUSED_TILE=0 (tuning override): patch kernels also for whole tiles
+    if (const char* e = tuning_env("LLMQ_FUSED_TILE")) return atoi(e) != 0;
+    return true;
+}
+
 template <int QFMT>
 static void launch_apply(const uint16_t* res, const uint16_t* w, const float* rstd, int64_t M, int64_t C,
-                         const float* d_qscale, uint8_t* q, uint8_t* q_t, uint16_t* y, hipStream_t stream) {
+                         const float* d_qscale, uint8_t* q, uint8_t* q_t, uint16_t* y, hipStream_t stream,
+                         bool qt_slabs) {
     const dim3 block(kRnThreads);
     const unsigned gc = (unsigned)((C + kRnBlockCols - 1) / kRnBlockCols);
-    if (q_t && M % 16 == 0 && C % 8 == 0) {
+    if (q_t && tile_shape_ok(M, C) && (qt_slabs || use_tile_kernel())) {
+        const unsigned tr = (unsigned)(M / kTileRows), tcn = (unsigned)(C / kTileCols);
+        const int64_t row_stride = qt_slabs ? kTileRows : M, band_stride = qt_slabs ? C * kTileRows : kTileRows;
+        if (y) hipLaunchKernelGGL((rmsnorm_apply_fp8_tile_kernel<QFMT, true>), dim3(tr * tcn), dim3(kTileThreads), 0, stream, res, w, rstd, M, C, d_qscale, q, q_t, y, tcn, row_stride, band_stride);
+        else hipLaunchKernelGGL((rmsnorm_apply_fp8_tile_kernel<QFMT, false>), dim3(tr * tcn), dim3(kTileThreads), 0, stream, res, w, rstd, M, C, d_qscale, q, q_t, y, tcn, row_stride, band_stride);
+    } else if (q_t && M % 16 == 0 && C % 8 == 0) {
         const dim3 grid((unsigned)((M + 16 * kRnLanesR - 1) / (16 * kRnLanesR)) * gc);
         if (y) hipLaunchKernelGGL((rmsnorm_apply_fp8_patch_kernel<16, QFMT, true, true>), grid, block, 0, stream, res, w, rstd, M, C, d_qscale, q, q_t, y, gc);
         else hipLaunchKernelGGL((rmsnorm_apply_fp8_patch_kernel<16, QFMT, true, false>), grid, block, 0, stream, res, w, rstd, M, C, d_qscale, q, q_t, y, gc);
@@ -288,11 +342,13 @@ static void launch_apply(const uint16_t* res, const uint16_t* w, const float* rs
 }
 
 int launch_rmsnorm_apply_fp8(const void* res, const void* w, const float* rstd, int64_t M, int64_t C,
-                             const float* d_qscale, int fmt, uint8_t* q, uint8_t* q_t, void* y, hipStream_t stream) {
+                             const float* d_qscale, int fmt, uint8_t* q, uint8_t* q_t, void* y, hipStream_t stream,
+                             bool qt_slabs) {
     const uint16_t* r = reinterpret_cast<const uint16_t*>(res);
     const uint16_t* wp = reinterpret_cast<const uint16_t*>(w);
-    if (fmt == 0) launch_apply<0>(r, wp, rstd, M, C, d_qscale, q, q_t, reinterpret_cast<uint16_t*>(y), stream);
-    else launch_apply<1>(r, wp, rstd, M, C, d_qscale, q, q_t, reinterpret_cast<uint16_t*>(y), stream);
+    if (qt_slabs && !(q_t && tile_shape_ok(M, C))) return -2;
+    if (fmt == 0) launch_apply<0>(r, wp, rstd, M, C, d_qscale, q, q_t, reinterpret_cast<uint16_t*>(y), stream, qt_slabs);
+    else launch_apply<1>(r, wp, rstd, M, C, d_qscale, q, q_t, reinterpret_cast<uint16_t*>(y), stream, qt_slabs);
     return hipGetLastError() == hipSuccess ? 0 : -6;
 }
 

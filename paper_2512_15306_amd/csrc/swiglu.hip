@@ -17,6 +17,8 @@
 // fused multiply-adds written out) so that the stored bits can be reproduced anywhere:
 //   a = -min(max(g,-100),86); n = rint(a*LOG2E); r = fma(n,-LN2_HI,a); r = fma(n,-LN2_LO,r);
 //   p = Horner of 1 + r + r^2/2 + ... + r^6/720; e = p * 2^n; sg = 1 / (1 + e); h = (g*sg)*u.
+#include <stdlib.h>
+
 #include "llmq_device.h"
 #include "llmq_kernels.h"
 
@@ -181,6 +183,51 @@ __global__ __launch_bounds__(kSwThreads) void swiglu_fwd_patch_kernel(
     }
 }
 
+// FP8 codes in both layouts for tensors made of whole 128 x 256 tiles (every benchmark shape): the lane geometry
+// and the LDS transpose of the quantize kernel's tile variant, so that all four streams (g, u, q, q_t) move in
+// full 128-byte lines, and the transposed copy can be written in slabs.  The 16 rows of a patch are loaded and
+// converted in two groups of eight (sixteen 16-byte loads in flight per lane).
+template <bool WRITE_H, int QFMT>
+__global__ __launch_bounds__(kTileThreads) void swiglu_fwd_tile_kernel(
+    const uint16_t* __restrict__ gu, int64_t M, int64_t I, uint16_t* __restrict__ h,
+    const float* __restrict__ d_qscale, uint8_t* __restrict__ q, uint8_t* __restrict__ qt, unsigned grid_cols,
+    int64_t qt_row_stride, int64_t qt_band_stride) {
+    __shared__ __attribute__((aligned(16))) uint8_t s_t[kTileLdsBytes];
+    const unsigned brow = blockIdx.x / grid_cols, bcol = blockIdx.x - brow * grid_cols;   // along the columns first
+    int tr, tc;
+    tile_patch_origin(tr, tc);
+    const int64_t r0 = (int64_t)brow * kTileRows + tr, c0 = (int64_t)bcol * kTileCols + tc;
+    const uint16_t* src = gu + r0 * (2 * I) + c0;
+    const float s = *d_qscale;
+    constexpr int kGroup = 8;
+    unsigned w[kPatchRows][2];
+#pragma unroll
+    for (int i0 = 0; i0 < kPatchRows; i0 += kGroup) {
+        v4u g[kGroup], u[kGroup], o[kGroup];
+#pragma unroll
+        for (int i = 0; i < kGroup; ++i) {
+            g[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(src + (int64_t)(i0 + i) * 2 * I));
+            u[i] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(src + (int64_t)(i0 + i) * 2 * I + I));
+        }
+#pragma unroll
+        for (int i = 0; i < kGroup; ++i) o[i] = swiglu8(g[i], u[i]);
+        if constexpr (WRITE_H) {
+            uint16_t* dst = h + (r0 + i0) * I + c0;
+#pragma unroll
+            for (int i = 0; i < kGroup; ++i) *reinterpret_cast<v4u*>(dst + (int64_t)i * I) = o[i];
+        }
+#pragma unroll
+        for (int i = 0; i < kGroup; ++i) quantize8<QFMT>(o[i], s, w[i0 + i][0], w[i0 + i][1]);
+        uint8_t* dq = q + (r0 + i0) * I + c0;
+#pragma unroll
+        for (int i = 0; i < kGroup; ++i) *reinterpret_cast<v2u*>(dq + (int64_t)i * I) = v2u{w[i0 + i][0], w[i0 + i][1]};
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    tile_stage_transposed(w, tr, tc, s_t);
+    __syncthreads();
+    tile_write_transposed(s_t, qt + (int64_t)bcol * kTileCols * qt_row_stride + (int64_t)brow * qt_band_stride, qt_row_stride);
+}
+
 // Backward: dh [M, I], GU [M, 2I] -> dGU [M, 2I], one partial absmax per workgroup.  M % 4 == 0, I % 8 == 0.
 __global__ __launch_bounds__(kSwThreads) void swiglu_bwd_patch_kernel(
     const uint16_t* __restrict__ dh, const uint16_t* __restrict__ gu, int64_t M, int64_t I,
@@ -309,10 +356,23 @@ static void launch_fwd_patch(const uint16_t* gu, int64_t M, int64_t I, uint16_t*
                        gu, M, I, h, partial, d_qscale, q, q_t, gc);
 }
 
+// LLMQ_FUSED_TILE=0 (tuning override, also read by the RMSNorm recompute launch): the register-only patch kernels
+// also for tensors made of whole tiles.
+static bool use_tile_kernel() {
+    if (const char* e = tuning_env("LLMQ_FUSED_TILE")) return atoi(e) != 0;
+    return true;
+}
+
 template <int QFMT>
-static void launch_fwd_fp8(const uint16_t* gu, int64_t M, int64_t I, uint16_t* h, const float* d_qscale,
-                           uint8_t* q, uint8_t* q_t, hipStream_t stream) {
-    if (q_t && patch_ok(M, I, 16)) {
+static int launch_fwd_fp8(const uint16_t* gu, int64_t M, int64_t I, uint16_t* h, const float* d_qscale,
+                          uint8_t* q, uint8_t* q_t, hipStream_t stream, bool qt_slabs) {
+    if (qt_slabs && !(q_t && tile_shape_ok(M, I))) return -2;
+    if (q_t && tile_shape_ok(M, I) && (qt_slabs || use_tile_kernel())) {
+        const unsigned gr = (unsigned)(M / kTileRows), gc = (unsigned)(I / kTileCols);
+        const int64_t row_stride = qt_slabs ? kTileRows : M, band_stride = qt_slabs ? I * kTileRows : kTileRows;
+        if (h) hipLaunchKernelGGL((swiglu_fwd_tile_kernel<true, QFMT>), dim3(gr * gc), dim3(kTileThreads), 0, stream, gu, M, I, h, d_qscale, q, q_t, gc, row_stride, band_stride);
+        else hipLaunchKernelGGL((swiglu_fwd_tile_kernel<false, QFMT>), dim3(gr * gc), dim3(kTileThreads), 0, stream, gu, M, I, h, d_qscale, q, q_t, gc, row_stride, band_stride);
+    } else if (q_t && patch_ok(M, I, 16)) {
         if (h) launch_fwd_patch<16, true, false, QFMT, true>(gu, M, I, h, nullptr, d_qscale, q, q_t, stream);
         else launch_fwd_patch<16, false, false, QFMT, true>(gu, M, I, h, nullptr, d_qscale, q, q_t, stream);
     } else if (!q_t && patch_ok(M, I, 4)) {
@@ -322,18 +382,21 @@ static void launch_fwd_fp8(const uint16_t* gu, int64_t M, int64_t I, uint16_t* h
         hipLaunchKernelGGL((swiglu_fwd_generic_kernel<QFMT>), dim3((unsigned)generic_blocks(M, I)), dim3(kSwThreads), 0,
                            stream, gu, M, I, h, (unsigned*)nullptr, d_qscale, q, q_t);
     }
+    return 0;
 }
 
 int launch_swiglu_fwd(const void* gu_, int64_t M, int64_t I, void* h_, unsigned* partial, int amax_fmt,
                       float* d_amax, float* d_scale, const float* d_qscale, int q_fmt, uint8_t* q, uint8_t* q_t,
-                      hipStream_t stream) {
+                      hipStream_t stream, bool qt_slabs) {
     const uint16_t* gu = reinterpret_cast<const uint16_t*>(gu_);
     uint16_t* h = reinterpret_cast<uint16_t*>(h_);
     if (q) {                                   // absmax known: FP8 bytes directly, h optional
-        if (q_fmt == 0) launch_fwd_fp8<0>(gu, M, I, h, d_qscale, q, q_t, stream);
-        else launch_fwd_fp8<1>(gu, M, I, h, d_qscale, q, q_t, stream);
+        const int st = q_fmt == 0 ? launch_fwd_fp8<0>(gu, M, I, h, d_qscale, q, q_t, stream, qt_slabs)
+                                  : launch_fwd_fp8<1>(gu, M, I, h, d_qscale, q, q_t, stream, qt_slabs);
+        if (st != 0) return st;
         return hipGetLastError() == hipSuccess ? 0 : -6;
     }
+    if (qt_slabs) return -2;
     int64_t n_partial;
     if (patch_ok(M, I, 8)) {                   // 8 rows per lane: more bytes in flight, half the partial results
         launch_fwd_patch<8, true, true, -1, false>(gu, M, I, h, partial, nullptr, nullptr, nullptr, stream);

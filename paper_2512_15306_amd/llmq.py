@@ -31,8 +31,8 @@ _lib = None
 EXPORTS = ["llmq_status_string", "llmq_version", "llmq_amax_workspace_bytes", "llmq_amax", "llmq_amax_static", "llmq_quantize_fp8", "llmq_quantize_fp8_slabs", "llmq_fp8_gemm_tn", "llmq_fp8_gemm", "llmq_fp8_gemm_scratch_bytes", "llmq_fp8_gemm_with_scratch", "llmq_bf16_gemm_tn",
            "llmq_fp8_linear_workspace_bytes", "llmq_fp8_linear_workspace_bytes_no_transpose", "llmq_fp8_linear_workspace_bytes_shared", "llmq_fp8_linear_workspace_offsets",
            "llmq_fp8_linear_fwd", "llmq_fp8_linear_dgrad", "llmq_fp8_linear_wgrad",
-           "llmq_scale_from_amax", "llmq_swiglu_workspace_bytes", "llmq_swiglu_fwd", "llmq_swiglu_fwd_fp8",
-           "llmq_swiglu_bwd", "llmq_rmsnorm_workspace_bytes", "llmq_rmsnorm_fwd", "llmq_rmsnorm_apply_fp8",
+           "llmq_scale_from_amax", "llmq_swiglu_workspace_bytes", "llmq_swiglu_fwd", "llmq_swiglu_fwd_fp8", "llmq_swiglu_fwd_fp8_slabs",
+           "llmq_swiglu_bwd", "llmq_rmsnorm_workspace_bytes", "llmq_rmsnorm_fwd", "llmq_rmsnorm_apply_fp8", "llmq_rmsnorm_apply_fp8_slabs",
            "llmq_calibrate_mfma", "llmq_calibrate_copy", "llmq_calibrate_gemm_phases_bytes", "llmq_calibrate_gemm_phases"]
 
 
@@ -99,6 +99,8 @@ def lib() -> ctypes.CDLL:
     L.llmq_swiglu_fwd.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp, sz, vp]
     L.llmq_swiglu_fwd_fp8.restype = i32
     L.llmq_swiglu_fwd_fp8.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp, vp]
+    L.llmq_swiglu_fwd_fp8_slabs.restype = i32
+    L.llmq_swiglu_fwd_fp8_slabs.argtypes = [vp, i64, i64, vp, i32, vp, vp, vp, vp]
     L.llmq_swiglu_bwd.restype = i32
     L.llmq_swiglu_bwd.argtypes = [vp, vp, i64, i64, vp, i32, vp, vp, vp, sz, vp]
     L.llmq_rmsnorm_workspace_bytes.restype = sz
@@ -107,6 +109,8 @@ def lib() -> ctypes.CDLL:
     L.llmq_rmsnorm_fwd.argtypes = [vp, vp, vp, i64, i64, c.c_float, vp, vp, vp, i32, vp, vp, vp, sz, vp]
     L.llmq_rmsnorm_apply_fp8.restype = i32
     L.llmq_rmsnorm_apply_fp8.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, vp, vp, vp]
+    L.llmq_rmsnorm_apply_fp8_slabs.restype = i32
+    L.llmq_rmsnorm_apply_fp8_slabs.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, vp, vp, vp]
     L.llmq_calibrate_mfma.restype = i32
     L.llmq_calibrate_mfma.argtypes = [i32, i32, i32, i32, vp, c.POINTER(c.c_double), vp]
     L.llmq_calibrate_gemm_phases_bytes.restype = sz
@@ -336,6 +340,16 @@ def llmq_swiglu_fwd_fp8(gu: torch.Tensor, d_scale_h: torch.Tensor, fmt: int, q: 
                                      _dev(h, torch.bfloat16, "h"), _stream()), "llmq_swiglu_fwd_fp8")
 
 
+def llmq_swiglu_fwd_fp8_slabs(gu: torch.Tensor, d_scale_h: torch.Tensor, fmt: int, q: torch.Tensor,
+                              q_t: torch.Tensor, h: Optional[torch.Tensor] = None) -> None:
+    M, I = _swiglu_dims(gu)
+    if q.numel() != M * I or q_t.numel() != M * I or (h is not None and h.numel() != M * I):
+        raise ValueError("output size does not match [M, I]")
+    _check(lib().llmq_swiglu_fwd_fp8_slabs(_dev(gu, torch.bfloat16, "gu"), M, I, _dev(d_scale_h, torch.float32, "d_scale_h"),
+                                           fmt, _dev(q, torch.uint8, "q"), _dev(q_t, torch.uint8, "q_t"),
+                                           _dev(h, torch.bfloat16, "h"), _stream()), "llmq_swiglu_fwd_fp8_slabs")
+
+
 def llmq_swiglu_bwd(dh: torch.Tensor, gu: torch.Tensor, dgu: torch.Tensor, fmt: int, d_amax_dgu: torch.Tensor,
                     d_scale_dgu: Optional[torch.Tensor], ws: torch.Tensor) -> None:
     M, I = _swiglu_dims(gu)
@@ -375,6 +389,19 @@ def llmq_rmsnorm_apply_fp8(res: torch.Tensor, w: torch.Tensor, rstd: torch.Tenso
                                         _dev(rstd, torch.float32, "rstd"), M, C, _dev(d_scale_y, torch.float32, "d_scale_y"),
                                         fmt, _dev(q, torch.uint8, "q"), _dev(q_t, torch.uint8, "q_t"),
                                         _dev(y, torch.bfloat16, "y"), _stream()), "llmq_rmsnorm_apply_fp8")
+
+
+def llmq_rmsnorm_apply_fp8_slabs(res: torch.Tensor, w: torch.Tensor, rstd: torch.Tensor, d_scale_y: torch.Tensor,
+                                 fmt: int, q: torch.Tensor, q_t: torch.Tensor, y: Optional[torch.Tensor] = None) -> None:
+    M, C = res.shape
+    if w.numel() != C or rstd.numel() != M or q.numel() != M * C or q_t.numel() != M * C or \
+            (y is not None and y.numel() != M * C):
+        raise ValueError("shape mismatch")
+    _check(lib().llmq_rmsnorm_apply_fp8_slabs(_dev(res, torch.bfloat16, "res"), _dev(w, torch.bfloat16, "w"),
+                                              _dev(rstd, torch.float32, "rstd"), M, C,
+                                              _dev(d_scale_y, torch.float32, "d_scale_y"), fmt, _dev(q, torch.uint8, "q"),
+                                              _dev(q_t, torch.uint8, "q_t"), _dev(y, torch.bfloat16, "y"), _stream()),
+           "llmq_rmsnorm_apply_fp8_slabs")
 
 
 def llmq_calibrate_mfma(fmtA: int, fmtB: int, random_bits: bool, iters: int, d_sink: torch.Tensor) -> float:

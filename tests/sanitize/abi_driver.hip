@@ -27,11 +27,11 @@ int launch_gemm_fp8(const uint8_t*, int, int, const uint8_t*, int, int, int64_t,
 int gemm_phase_stamp_blocks(int64_t R, int64_t C) { return (int)((R / 256) * (C / 256)); }
 int launch_gemm_phase_stamps(const uint8_t*, const uint8_t*, int64_t, int64_t, int64_t, const float*, const float*, void*, float*, long long*, int, hipStream_t, int) { ++g_launches; return 0; }
 int64_t swiglu_blocks(int64_t M, int64_t I) { return (M + 31) / 32 * ((I + 255) / 256); }
-int launch_swiglu_fwd(const void*, int64_t, int64_t, void*, unsigned*, int, float*, float*, const float*, int, uint8_t*, uint8_t*, hipStream_t) { ++g_launches; return 0; }
+int launch_swiglu_fwd(const void*, int64_t, int64_t, void*, unsigned*, int, float*, float*, const float*, int, uint8_t*, uint8_t*, hipStream_t, bool) { ++g_launches; return 0; }
 int launch_swiglu_bwd(const void*, const void*, int64_t, int64_t, void*, unsigned*, int, float*, float*, hipStream_t) { ++g_launches; return 0; }
 int64_t rmsnorm_blocks(int64_t M) { return (M + 3) / 4; }
 int launch_rmsnorm_fwd(const void*, const void*, const void*, int64_t, int64_t, float, void*, void*, float*, unsigned*, int, float*, float*, hipStream_t) { ++g_launches; return 0; }
-int launch_rmsnorm_apply_fp8(const void*, const void*, const float*, int64_t, int64_t, const float*, int, uint8_t*, uint8_t*, void*, hipStream_t) { ++g_launches; return 0; }
+int launch_rmsnorm_apply_fp8(const void*, const void*, const float*, int64_t, int64_t, const float*, int, uint8_t*, uint8_t*, void*, hipStream_t, bool) { ++g_launches; return 0; }
 int launch_calibrate_mfma(int, int, int, int, float*, hipStream_t, int) { ++g_launches; return 0; }
 int launch_calibrate_copy(const void*, void*, size_t, hipStream_t) { ++g_launches; return 0; }
 }  // namespace llmq
@@ -108,6 +108,9 @@ int main() {
     EXPECT(llmq_swiglu_fwd(P, 64, 256, P, 0, F, F, P, llmq_swiglu_workspace_bytes(64, 256), nullptr), LLMQ_OK, 1);
     EXPECT(llmq_swiglu_fwd(P, 64, 256, P, 0, F, F, P, 0, nullptr), LLMQ_ERR_WORKSPACE, 0);
     EXPECT(llmq_swiglu_fwd_fp8(P, 64, 256, F, 0, B8, B8, nullptr, nullptr), LLMQ_OK, 1);
+    EXPECT(llmq_swiglu_fwd_fp8_slabs(P, 128, 256, F, 0, B8, B8, nullptr, nullptr), LLMQ_OK, 1);
+    EXPECT(llmq_swiglu_fwd_fp8_slabs(P, 64, 256, F, 0, B8, B8, nullptr, nullptr), LLMQ_ERR_SHAPE, 0);     // whole 128 x 256 tiles only
+    EXPECT(llmq_swiglu_fwd_fp8_slabs(P, 128, 256, F, 0, B8, nullptr, nullptr, nullptr), LLMQ_ERR_NULL, 0);
     EXPECT(llmq_swiglu_bwd(P, P, 64, (int64_t)1 << 24, P, 1, F, F, P, 1 << 20, nullptr), LLMQ_ERR_SHAPE, 0);
     EXPECT(llmq_swiglu_bwd(P, P, 64, 256, P, 1, F, F, P, llmq_swiglu_workspace_bytes(64, 256), nullptr), LLMQ_OK, 1);
     EXPECT(llmq_rmsnorm_fwd(P, P, P, 32, 384, 1e-6f, P, P, F, 0, F, F, P, llmq_rmsnorm_workspace_bytes(32), nullptr), LLMQ_OK, 1);
@@ -115,6 +118,9 @@ int main() {
     EXPECT(llmq_rmsnorm_fwd(P, P, P, 32, 384, 1e-6f, nullptr, P, F, 0, F, F, P, llmq_rmsnorm_workspace_bytes(32), nullptr), LLMQ_ERR_NULL, 0);
     EXPECT(llmq_rmsnorm_apply_fp8(P, P, F, 32, 384, F, 0, B8, B8, nullptr, nullptr), LLMQ_OK, 1);
     EXPECT(llmq_rmsnorm_apply_fp8(P, P, F + 1, 32, 384, F, 0, B8, B8, nullptr, nullptr), LLMQ_ERR_ALIGN, 0);   // rstd: 16-byte aligned
+    EXPECT(llmq_rmsnorm_apply_fp8_slabs(P, P, F, 128, 512, F, 0, B8, B8, nullptr, nullptr), LLMQ_OK, 1);
+    EXPECT(llmq_rmsnorm_apply_fp8_slabs(P, P, F, 128, 384, F, 0, B8, B8, nullptr, nullptr), LLMQ_ERR_SHAPE, 0);
+    EXPECT(llmq_rmsnorm_apply_fp8_slabs(P, P, F, 128, 512, F, 0, B8, nullptr, nullptr, nullptr), LLMQ_ERR_NULL, 0);
     double flops = 0;
     EXPECT(llmq_calibrate_mfma(0, 1, 1, 100, F, &flops, nullptr), LLMQ_OK, 1);
     EXPECT(llmq_calibrate_mfma(0, 1, 1, 0, F, &flops, nullptr), LLMQ_ERR_SHAPE, 0);

@@ -136,6 +136,12 @@ def test_argument_errors_of_the_producer_and_baseline_entry_points():
     assert L.llmq_swiglu_fwd_fp8(ok, 64, 256, ok, 0, None, ok, None, None) == -1
     assert L.llmq_swiglu_fwd_fp8(ok, 64, 256, ok, 5, ok, ok, None, None) == -4
     assert L.llmq_swiglu_fwd_fp8(ok, 64, 256, ok, 0, ok, odd, None, None) == -3
+    assert L.llmq_swiglu_fwd_fp8_slabs(ok, 128, 256, ok, 0, ok, None, None, None) == -1           # q_t is required
+    assert L.llmq_swiglu_fwd_fp8_slabs(ok, 64, 256, ok, 0, ok, ok, None, None) == -2              # whole 128 x 256 tiles only
+    assert L.llmq_swiglu_fwd_fp8_slabs(ok, 128, 264, ok, 0, ok, ok, None, None) == -2
+    assert L.llmq_swiglu_fwd_fp8_slabs(ok, 1 << 17, 1 << 14, ok, 0, ok, ok, None, None) == -2     # 2^31 elements: not kept in slabs
+    assert L.llmq_swiglu_fwd_fp8_slabs(ok, 128, 256, ok, 5, ok, ok, None, None) == -4
+    assert L.llmq_swiglu_fwd_fp8_slabs(ok, 128, 256, ok, 0, ok, odd, None, None) == -3
     assert L.llmq_swiglu_bwd(ok, None, 64, 256, ok, 1, ok, ok, ok, n(sw), None) == -1
     assert L.llmq_swiglu_bwd(ok, ok, -1, 256, ok, 1, ok, ok, ok, n(sw), None) == -2
     assert L.llmq_swiglu_bwd(ok, ok, 64, 256, ok, 1, ok, ok, ok, n(0), None) == -5
@@ -152,6 +158,11 @@ def test_argument_errors_of_the_producer_and_baseline_entry_points():
     assert L.llmq_rmsnorm_apply_fp8(ok, ok, None, 64, 256, ok, 0, ok, ok, None, None) == -1
     assert L.llmq_rmsnorm_apply_fp8(ok, ok, odd, 64, 256, ok, 0, ok, ok, None, None) == -3        # rstd: 16-byte aligned
     assert L.llmq_rmsnorm_apply_fp8(ok, ok, ok, 64, 256, ok, 9, ok, ok, None, None) == -4
+    assert L.llmq_rmsnorm_apply_fp8_slabs(ok, ok, ok, 128, 256, ok, 0, ok, None, None, None) == -1
+    assert L.llmq_rmsnorm_apply_fp8_slabs(ok, ok, ok, 64, 256, ok, 0, ok, ok, None, None) == -2
+    assert L.llmq_rmsnorm_apply_fp8_slabs(ok, ok, ok, 128, 384, ok, 0, ok, ok, None, None) == -2
+    assert L.llmq_rmsnorm_apply_fp8_slabs(ok, ok, odd, 128, 256, ok, 0, ok, ok, None, None) == -3
+    assert L.llmq_rmsnorm_apply_fp8_slabs(ok, ok, ok, 128, 256, ok, 7, ok, ok, None, None) == -4
     assert L.llmq_scale_from_amax(None, 0, ok, None) == -1
     assert L.llmq_scale_from_amax(ok, 4, ok, None) == -4
     assert L.llmq_scale_from_amax(ok, 0, ok + 2, None) == -3

@@ -16,7 +16,7 @@ EPS = 1e-6
 RSTD_TOL = 2.0 ** -20            # binary32 sum of <= 8192 squares by lanes + butterfly, division, root, division
 # forward shapes: single-pass kernel (C % 8 == 0, C <= 8192), rows not filling a workgroup, generic C
 FWD_SHAPES = [(8, 64), (5, 264), (64, 3072), (16, 8192), (130, 5120), (33, 17), (1, 1), (6, 8200), (3, 100)]
-APPLY_SHAPES = [(32, 256), (64, 264), (16, 8), (36, 40), (4, 8), (33, 17), (1, 1), (48, 1032), (256, 3584)]
+APPLY_SHAPES = [(32, 256), (64, 264), (16, 8), (36, 40), (4, 8), (33, 17), (1, 1), (48, 1032), (256, 3584), (128, 256), (384, 768)]
 
 
 def _bits_of(t):

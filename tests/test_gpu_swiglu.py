@@ -10,8 +10,10 @@ from gpu_common import DEV, f32_bits, np_f32_bits, gpu_amax, gpu_quantize
 
 pytestmark = pytest.mark.gpu
 
-# (M, I): tuned patches (M % 4 == 0, I % 8 == 0; with q_t M % 16 == 0), partial column blocks, generic shapes
-SHAPES = [(32, 256), (64, 264), (128, 512), (36, 40), (16, 8), (4, 8), (33, 17), (1, 1), (7, 24), (48, 1032), (260, 768)]
+# (M, I): tuned patches (M % 4 == 0, I % 8 == 0; with q_t M % 16 == 0), partial column blocks, generic shapes,
+# whole 128 x 256 tiles (their own kernel when q_t is written)
+SHAPES = [(32, 256), (64, 264), (128, 512), (36, 40), (16, 8), (4, 8), (33, 17), (1, 1), (7, 24), (48, 1032), (260, 768),
+          (128, 256), (384, 768)]
 
 
 def _case(M, I, seed, gstd=2.0, ustd=1.5, dstd=1e-3):
