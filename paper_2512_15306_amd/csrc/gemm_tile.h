@@ -56,14 +56,14 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes
 
 // Workgroup id -> position in a walk of n items, XCD-aware: the hardware deals workgroup ids round-robin to
 // the XCDs, and every XCD gets a contiguous range of positions.  -1 for the padding ids.
-__device__ inline int walk_position(int pid, int n) {
+__host__ __device__ inline int walk_position(int pid, int n) {
     const int per_xcd = (n + kXcds - 1) / kXcds;
     const int pos = (pid % kXcds) * per_xcd + pid / kXcds;
     return pos < n ? pos : -1;
 }
 
 // Position in the walk of tiles -> output tile: bands band_rows tile rows high, walked down the rows first.
-__device__ inline void tile_of_position(int pos, int tiles_r, int tiles_c, int band_rows, int& tr, int& tc) {
+__host__ __device__ inline void tile_of_position(int pos, int tiles_r, int tiles_c, int band_rows, int& tr, int& tc) {
     const int band = band_rows * tiles_c;
     const int first = (pos / band) * band_rows;
     const int h = tiles_r - first < band_rows ? tiles_r - first : band_rows;
