@@ -96,6 +96,19 @@ __device__ inline float resolve_scale(const ScaleSource& src, bool first_block, 
     return s;
 }
 
+// Workgroup id -> block (brow, bcol) of a grid of grid_rows x grid_cols blocks: bands of `band` block columns
+// (1 <= band <= grid_cols, so that band * grid_rows stays within the grid size, which fits 32 bits), walked down
+// the rows, `band` neighbouring blocks of a row one after the other; the last band takes the columns that are
+// left.  band = 1: down the rows; band = grid_cols: along the columns.
+__host__ __device__ inline void band_walk(unsigned id, unsigned grid_rows, unsigned grid_cols, unsigned band,
+                                          unsigned& brow, unsigned& bcol) {
+    const unsigned band_first = (id / (band * grid_rows)) * band;
+    const unsigned band_width = grid_cols - band_first < band ? grid_cols - band_first : band;
+    const unsigned in_band = id - band_first * grid_rows;
+    brow = in_band / band_width;
+    bcol = band_first + in_band % band_width;
+}
+
 // ---- FP8 cast helpers (used by the quantize kernel and by the producers that emit FP8 directly) ----
 
 template <int FMT>

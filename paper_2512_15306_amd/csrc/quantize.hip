@@ -46,11 +46,8 @@ __global__ __launch_bounds__(kQThreads) void quantize_patch_kernel(
     // neighbouring blocks of a row one after the other.  Workgroups in flight together then read runs of
     // band * 512 bytes of a row and write runs of the transposed tensor's rows that keep growing as the walk
     // moves down (band = 1: plain walk down the rows; band >= grid_cols: along the columns).
-    const unsigned band_first = (blockIdx.x / (band * grid_rows)) * band;
-    const unsigned band_width = grid_cols - band_first < band ? grid_cols - band_first : band;
-    const unsigned in_band = blockIdx.x - band_first * grid_rows;
-    const unsigned brow = in_band / band_width;
-    const unsigned bcol = band_first + in_band % band_width;
+    unsigned brow, bcol;
+    band_walk(blockIdx.x, grid_rows, grid_cols, band, brow, bcol);
     constexpr int PC = V::kPatchCols, LR = V::kLanesR, LC = kWave / LR;
     constexpr int NV = PC / 8;                              // 16-byte loads per row of the patch
     constexpr int kWaveRows = kPatchRows * LR, kWaveCols = PC * LC;

@@ -1,6 +1,6 @@
 // Host-side brute force over the index arithmetic of the tile kernel's launches, under the sanitizers: the walk
-// of the workgroup ids over the tiles, and the planner that shares a ragged last round of tiles among the compute
-// units.  Every tile, and every K step of every shared tile, must be computed exactly once, and every partial
+// of the workgroup ids over the tiles, the planner that shares a ragged last round of tiles among the compute
+// units, and the walk of the quantize kernel's workgroups over the blocks of its tensor.  Every tile, and every K step of every shared tile, must be computed exactly once, and every partial
 // result must have a slot of its own inside the scratch the plan asks for.
 #include <stdio.h>
 #include <stdlib.h>
@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "../../paper_2512_15306_amd/csrc/gemm_tile.h"
+#include "../../paper_2512_15306_amd/csrc/llmq_device.h"
 
 using namespace llmq;
 
@@ -46,6 +47,23 @@ static void check_tiles(int tiles_r, int tiles_c, int band) {
         if (tr >= 0 && tr < tiles_r && tc >= 0 && tc < tiles_c) ++seen[tr * tiles_c + tc];
     }
     for (int t = 0; t < nt; ++t) CHECK(seen[t] == 1, "%d x %d band %d: tile %d computed %d times", tiles_r, tiles_c, band, t, seen[t]);
+}
+
+// The walk of the quantize kernel's workgroups over the blocks of its tensor (band_walk): a bijection, also for the
+// grids of very tall tensors, where band x grid_rows comes close to 2^32.
+static void check_bands(unsigned gr, unsigned gc, unsigned band) {
+    if (band > gc) band = gc;                      // as the launcher does
+    const unsigned long long n = (unsigned long long)gr * gc;
+    std::vector<unsigned char> seen(n, 0);
+    for (unsigned long long id = 0; id < n; ++id) {
+        unsigned br = ~0u, bc = ~0u;
+        band_walk((unsigned)id, gr, gc, band, br, bc);
+        CHECK(br < gr && bc < gc, "grid %u x %u band %u: id %llu -> (%u, %u)", gr, gc, band, id, br, bc);
+        if (br < gr && bc < gc) {
+            CHECK(seen[(size_t)br * gc + bc] == 0, "grid %u x %u band %u: block (%u, %u) twice", gr, gc, band, br, bc);
+            seen[(size_t)br * gc + bc] = 1;
+        }
+    }
 }
 
 // Replays what the three launches of a contraction do with the plan, as the kernel's prologue does.
@@ -115,6 +133,15 @@ int main() {
         for (int c = 1; c <= 220; c += (c < 10 ? 1 : 23))
             for (int b : bands) check_tiles(r, c, b);
     check_tiles(64, 216, 4);
+    const unsigned band_sizes[] = {1, 2, 3, 7, 16, 1u << 20};
+    for (unsigned gr : {1u, 2u, 5u, 64u, 130u})
+        for (unsigned gc : {1u, 2u, 3u, 14u, 20u, 33u})
+            for (unsigned b : band_sizes) check_bands(gr, gc, b);
+    for (unsigned b : band_sizes) {
+        check_bands(4096, 20, b);                  // 524288 rows: 2^20 x 4096 would wrap to 0 without the clamp
+        check_bands(3 * 4096 + 1, 7, b);
+        check_bands(1u << 20, 2, b);               // 2^27 rows
+    }
     const char* modes[] = {nullptr, "1", "a2", "a3", "a5", "a16", "0"};
     const int nks[] = {1, 2, 7, 8, 15, 16, 28, 40, 63, 64, 65, 108, 128, 216, 432};
     const int slot_counts[] = {256, 64, 8};
