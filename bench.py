@@ -111,9 +111,11 @@ def run_step(states, prequantized_w, producer_absmax=False, extra_flags=None):
                                    extra_flags | llmq.REUSE_X | llmq.REUSE_DY)
 
 
-def run_gemms_only(states, extra_flags=None):
+def run_gemms_only(states, extra_flags=None, accumulate_dw=False):
     """The three GEMM launches of every linear on the operands the step left in the workspace, through
-    the same entry points as the step (all REUSE flags set: nothing is quantized)."""
+    the same entry points as the step (all REUSE flags set: nothing is quantized).  accumulate_dw: the weight
+    gradients are added to dW in BF16 (one rounding), as on every micro-step of a gradient accumulation but
+    the first."""
     from paper_2512_15306_amd import llmq
     if extra_flags is None:
         extra_flags = DEFAULT_LINEAR_FLAGS["flags"]
@@ -122,7 +124,7 @@ def run_gemms_only(states, extra_flags=None):
         llmq.llmq_fp8_linear_fwd(None, None, M, N, K, s.sx, s.sw, s.Y, None, s.ws, extra_flags | llmq.REUSE_X | llmq.REUSE_W)
         llmq.llmq_fp8_linear_dgrad(None, None, M, N, K, s.sd, s.sw, llmq.E5M2, s.dX, None, s.ws,
                                    extra_flags | llmq.REUSE_DY | llmq.REUSE_W)
-        llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, s.sd, s.sx, llmq.E5M2, s.dW, False, s.ws,
+        llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, s.sd, s.sx, llmq.E5M2, s.dW, accumulate_dw, s.ws,
                                    extra_flags | llmq.REUSE_X | llmq.REUSE_DY)
 
 
@@ -480,6 +482,9 @@ def measure_config(cfg, args, dev, full):
     if full:
         r["ms_fused"] = timed(lambda: run_step(states, args.prequantized_w, producer_absmax=True), reps)
         r["ms_qrow"] = timed(lambda: run_quantize_row_major_only(states), reps)
+        for s in states:
+            s.dW.zero_()                               # sums of a few dozen equal gradients stay finite in BF16
+        r["ms_gemm_acc"] = timed(lambda: run_gemms_only(states, accumulate_dw=True), reps)
         # the same step on row-major FP8 copies only (the backward GEMMs read them T-major): a side figure
         run_step(states, args.prequantized_w, extra_flags=llmq.NO_TRANSPOSE)       # first use loads those kernels
         r["ms_nt"] = timed(lambda: run_step(states, args.prequantized_w, extra_flags=llmq.NO_TRANSPOSE), reps)
@@ -571,6 +576,7 @@ def main():
         "step_tflops_with_producer_fused_absmax": round(flops / (r["ms_fused"] * 1e-3) / 1e12, 2),
         "step_tflops_without_transposed_copies": round(flops / (r["ms_nt"] * 1e-3) / 1e12, 2),
         "gemm_only_tflops_without_transposed_copies": round(flops / (r["ms_nt_gemm"] * 1e-3) / 1e12, 2),
+        "gemm_only_tflops_with_bf16_accumulation_of_dw": round(flops / (r["ms_gemm_acc"] * 1e-3) / 1e12, 2),
         "step_tflops_without_transposed_copies_with_producer_fused_absmax": round(flops / (r["ms_nt_fused"] * 1e-3) / 1e12, 2),
         "measured_peaks": peaks,
         "gemm_only_pct_measured_random_bits_peak": round(100.0 * gemm_tflops / peaks["mfma_fp8_random_bits_tflops"], 2),

@@ -127,7 +127,7 @@ const char* llmq_status_string(int status) {
     }
 }
 
-int llmq_version(void) { return 211; }
+int llmq_version(void) { return 212; }
 
 size_t llmq_amax_workspace_bytes(void) { return (size_t)llmq::kAmaxMaxPartials * sizeof(unsigned); }
 

@@ -742,25 +742,71 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_tile_kernel(
         }
         if constexpr (V::kProfile) stamp(4);
     } else {
-        // BF16 accumulation needs the old value before the single rounding: straight from the registers.
-        const int row_base = tr * BM + wr * 32 * NI + fr_row;
-        const int col_base = tc * BN + wc * 32 * NJ + fr_q * 4;
+        // BF16 accumulation: C = bf16(C + y), one rounding, so the old values are needed in binary32 arithmetic
+        // before the conversion.  The de-scaled binary32 results take the same way through LDS as the BF16
+        // values above (32 rows of the wave's quadrant at a time, 16 bytes per block and lane), so that the old
+        // values are loaded, and the sums stored, as full row segments of 16 bytes per lane as well; read and
+        // written 8 bytes per lane straight from the accumulator layout (32-byte runs of 16 rows per instruction)
+        // this epilogue took 15-20 % of a contraction of 64 K steps.  A staged row holds 4 NJ 16-byte pieces of
+        // BF16 output = 8 NJ units of four binary32 values: the first units of all pieces, then the second
+        // units; the piece index is rotated by the row number, which keeps the 16-byte writes of 8 rows and the
+        // 16-byte reads of 8 neighbouring pieces in different banks.
+        constexpr int kSlots = 4 * NJ;                                       // 16-byte pieces of output per row
+        constexpr int kPitch = 32 * kSlots;                                  // bytes of a staged binary32 row
+        uint8_t* stage = wave == 0 ? ldsA0 : wave == 1 ? ldsB0 : wave == 2 ? ldsA1 : ldsB1;
+        static_assert(32 * kPitch <= kSlabA && 32 * kPitch <= kSlabB - 16, "32 staged rows fit the start of any slab");
+        uint16_t* cbase = C + (size_t)(tr * BM + wr * 32 * NI) * Cn + tc * BN + wc * 32 * NJ;
+        constexpr int kPiecesPerLane = 32 * kSlots / kWave;
+        const int piece0 = fr_q >> 1, unit_off = (fr_q & 1) * (16 * kSlots);
 #pragma unroll
-        for (int i = 0; i < MI; ++i) {
-            uint16_t* crow = C + (size_t)(row_base + i * 16) * Cn + col_base;
+        for (int i = 0; i < NI; ++i) {
+            if constexpr (V::kEpilogueFence) __builtin_amdgcn_sched_barrier(0);
+            v4u old[kPiecesPerLane];               // requested first: their way from memory hides behind the staging
 #pragma unroll
-            for (int j = 0; j < MJ; ++j) {
-                uint16_t* dst = crow + j * 16;
-                v4f y = descale4(acc.get(i, j));
-                v2u old = *reinterpret_cast<const v2u*>(dst);
-                y[0] += __uint_as_float(old[0] << 16);
-                y[1] += __uint_as_float(old[0] & 0xFFFF0000u);
-                y[2] += __uint_as_float(old[1] << 16);
-                y[3] += __uint_as_float(old[1] & 0xFFFF0000u);
-                track4(y);
-                *reinterpret_cast<bf16x4*>(dst) = __builtin_convertvector(y, bf16x4);
+            for (int k = 0; k < kPiecesPerLane; ++k) {
+                const int p = lane + k * kWave;
+                const int r = i * 32 + p / kSlots, sl = p % kSlots;
+                old[k] = *reinterpret_cast<const v4u*>(cbase + (size_t)r * Cn + sl * 8);
+            }
+#pragma unroll
+            for (int ii = 0; ii < 2; ++ii) {
+                const int row = 16 * ii + fr_row;
+                uint8_t* srow = stage + row * kPitch + unit_off;
+#pragma unroll
+                for (int j = 0; j < MJ; ++j)
+                    *reinterpret_cast<v4f*>(srow + (((2 * j + piece0 + row) % kSlots) << 4)) = descale4(acc.get(2 * i + ii, j));
+            }
+            v4f lo[kPiecesPerLane], hi[kPiecesPerLane];
+#pragma unroll
+            for (int k = 0; k < kPiecesPerLane; ++k) {
+                const int p = lane + k * kWave;
+                const int r = p / kSlots, sl = p % kSlots;
+                const uint8_t* src = stage + r * kPitch + (((sl + r) % kSlots) << 4);
+                lo[k] = *reinterpret_cast<const v4f*>(src);
+                hi[k] = *reinterpret_cast<const v4f*>(src + 16 * kSlots);
+            }
+            if constexpr (V::kEpilogueFence) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < kPiecesPerLane; ++k) {
+                const int p = lane + k * kWave;
+                const int r = i * 32 + p / kSlots, sl = p % kSlots;
+                v4f y0 = lo[k], y1 = hi[k];
+                y0[0] += __uint_as_float(old[k][0] << 16);
+                y0[1] += __uint_as_float(old[k][0] & 0xFFFF0000u);
+                y0[2] += __uint_as_float(old[k][1] << 16);
+                y0[3] += __uint_as_float(old[k][1] & 0xFFFF0000u);
+                y1[0] += __uint_as_float(old[k][2] << 16);
+                y1[1] += __uint_as_float(old[k][2] & 0xFFFF0000u);
+                y1[2] += __uint_as_float(old[k][3] << 16);
+                y1[3] += __uint_as_float(old[k][3] & 0xFFFF0000u);
+                track4(y0);
+                track4(y1);
+                const bf16x4 o0 = __builtin_convertvector(y0, bf16x4), o1 = __builtin_convertvector(y1, bf16x4);
+                const v2u w0 = __builtin_bit_cast(v2u, o0), w1 = __builtin_bit_cast(v2u, o1);
+                *reinterpret_cast<v4u*>(cbase + (size_t)r * Cn + sl * 8) = v4u{w0[0], w0[1], w1[0], w1[1]};
             }
         }
+        if constexpr (V::kProfile) stamp(4);
     }
     };
     if (one_mul) {

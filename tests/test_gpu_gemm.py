@@ -118,6 +118,44 @@ def test_gemm_accumulate_in_bf16(R, C, T):
     assert np.all(np.abs(got - want) <= GEMM_TOL * S + 2.0 ** -8 * np.abs(want))
 
 
+def test_accumulation_is_one_rounding_of_the_exact_sum_in_every_tile_shape():
+    """Small-integer operands and power-of-two scales: the binary32 contraction, its de-scaling and the addition
+    of the old BF16 value are all exact, so `accumulate` must give RNE-to-BF16 of the exact sum, bit for bit,
+    whatever wave tile computes it (each has its own staging geometry in the epilogue), with the fused absmax that
+    of the stored result; run twice per shape: the second call accumulates onto the first."""
+    import os
+    R, C, T = 768, 1536, 384                      # multiples of 128, 192 and 256: every tile shape divides them
+    rng = np.random.default_rng(77)
+    Ai, Bi = rng.integers(-3, 4, size=(R, T)), rng.integers(-3, 4, size=(C, T))
+    to_bits = lambda v: synth.bf16_bits(torch.from_numpy(v.astype(np.float32)).to(torch.bfloat16))
+    A = oracle.quantize(to_bits(Ai), 1.0, 1)[0]
+    B = oracle.quantize(to_bits(Bi), 1.0, 0)[0]
+    dec_a, dec_b = oracle.decode_table(1), oracle.decode_table(0)
+    assert np.array_equal(dec_a[A], Ai.astype(np.float64)) and np.array_equal(dec_b[B], Bi.astype(np.float64))
+    y = (Ai @ Bi.T).astype(np.float64) / 2.0       # scales 4 and 0.5: de-scaling multiplies by 1 / 2
+    Ad, Bd = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    dsa, dsb = _scales(4.0, 0.5)
+    g = torch.Generator().manual_seed(11)
+    c0 = (torch.round(torch.randn((R, C), generator=g) * 160) / 4).to(torch.bfloat16)      # multiples of 1/4
+    rne = lambda v: torch.from_numpy(v).to(torch.float32).to(torch.bfloat16)     # exact in binary32, one rounding
+    want1 = rne(bf16_to_f64(c0) + y)
+    want2 = rne(bf16_to_f64(want1) + y)
+    assert np.all(np.abs(bf16_to_f64(c0) + y) < 2.0 ** 14)       # 16 bits above the quarter: the binary32 sum is exact
+    try:
+        for tile in ["4x4", "2x2", "4x3", "3x4", "3x3", "4x2", "2x4", "3x2", "2x3"]:
+            os.environ["LLMQ_GEMM_TILE"] = tile
+            c = c0.to(DEV).clone()
+            am = torch.full((1,), -1.0, dtype=torch.float32, device=DEV)
+            llmq.llmq_fp8_gemm_tn(Ad, 1, Bd, 0, dsa, dsb, c, True, am)
+            assert torch.equal(c.cpu().view(torch.int16), want1.view(torch.int16)), "tile %s, first call" % tile
+            assert am.item() == want1.float().abs().max().item(), tile
+            llmq.llmq_fp8_gemm_tn(Ad, 1, Bd, 0, dsa, dsb, c, True, am)
+            assert torch.equal(c.cpu().view(torch.int16), want2.view(torch.int16)), "tile %s, second call" % tile
+            assert am.item() == want2.float().abs().max().item(), tile
+    finally:
+        os.environ.pop("LLMQ_GEMM_TILE", None)
+
+
 @pytest.mark.parametrize("M,K,N", [(5, 7, 3), (40, 32, 24), (256, 128, 256)])
 def test_integer_inputs_give_exact_products(M, K, N):
     """Lossless inputs (small integers, absmax 7): every GEMM result is an exact small integer."""
