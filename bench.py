@@ -28,7 +28,7 @@ PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E, published
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script scaled by a plain 1 GiB copy
 # (profiles/bench_config<N>_gemm_quantize_amax.md); None where not measured.  They include hits in the
 # memory-side last-level cache: the 8 XCDs have private L2s and each re-reads the operands of its tiles.
-MEASURED_GEMM_TRAFFIC_BYTES = {2: 222.4e6, 3: 945.2e6, 4: 1076.8e6, 5: 3677.7e6}
+MEASURED_GEMM_TRAFFIC_BYTES = {2: 221.5e6, 3: 940.1e6, 4: 1070.5e6, 5: 3660.1e6}
 HEADLINE_CONFIG = 5           # the largest single-GPU configuration (32B-class block)
 SIDE_CONFIGS = (3, 4)         # 7B- and 14B-class blocks: reported in the same line
 
