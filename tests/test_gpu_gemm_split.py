@@ -103,10 +103,18 @@ def test_integer_inputs_stay_exact_when_tiles_are_shared(monkeypatch):
     A, B = vals[rng.integers(0, 5, (R, T))], vals[rng.integers(0, 5, (C, T))]
     dec = oracle.decode_table(0)
     want = torch.from_numpy(dec[A] @ dec[B].T).to(torch.bfloat16).to(torch.float64).numpy()
+    g = torch.Generator().manual_seed(8)
+    c0 = (torch.round(torch.randn((R, C), generator=g) * 160) / 4).to(torch.bfloat16)        # multiples of 1/4
+    exact = bf16_to_f64(c0) + dec[A] @ dec[B].T                 # fits binary32 exactly: one rounding is left
+    want_acc = torch.from_numpy(exact).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
     for split in ("0", "a2", "a6"):
         monkeypatch.setenv("LLMQ_GEMM_SPLIT", split)
         c, _ = _run(A, 0, False, B, 0, False, 1.0, 1.0)
         assert np.array_equal(bf16_to_f64(c), want), split
+        # the sums launch of the shared tiles with BF16 accumulation: old value + exact sum, rounded once
+        c, am = _run(A, 0, False, B, 0, False, 1.0, 1.0, accumulate=True, c_init=c0.to(DEV))
+        assert np.array_equal(bf16_to_f64(c), want_acc), split
+        assert am.item() == np.abs(want_acc).max(), split
 
 
 @pytest.mark.parametrize("cfg_i,li,which", [(4, 2, "dgrad"), (5, 0, "wgrad"), (5, 3, "wgrad")])
