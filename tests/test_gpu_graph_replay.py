@@ -1,7 +1,8 @@
-"""The library under HIP graph capture: every entry point only enqueues kernels on the stream it is given (no
-allocation, no memset, no synchronisation), so a captured sequence of calls must give, on every replay, the
-bytes the same calls give eagerly on the inputs of that moment.  Replayed several times with eager work of the
-same kernels, changed inputs and synchronisations in between."""
+"""The library under HIP graph capture and under concurrent callers: every entry point only enqueues kernels on
+the stream it is given (no allocation, no memset, no synchronisation, no state of its own but the per-GPU scratch
+of llmq_amax_static), so a captured sequence of calls must give, on every replay, the bytes the same calls give
+eagerly on the inputs of that moment (replayed several times with eager work of the same kernels, changed inputs
+and synchronisations in between), and two host threads on two streams must not disturb each other."""
 import pytest
 import torch
 
@@ -35,7 +36,7 @@ class Block:
     def outputs(self):
         return [self.res_out, self.y_norm, self.rstd, self.h, self.Y, self.dX, self.dW, self.f, self.q, self.qt, self.ws]
 
-    def run(self):
+    def run(self, with_static_scratch=True):
         f, M, K, N = self.f, self.M, self.K, self.N
         llmq.llmq_rmsnorm_fwd(self.res, self.xin, self.w_norm, 1e-6, self.res_out, self.y_norm, self.rstd, llmq.E4M3, f[0:1], f[1:2], self.ws_rn)
         llmq.llmq_swiglu_fwd(self.gu, self.h, llmq.E4M3, f[2:3], f[3:4], self.ws_sw)
@@ -46,7 +47,8 @@ class Block:
         llmq.llmq_fp8_linear_wgrad(None, None, M, N, K, f[6:7], f[3:4], llmq.E5M2, self.dW, False, self.ws,
                                    FLAGS | llmq.REUSE_X | llmq.REUSE_DY)
         llmq.llmq_amax(self.dX, llmq.E5M2, f[8:9], f[9:10], self.ws_am)
-        llmq.llmq_amax_static(self.Y, llmq.E4M3, f[10:11], f[11:12])
+        if with_static_scratch:              # one scratch array per GPU: calls that overlap on one GPU would race
+            llmq.llmq_amax_static(self.Y, llmq.E4M3, f[10:11], f[11:12])
         if M % 128 == 0 and K % 256 == 0:
             llmq.llmq_swiglu_fwd_fp8_slabs(self.gu, f[3:4], llmq.E4M3, self.q, self.qt, None)
         else:
@@ -90,3 +92,41 @@ def test_captured_calls_replay_the_eager_bytes(M, K, N):
         torch.cuda.synchronize()
         for i, (got, ref) in enumerate(zip(b.outputs(), want)):
             assert torch.equal(got.view(torch.uint8), ref.view(torch.uint8)), "replay %d, output %d differs from the eager call" % (k, i)
+
+
+def test_two_host_threads_on_two_streams():
+    """Two host threads call the library at the same time, each on its own stream with its own buffers and
+    workspaces (everything but llmq_amax_static, whose scratch is per GPU): the results are those of the same calls
+    made one after the other."""
+    import threading
+    blocks = [Block(512, 768, 1024, 21), Block(768, 512, 640, 22)]
+    want = []
+    for b in blocks:
+        b.poison()
+        b.run(with_static_scratch=False)
+        torch.cuda.synchronize()
+        want.append([t.clone() for t in b.outputs()])
+        b.poison()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    errors = []
+
+    def work(i):
+        try:
+            with torch.cuda.stream(streams[i]):
+                for _ in range(25):
+                    blocks[i].run(with_static_scratch=False)
+            streams[i].synchronize()
+        except Exception as e:           # surfaced below: an exception in a thread would otherwise be lost
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=60)
+    assert not errors, errors
+    assert not any(t.is_alive() for t in threads)
+    torch.cuda.synchronize()
+    for i, b in enumerate(blocks):
+        for j, (got, ref) in enumerate(zip(b.outputs(), want[i])):
+            assert torch.equal(got.view(torch.uint8), ref.view(torch.uint8)), "thread %d output %d" % (i, j)
