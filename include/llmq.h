@@ -17,7 +17,11 @@
  *     passed as void* (NULL = the default stream).  The library allocates nothing, frees nothing and
  *     keeps no pointer after a call returns (Section 3 "Overview": all allocation happens at start-up).
  *   - Calls only enqueue work on `stream` and return; nothing synchronises with the host.  Scales and
- *     absmax values are read from and written to device memory.
+ *     absmax values are read from and written to device memory.  The calls enqueue kernels only (no memory
+ *     set or copy commands), so a stream that is being captured into a HIP graph can take them, and replays
+ *     compute from what the buffers hold then.  Several host threads may call at the same time on streams
+ *     and buffers of their own; the one piece of state the library keeps on a GPU is the scratch array of
+ *     llmq_amax_static (see there).
  *   - BF16 and FP8 tensor pointers must be 16-byte aligned, float pointers 4-byte aligned.
  *   - Return value: LLMQ_OK or a negative llmq_status.  Argument errors are found on the host before
  *     anything is launched and leave all outputs untouched.  LLMQ_ERR_DEVICE reports a launch failure.
